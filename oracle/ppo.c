@@ -1,0 +1,533 @@
+/*
+ * ppo.c - CPU oracle for batched synchronous-pipeline plan evaluation.
+ *
+ * TEST INFRASTRUCTURE ONLY (see ppo.h).  Plain nested loops in int64, one
+ * function per step of the method, each following the passage it cites.
+ * No blocking, fusion or reordering; the only parallelism is an OpenMP loop
+ * over independent candidates.
+ */
+#include "ppo.h"
+
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define INF INT64_MAX
+#define CAP ((int64_t)1 << 62)
+
+static int g_threads = 0; /* 0 = OpenMP default */
+
+int ppo_get_num_threads(void) {
+#ifdef _OPENMP
+    return g_threads > 0 ? g_threads : omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void ppo_set_num_threads(int n) { g_threads = n > 0 ? n : 0; }
+
+static int64_t max2(int64_t a, int64_t b) { return a > b ? a : b; }
+
+/* ceil(a / b) for a >= 0, b >= 1 */
+static int64_t ceil_div(int64_t a, int64_t b) { return a / b + (a % b != 0); }
+
+/* ------------------------------------------------------------------ */
+/* Step 1: prefix sums and transfer-time tables                         */
+/* ------------------------------------------------------------------ */
+
+int ppo_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
+                     const int64_t *act_fwd_bytes, const int64_t *act_bwd_bytes,
+                     const int64_t *bw, int64_t *PF, int64_t *PB, int64_t *XF,
+                     int64_t *XB) {
+    if (L < 1 || D < 1 || !fwd_us || !bwd_us || !act_fwd_bytes || !bw || !PF ||
+        !PB || !XF || !XB)
+        return PPO_ERR_INVALID_ARG;
+    if (!act_bwd_bytes) act_bwd_bytes = act_fwd_bytes;
+    int fault = 0;
+
+    /* stage compute time = sum over its layers of p^f_l + p^b_l */
+    PF[0] = 0;
+    PB[0] = 0;
+    for (int l = 0; l < L; ++l) {
+        if (fwd_us[l] < 0 || bwd_us[l] < 0) fault |= PPO_FAULT_NEGATIVE;
+        if (fwd_us[l] >= CAP || bwd_us[l] >= CAP) fault |= PPO_FAULT_OVERFLOW;
+        /* unsigned add: wrap-around is defined; a wrapped value is a fault */
+        PF[l + 1] = (int64_t)((uint64_t)PF[l] + (uint64_t)fwd_us[l]);
+        PB[l + 1] = (int64_t)((uint64_t)PB[l] + (uint64_t)bwd_us[l]);
+        if (PF[l + 1] >= CAP || PF[l + 1] < 0 || PB[l + 1] >= CAP ||
+            PB[l + 1] < 0)
+            fault |= PPO_FAULT_OVERFLOW;
+    }
+    for (int l = 0; l + 1 < L; ++l)
+        if (act_fwd_bytes[l] < 0 || act_bwd_bytes[l] < 0)
+            fault |= PPO_FAULT_NEGATIVE;
+
+    /* c^f = d^f / b_{v,v'},  c^b = d^b / b_{v',v}  (one GPU per stage) */
+    for (int u = 0; u < D; ++u)
+        for (int v = 0; v < D; ++v) {
+            int64_t *xf = XF + ((size_t)u * D + v) * L;
+            int64_t *xb = XB + ((size_t)u * D + v) * L;
+            for (int k = 0; k < L; ++k) xf[k] = xb[k] = 0;
+            if (u == v) continue;
+            int64_t buv = bw[(size_t)u * D + v], bvu = bw[(size_t)v * D + u];
+            if (buv <= 0 || bvu <= 0) {
+                fault |= PPO_FAULT_BANDWIDTH;
+                continue;
+            }
+            for (int k = 0; k + 1 < L; ++k) {
+                if (act_fwd_bytes[k] >= 0) xf[k] = ceil_div(act_fwd_bytes[k], buv);
+                if (act_bwd_bytes[k] >= 0) xb[k] = ceil_div(act_bwd_bytes[k], bvu);
+                if (xf[k] >= CAP || xb[k] >= CAP) fault |= PPO_FAULT_OVERFLOW;
+            }
+        }
+    return fault;
+}
+
+/* ------------------------------------------------------------------ */
+/* candidate orderings                                                  */
+/* ------------------------------------------------------------------ */
+
+static int64_t factorial_or_neg(int D) {
+    int64_t f = 1;
+    for (int i = 2; i <= D; ++i) {
+        if (f > INT64_MAX / i) return -1;
+        f *= i;
+    }
+    return f;
+}
+
+/* next permutation in lexicographic order (textbook: find the longest
+ * non-increasing suffix, swap its predecessor with the next larger element
+ * of the suffix, reverse the suffix) */
+static void next_perm(int32_t *a, int n) {
+    int i = n - 2;
+    while (i >= 0 && a[i] >= a[i + 1]) --i;
+    if (i < 0) return;
+    int j = n - 1;
+    while (a[j] <= a[i]) --j;
+    int32_t t = a[i];
+    a[i] = a[j];
+    a[j] = t;
+    for (int p = i + 1, q = n - 1; p < q; ++p, --q) {
+        t = a[p];
+        a[p] = a[q];
+        a[q] = t;
+    }
+}
+
+/* all D! orderings, row c = the c-th in lexicographic order */
+static int32_t *all_orderings(int D, int64_t N) {
+    int32_t *o = (int32_t *)malloc((size_t)N * D * sizeof(int32_t));
+    if (!o) return NULL;
+    for (int i = 0; i < D; ++i) o[i] = i;
+    for (int64_t c = 1; c < N; ++c) {
+        memcpy(o + c * D, o + (c - 1) * D, (size_t)D * sizeof(int32_t));
+        next_perm(o + c * D, D);
+    }
+    return o;
+}
+
+static int check_common(int L, int D, int S, int64_t N, const int32_t *orderings) {
+    if (L < 1 || D < 1 || S < 1 || S > L || S > D || S > PPO_MAX_STAGES || N < 1)
+        return PPO_ERR_INVALID_ARG;
+    if (!orderings) {
+        if (S != D) return PPO_ERR_INVALID_ARG;
+        int64_t f = factorial_or_neg(D);
+        if (f < 0 || f != N) return PPO_ERR_INVALID_ARG;
+    }
+    return PPO_OK;
+}
+
+static int ordering_ok(const int32_t *o, int S, int D) {
+    for (int n = 0; n < S; ++n) {
+        if (o[n] < 0 || o[n] >= D) return 0;
+        for (int q = 0; q < n; ++q)
+            if (o[q] == o[n]) return 0;
+    }
+    return 1;
+}
+
+static int bounds_ok(const int32_t *e, int S, int L) {
+    int prev = 0;
+    for (int n = 0; n < S; ++n) {
+        if (e[n] <= prev) return 0;
+        prev = e[n];
+    }
+    return prev == L;
+}
+
+/* ------------------------------------------------------------------ */
+/* Step 2+3: partition DP and backtrack, one candidate                  */
+/* ------------------------------------------------------------------ */
+
+/*
+ * W[n][l] (n = xi-1 stages before the last one, first l layers) is the
+ * paper's W(l, xi, 1, xi) divided by M:
+ *   W(l, 1)  = sum_{i<=l} (p^f_i + p^b_i)
+ *   W(l, xi) = min_{1 <= l' <= l-1} max{ W(l', xi-1),
+ *                                        c^f + c^b at the cut after l',
+ *                                        sum_{l' < i <= l} (p^f_i + p^b_i) }
+ * with W = INF when l < xi (no feasible split).  The update is strict
+ * (replace only if the stored value is larger), l' ascending, so the lowest
+ * minimising l' is kept.  Wbuf: S*(L+1) int64, argbuf: S*(L+1) int32.
+ */
+static void dp_one(int L, int D, int S, const int64_t *PF, const int64_t *PB,
+                   const int64_t *XF, const int64_t *XB, const int32_t *o,
+                   int64_t *Wbuf, int32_t *argbuf, int64_t *C, int32_t *bounds) {
+    const int W1 = L + 1;
+    for (int n = 0; n < S; ++n)
+        for (int l = 0; l <= L; ++l) {
+            Wbuf[n * W1 + l] = INF;
+            argbuf[n * W1 + l] = 0;
+        }
+    for (int l = 1; l <= L; ++l) Wbuf[l] = PF[l] + PB[l];
+
+    for (int xi = 2; xi <= S; ++xi) {
+        const int n = xi - 1;
+        const size_t link = ((size_t)o[n - 1] * D + o[n]) * L;
+        for (int l = xi; l <= L; ++l) {
+            int64_t min_max_time = INF;
+            int32_t best_lp = 0;
+            for (int lp = 1; lp <= l - 1; ++lp) {
+                int64_t sub = Wbuf[(n - 1) * W1 + lp];
+                int64_t comm = XF[link + lp - 1] + XB[link + lp - 1];
+                int64_t last = (PF[l] + PB[l]) - (PF[lp] + PB[lp]);
+                int64_t max_time = max2(sub, max2(comm, last));
+                if (min_max_time > max_time) {
+                    min_max_time = max_time;
+                    best_lp = lp;
+                }
+            }
+            Wbuf[n * W1 + l] = min_max_time;
+            argbuf[n * W1 + l] = best_lp;
+        }
+    }
+    *C = Wbuf[(S - 1) * W1 + L];
+    int e = L;
+    for (int n = S - 1; n >= 0; --n) {
+        bounds[n] = e;
+        e = argbuf[n * W1 + e];
+    }
+}
+
+int ppo_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF,
+                     const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                     const int32_t *orderings, int64_t *C_out,
+                     int32_t *bounds_out) {
+    int rc = check_common(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (!PF || !PB || !XF || !XB || !C_out || !bounds_out)
+        return PPO_ERR_INVALID_ARG;
+    int32_t *own = NULL;
+    if (!orderings) {
+        own = all_orderings(D, N);
+        if (!own) return PPO_ERR_NOMEM;
+        orderings = own;
+    }
+    int fault = 0, nomem = 0;
+    int nt = ppo_get_num_threads();
+    (void)nt;
+#pragma omp parallel num_threads(nt) reduction(| : fault, nomem)
+    {
+        int64_t *Wbuf = (int64_t *)malloc((size_t)S * (L + 1) * sizeof(int64_t));
+        int32_t *argbuf = (int32_t *)malloc((size_t)S * (L + 1) * sizeof(int32_t));
+        if (!Wbuf || !argbuf) nomem = 1;
+#pragma omp for schedule(static)
+        for (int64_t c = 0; c < N; ++c) {
+            if (nomem) continue;
+            const int32_t *o = orderings + c * S;
+            if (!ordering_ok(o, S, D)) {
+                fault |= PPO_FAULT_ORDERING;
+                C_out[c] = INF;
+                for (int n = 0; n < S; ++n) bounds_out[c * S + n] = 0;
+                continue;
+            }
+            dp_one(L, D, S, PF, PB, XF, XB, o, Wbuf, argbuf, &C_out[c],
+                   bounds_out + c * S);
+        }
+        free(Wbuf);
+        free(argbuf);
+    }
+    free(own);
+    if (nomem) return PPO_ERR_NOMEM;
+    return fault;
+}
+
+/* ------------------------------------------------------------------ */
+/* Step 4: PE scheduler (Alg. 1)                                        */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Resources in pipeline order, r = 1..R, R = 2S-1: odd r = stage (r-1)/2,
+ * even r = the channel between stages r/2-1 and r/2 (one serial resource
+ * for both directions: C and W charge a channel c^f + c^b).
+ * Blocks j = 1..J, J = 4S-3 = 2R-1, in dependency order: j < R forward on
+ * resource j; j == R the merged forward+backward of the last stage; j > R
+ * backward on resource 2R-j.
+ */
+static int block_resource(int j, int R) { return j <= R ? j : 2 * R - j; }
+
+/*
+ * Execution ordering (first loop of Alg. 1).  One sweep over the block list
+ * moves at most one microbatch per block; which queues are non-empty is
+ * looked up at the start of the sweep, so a microbatch advances one block
+ * per sweep (the paper's cycle example: in the second cycle only F of
+ * microbatch 2 and the forward transfer of microbatch 1 run).  U[r] receives
+ * the (microbatch, block) pairs of resource r in the order they are drawn;
+ * channels follow the same list order as stages.
+ * Returns the number of sweeps.  handled, if not NULL, gets per sweep the
+ * microbatch handled by each block (0 = none), capacity max_rounds sweeps.
+ */
+typedef struct {
+    int32_t m, j;
+} pe_item;
+
+static int pe_order(int S, int M, pe_item **U, int *Ulen, int32_t *handled,
+                    int max_rounds) {
+    const int R = 2 * S - 1, J = 2 * R - 1;
+    /* Q[j] holds microbatch ids; each queue sees every microbatch once */
+    int32_t *Q = (int32_t *)malloc((size_t)(J + 2) * M * sizeof(int32_t));
+    int *head = (int *)calloc((size_t)J + 2, sizeof(int));
+    int *tail = (int *)calloc((size_t)J + 2, sizeof(int));
+    char *nonempty = (char *)malloc((size_t)J + 2);
+    if (!Q || !head || !tail || !nonempty) {
+        free(Q); free(head); free(tail); free(nonempty);
+        return PPO_ERR_NOMEM;
+    }
+    for (int m = 1; m <= M; ++m) Q[1 * M + tail[1]++] = m;
+    for (int r = 1; r <= R; ++r) Ulen[r] = 0;
+
+    int rounds = 0;
+    for (;;) {
+        int any = 0;
+        for (int j = 1; j <= J; ++j) {
+            nonempty[j] = head[j] < tail[j];
+            any |= nonempty[j];
+        }
+        if (!any) break;
+        for (int j = 1; j <= J; ++j) {
+            int32_t got = 0;
+            if (nonempty[j]) {
+                int32_t m = Q[j * M + head[j]++];
+                if (j < J) Q[(j + 1) * M + tail[j + 1]++] = m;
+                int r = block_resource(j, R);
+                U[r][Ulen[r]].m = m;
+                U[r][Ulen[r]].j = j;
+                Ulen[r]++;
+                got = m;
+            }
+            if (handled && rounds < max_rounds) handled[(size_t)rounds * J + j - 1] = got;
+        }
+        ++rounds;
+    }
+    free(Q); free(head); free(tail); free(nonempty);
+    return rounds;
+}
+
+int ppo_execution_order(int S, int M, int32_t *rounds_out, int max_rounds) {
+    if (S < 1 || S > PPO_MAX_STAGES || M < 1 || !rounds_out || max_rounds < 1)
+        return PPO_ERR_INVALID_ARG;
+    const int R = 2 * S - 1;
+    pe_item **U = (pe_item **)calloc((size_t)R + 1, sizeof(pe_item *));
+    int *Ulen = (int *)calloc((size_t)R + 1, sizeof(int));
+    if (!U || !Ulen) { free(U); free(Ulen); return PPO_ERR_NOMEM; }
+    int ok = 1;
+    for (int r = 1; r <= R; ++r) {
+        U[r] = (pe_item *)malloc((size_t)2 * M * sizeof(pe_item));
+        if (!U[r]) ok = 0;
+    }
+    int rounds = ok ? pe_order(S, M, U, Ulen, rounds_out, max_rounds) : PPO_ERR_NOMEM;
+    for (int r = 1; r <= R; ++r) free(U[r]);
+    free(U);
+    free(Ulen);
+    return rounds;
+}
+
+/*
+ * Scheduling (second loop of Alg. 1): every resource works through its list
+ * U[r] in order and starts the head item as soon as its microbatch has left
+ * the preceding block and the resource is idle; e^f of microbatch 1 on stage
+ * 1 is 0.  Returns max_m (e^b_{m,s_1} + backward time of stage 1), the first
+ * term of the makespan objective (nothing is replicated, so there is no
+ * AllReduce term).
+ */
+int64_t ppo_pe_makespan(int S, int M, const int64_t *F, const int64_t *B,
+                        const int64_t *cf, const int64_t *cb,
+                        int64_t *start_out, int64_t *finish_out) {
+    if (S < 1 || S > PPO_MAX_STAGES || M < 1 || !F || !B) return -1;
+    if (S > 1 && (!cf || !cb)) return -1;
+    const int R = 2 * S - 1, J = 2 * R - 1;
+    int64_t *dur = (int64_t *)malloc((size_t)(J + 1) * sizeof(int64_t));
+    int64_t *done = (int64_t *)malloc((size_t)(J + 1) * (M + 1) * sizeof(int64_t));
+    int64_t *idle_at = (int64_t *)calloc((size_t)R + 1, sizeof(int64_t));
+    int *next = (int *)calloc((size_t)R + 1, sizeof(int));
+    int *Ulen = (int *)calloc((size_t)R + 1, sizeof(int));
+    pe_item **U = (pe_item **)calloc((size_t)R + 1, sizeof(pe_item *));
+    int64_t T = -1;
+    if (!dur || !done || !idle_at || !next || !Ulen || !U) goto out;
+    for (int r = 1; r <= R; ++r) {
+        U[r] = (pe_item *)malloc((size_t)2 * M * sizeof(pe_item));
+        if (!U[r]) goto out;
+    }
+    /* block durations */
+    for (int j = 1; j <= J; ++j) {
+        int r = block_resource(j, R);
+        int is_stage = r & 1;
+        int n = is_stage ? (r - 1) / 2 : r / 2; /* stage index or channel index */
+        if (j == R)
+            dur[j] = F[S - 1] + B[S - 1];
+        else if (j < R)
+            dur[j] = is_stage ? F[n] : cf[n];
+        else
+            dur[j] = is_stage ? B[n] : cb[n];
+    }
+    if (pe_order(S, M, U, Ulen, NULL, 0) < 0) goto out;
+
+    for (size_t i = 0; i < (size_t)(J + 1) * (M + 1); ++i) done[i] = -1;
+    for (;;) {
+        int progress = 0, remaining = 0;
+        for (int r = 1; r <= R; ++r) {
+            while (next[r] < Ulen[r]) {
+                pe_item it = U[r][next[r]];
+                int64_t ready = 0;
+                if (it.j > 1) {
+                    ready = done[(size_t)(it.j - 1) * (M + 1) + it.m];
+                    if (ready < 0) break; /* predecessor block not finished */
+                }
+                int64_t start = max2(idle_at[r], ready);
+                int64_t fin = start + dur[it.j];
+                done[(size_t)it.j * (M + 1) + it.m] = fin;
+                idle_at[r] = fin;
+                if (start_out) start_out[(size_t)(it.j - 1) * M + it.m - 1] = start;
+                if (finish_out) finish_out[(size_t)(it.j - 1) * M + it.m - 1] = fin;
+                next[r]++;
+                progress = 1;
+            }
+            remaining |= next[r] < Ulen[r];
+        }
+        if (!remaining) break;
+        if (!progress) goto out; /* cannot happen: the lists are consistent */
+    }
+    T = 0;
+    for (int m = 1; m <= M; ++m) T = max2(T, done[(size_t)J * (M + 1) + m]);
+out:
+    if (U)
+        for (int r = 1; r <= R; ++r) free(U[r]);
+    free(U); free(Ulen); free(next); free(idle_at); free(done); free(dur);
+    return T;
+}
+
+/* durations of one plan from the tables; returns fault bits */
+static int plan_durations(int L, int D, int S, int M, const int64_t *PF,
+                          const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                          const int32_t *o, const int32_t *e, int64_t *F,
+                          int64_t *B, int64_t *cf, int64_t *cb) {
+    int64_t worst = 0;
+    for (int n = 0; n < S; ++n) {
+        int lo = n ? e[n - 1] : 0, hi = e[n];
+        F[n] = PF[hi] - PF[lo];
+        B[n] = PB[hi] - PB[lo];
+        worst = max2(worst, F[n] + B[n]);
+        cf[n] = cb[n] = 0;
+        if (n) {
+            size_t at = ((size_t)o[n - 1] * D + o[n]) * L + (size_t)(lo - 1);
+            cf[n] = XF[at];
+            cb[n] = XB[at];
+            worst = max2(worst, cf[n] + cb[n]);
+        }
+    }
+    /* the schedule is no longer than (M + 4S - 4) * C (Lemma 1) */
+    if (worst > (CAP - 1) / ((int64_t)M + 4 * S - 4)) return PPO_FAULT_OVERFLOW;
+    return 0;
+}
+
+int ppo_schedule_makespan(int L, int D, int S, int64_t N, int M,
+                          const int64_t *PF, const int64_t *PB,
+                          const int64_t *XF, const int64_t *XB,
+                          const int32_t *orderings, const int32_t *bounds,
+                          int64_t *T_out) {
+    int rc = check_common(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out)
+        return PPO_ERR_INVALID_ARG;
+    int32_t *own = NULL;
+    if (!orderings) {
+        own = all_orderings(D, N);
+        if (!own) return PPO_ERR_NOMEM;
+        orderings = own;
+    }
+    int fault = 0, nomem = 0;
+    int nt = ppo_get_num_threads();
+    (void)nt;
+#pragma omp parallel for schedule(static) num_threads(nt) reduction(| : fault, nomem)
+    for (int64_t c = 0; c < N; ++c) {
+        const int32_t *o = orderings + c * S, *e = bounds + c * S;
+        int64_t F[PPO_MAX_STAGES], B[PPO_MAX_STAGES], cf[PPO_MAX_STAGES],
+            cb[PPO_MAX_STAGES];
+        T_out[c] = INF;
+        if (!ordering_ok(o, S, D)) { fault |= PPO_FAULT_ORDERING; continue; }
+        if (!bounds_ok(e, S, L)) { fault |= PPO_FAULT_BOUNDS; continue; }
+        int f = plan_durations(L, D, S, M, PF, PB, XF, XB, o, e, F, B, cf, cb);
+        if (f) { fault |= f; continue; }
+        int64_t T = ppo_pe_makespan(S, M, F, B, cf, cb, NULL, NULL);
+        if (T < 0) { nomem = 1; continue; }
+        T_out[c] = T;
+    }
+    free(own);
+    if (nomem) return PPO_ERR_NOMEM;
+    return fault;
+}
+
+/* ------------------------------------------------------------------ */
+/* Step 5: keep the candidate with the smallest makespan                */
+/* ------------------------------------------------------------------ */
+
+int ppo_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                  const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                  const int32_t *orderings, ppo_result *out, int64_t *T_all,
+                  int64_t *C_all) {
+    int rc = check_common(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !out) return PPO_ERR_INVALID_ARG;
+    int32_t *own = NULL;
+    if (!orderings) {
+        own = all_orderings(D, N);
+        if (!own) return PPO_ERR_NOMEM;
+        orderings = own;
+    }
+    int64_t *T = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+    int64_t *C = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+    int32_t *bounds = (int32_t *)malloc((size_t)N * S * sizeof(int32_t));
+    int fault = PPO_ERR_NOMEM;
+    if (T && C && bounds) {
+        fault = ppo_partition_dp(L, D, S, N, PF, PB, XF, XB, orderings, C, bounds);
+        if (fault == 0)
+            fault = ppo_schedule_makespan(L, D, S, N, M, PF, PB, XF, XB,
+                                          orderings, bounds, T);
+    }
+    if (fault == 0) {
+        /* T_SPP <- T_PE only if T_PE < T_SPP, candidates in index order */
+        int64_t T_best = INF, best = -1;
+        for (int64_t c = 0; c < N; ++c)
+            if (T[c] < T_best) {
+                T_best = T[c];
+                best = c;
+            }
+        memset(out, 0, sizeof(*out));
+        out->best_index = best;
+        out->S = S;
+        out->T = T_best;
+        out->C = best >= 0 ? C[best] : INF;
+        for (int n = 0; n < S && best >= 0; ++n) {
+            out->bounds[n] = bounds[best * S + n];
+            out->order[n] = orderings[best * S + n];
+        }
+        if (T_all) memcpy(T_all, T, (size_t)N * sizeof(int64_t));
+        if (C_all) memcpy(C_all, C, (size_t)N * sizeof(int64_t));
+    }
+    free(T); free(C); free(bounds); free(own);
+    return fault;
+}

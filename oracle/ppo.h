@@ -1,0 +1,115 @@
+/*
+ * ppo.h - CPU oracle for batched synchronous-pipeline plan evaluation.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, obviously-correct host
+ * implementation written from the paper (arXiv 2204.10562).  It exists so
+ * that the GPU library can be checked against it; it shares no code, header,
+ * table or helper with the GPU path, and the product never calls it.
+ *
+ * Everything is integer (int64 microseconds, bytes, bytes per microsecond),
+ * so the results are exact.  All pointers are HOST pointers.
+ *
+ * Conventions (0-based, half-open):
+ *   layers 0..L-1;  PF[l] = sum_{i<l} fwd[i], PB likewise, P = PF + PB.
+ *   boundary k (1 <= k <= L-1) = the cut between layer k-1 and layer k; it
+ *     carries act_fwd[k-1] bytes forward and act_bwd[k-1] bytes backward.
+ *   XF[(u*D+v)*L + (k-1)] = ceil(act_fwd[k-1] / bw[u*D+v])   (u -> v, forward)
+ *   XB[(u*D+v)*L + (k-1)] = ceil(act_bwd[k-1] / bw[v*D+u])   (v -> u, backward)
+ *     entry L-1 of every row and every diagonal row (u == v) is 0.
+ *   candidate c = ordering o_c[0..S-1] of distinct devices; stage n runs on
+ *     o_c[n].  A plan = end-exclusive bounds e[0] < e[1] < ... < e[S-1] = L.
+ *
+ * Pins (tests/, marker "not gpu"): brute force over all contiguous
+ * partitions and all orderings on tiny inputs; the paper's cycle example
+ * (Sec. IV-A, proof of Lemma 1: M = 6, two stages, 10 cycles); hand-worked
+ * two-stage schedules; the bounds M*C <= T <= (M + 4S - 4)*C of Lemma 1;
+ * closed forms for S = 1, S = L, M = 1; an independent event-driven
+ * simulator.  Parity with the authors' own (unreleased) planner: unpinned.
+ */
+#ifndef PPO_H
+#define PPO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PPO_OK 0
+#define PPO_ERR_INVALID_ARG (-1)
+#define PPO_ERR_NOMEM (-2)
+
+/* data faults: returned as a positive OR of these bits; outputs are then
+ * unspecified. */
+#define PPO_FAULT_BANDWIDTH 1 /* off-diagonal bandwidth <= 0               */
+#define PPO_FAULT_NEGATIVE 2  /* negative time or size                     */
+#define PPO_FAULT_ORDERING 4  /* ordering row not distinct devices in [0,D)*/
+#define PPO_FAULT_BOUNDS 8    /* bounds not strictly increasing to L       */
+#define PPO_FAULT_OVERFLOW 16 /* a value reached 2^62                      */
+
+#define PPO_MAX_STAGES 64
+
+typedef struct {
+    int64_t best_index; /* lowest c attaining the minimum T; -1 if none */
+    int64_t T;          /* per-iteration time of that plan              */
+    int64_t C;          /* its per-microbatch bottleneck                */
+    int32_t S;
+    int32_t bounds[PPO_MAX_STAGES];
+    int32_t order[PPO_MAX_STAGES];
+} ppo_result;
+
+/* Stage compute time is the sum of per-layer forward+backward times
+ * (Lemma 1, definition of C); transfer time is size / bandwidth with one
+ * GPU per stage (Sec. III-B, c^f and c^b), rounded up per direction. */
+int ppo_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
+                     const int64_t *act_fwd_bytes, const int64_t *act_bwd_bytes,
+                     const int64_t *bw_bytes_per_us, int64_t *PF, int64_t *PB,
+                     int64_t *XF, int64_t *XB);
+
+/* Min-max partition of L layers into S contiguous stages along one device
+ * ordering: recursion for W(l, xi, r, i) in Sec. IV-B / the PRM listing in
+ * the appendix, with one replica per stage (r = r' = 1, AllReduce term 0),
+ * and the factor M divided out.  orderings == NULL means all D! orderings
+ * in lexicographic order (requires S == D, N == D!). */
+int ppo_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF,
+                     const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                     const int32_t *orderings, int64_t *C_out,
+                     int32_t *bounds_out);
+
+/* Per-iteration time of given plans under the PE scheduler (Alg. 1). */
+int ppo_schedule_makespan(int L, int D, int S, int64_t N, int M,
+                          const int64_t *PF, const int64_t *PB,
+                          const int64_t *XF, const int64_t *XB,
+                          const int32_t *orderings, const int32_t *bounds,
+                          int64_t *T_out);
+
+/* DP plan per candidate, its makespan, and the keep-the-minimum of the SPP
+ * listing (Alg. 3, strict '<' while scanning candidates in order). */
+int ppo_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                  const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                  const int32_t *orderings, ppo_result *out, int64_t *T_all,
+                  int64_t *C_all);
+
+/* Execution-ordering phase of Alg. 1 alone, for a pipeline of S stages and
+ * M microbatches.  rounds_out[t*(4S-3) + (j-1)] = microbatch (1-based) that
+ * block j handles in sweep t, or 0.  Returns the number of sweeps, or a
+ * negative error; max_rounds is the capacity of rounds_out in sweeps. */
+int ppo_execution_order(int S, int M, int32_t *rounds_out, int max_rounds);
+
+/* Makespan of one pipeline given directly by its durations (no tables):
+ * F[n], B[n] for stages 0..S-1; cf[n], cb[n] for channel n (between stage
+ * n-1 and n), entries 1..S-1 used.  start_out/finish_out, if not NULL, get
+ * the start/finish time of block j (1-based) for microbatch m (1-based) at
+ * [(j-1)*M + (m-1)]. */
+int64_t ppo_pe_makespan(int S, int M, const int64_t *F, const int64_t *B,
+                        const int64_t *cf, const int64_t *cb,
+                        int64_t *start_out, int64_t *finish_out);
+
+/* threads the candidate loops use (OpenMP), and a setter */
+int ppo_get_num_threads(void);
+void ppo_set_num_threads(int n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,128 @@
+"""Independent reference pieces used to pin the oracle (pure Python, tiny inputs).
+
+Nothing here is shared with oracle/ or with the GPU path: the partition
+optimum is found by enumerating every contiguous partition, and the schedule
+by a heap-driven discrete-event simulation whose per-resource order comes from
+the closed form 'block j serves microbatch m in sweep m + j - 1'.
+"""
+import heapq
+import itertools
+
+
+def stage_costs(P, X, cuts, L):
+    """Per-resource per-microbatch times of the partition with the given cuts.
+    P: prefix of fwd+bwd (len L+1); X[n][k] = channel n (1-based) cost at cut k."""
+    edges = [0] + list(cuts) + [L]
+    comp = [P[edges[i + 1]] - P[edges[i]] for i in range(len(edges) - 1)]
+    chan = [X[n][edges[n]] for n in range(1, len(edges) - 1)]
+    return comp, chan
+
+
+def brute_optimum(P, X, S, l):
+    """min over all partitions of layers [0,l) into S non-empty contiguous stages of the
+    largest per-stage / per-channel time; X[n][k] as above for channels 1..S-1."""
+    best = None
+    for cuts in itertools.combinations(range(1, l), S - 1):
+        comp, chan = stage_costs(P, X, cuts, l)
+        w = max(comp + chan)
+        if best is None or w < best:
+            best = w
+    return best
+
+
+def brute_plan(P, X, S, L):
+    """The tie-broken plan: the last cut is the smallest k for which the optimum of the
+    first k layers in S-1 stages, the channel at k and the last stage [k,L) together reach
+    the optimum; then the same rule on the prefix with its own optimum."""
+    bounds = [L]
+    l = L
+    for n in range(S - 1, 0, -1):
+        target = brute_optimum(P, X, n + 1, l)
+        for k in range(n, l):
+            w = max(brute_optimum(P, X, n, k), X[n][k], P[l] - P[k])
+            if w == target:
+                bounds.append(k)
+                l = k
+                break
+        else:
+            raise AssertionError("no split reaches the optimum")
+    return list(reversed(bounds))
+
+
+def channel_table(XF, XB, D, L, order):
+    """X[n][k] for n = 1..S-1 along an ordering, from flat tables indexed (u*D+v)*L + k-1."""
+    X = [None]
+    for n in range(1, len(order)):
+        u, v = int(order[n - 1]), int(order[n])
+        base = (u * D + v) * L
+        X.append([None] + [int(XF[base + k - 1]) + int(XB[base + k - 1]) for k in range(1, L)])
+    return X
+
+
+def event_sim(F, B, cf, cb, M):
+    """Discrete-event simulation of a flushed synchronous pipeline.
+    Resources r = 1..R (odd: stages, even: channels); blocks j = 1..2R-1.
+    Returns (T, start[j][m]) with 1-based j and m in dicts."""
+    S = len(F)
+    R = 2 * S - 1
+    J = 2 * R - 1
+
+    def res(j):
+        return j if j <= R else 2 * R - j
+
+    def dur(j):
+        r = res(j)
+        n = (r - 1) // 2 if r % 2 else r // 2
+        if j == R:
+            return F[S - 1] + B[S - 1]
+        if r % 2:
+            return F[n] if j < R else B[n]
+        return cf[n] if j < R else cb[n]
+
+    # service order per resource: sweep t = m + j - 1 ascending, then block ascending
+    order = {r: [] for r in range(1, R + 1)}
+    for j in range(1, J + 1):
+        for m in range(1, M + 1):
+            order[res(j)].append((m + j - 1, j, m))
+    for r in order:
+        order[r].sort()
+    pos = {r: 0 for r in order}
+    busy_until = {r: None for r in order}     # None = idle
+    done = {}
+    start = {}
+    now = 0
+    events = []  # (finish time, resource, j, m)
+
+    def try_start(r):
+        if busy_until[r] is not None or pos[r] >= len(order[r]):
+            return
+        _, j, m = order[r][pos[r]]
+        if j > 1 and (j - 1, m) not in done:
+            return
+        start[(j, m)] = now
+        busy_until[r] = now + dur(j)
+        heapq.heappush(events, (now + dur(j), r, j, m))
+        pos[r] += 1
+
+    try_start(1)
+    while events:
+        now = events[0][0]
+        # retire everything finishing now, then let every idle resource look at its head;
+        # zero-length work finishes at the same instant, so repeat until nothing moves
+        while True:
+            moved = False
+            while events and events[0][0] == now:
+                _, r, j, m = heapq.heappop(events)
+                done[(j, m)] = now
+                busy_until[r] = None
+                moved = True
+            before = len(start)
+            for r in order:
+                try_start(r)
+            if len(start) != before:
+                moved = True
+            if not moved:
+                break
+    assert len(done) == J * M, "simulation stalled"
+    T = max(done[(J, m)] for m in range(1, M + 1))
+    return T, start
