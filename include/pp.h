@@ -1,0 +1,165 @@
+/*
+ * pp.h - batched evaluation of synchronous-pipeline plans on one MI355X.
+ *
+ * C ABI of libpp (hand-written HIP kernels for gfx950).  The library is the
+ * data-parallel hot path of the planner of arXiv 2204.10562: for a batch of
+ * candidate device orderings it partitions the L layers of a model into
+ * contiguous stages with a min-max dynamic program, computes every plan's
+ * per-iteration time for M microbatches under the paper's pipeline execution
+ * scheduler, and keeps the best plan.
+ *
+ * General rules
+ *   - Every array pointer is a DEVICE pointer unless marked "host".  The
+ *     caller owns all buffers; the library allocates nothing, keeps no state
+ *     between calls and never synchronises.  All work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream)
+ *     and the outputs are valid once that stream has reached the call's end.
+ *   - Times are int64 microseconds, sizes int64 bytes, bandwidth int64 bytes
+ *     per microsecond (1 GB/s = 1000).  Everything is exact integer work.
+ *   - Layers 0..L-1.  PF[l] = sum_{i<l} fwd[i], PB likewise (length L+1).
+ *     Boundary k (1 <= k <= L-1) is the cut between layers k-1 and k.
+ *     XF[(u*D+v)*L + (k-1)] is the forward transfer time over the link u->v
+ *     at boundary k, XB[(u*D+v)*L + (k-1)] the backward one (over v->u).
+ *   - A candidate c is a row o_c[0..S-1] of distinct devices: stage n runs on
+ *     device o_c[n].  A plan is its end-exclusive stage bounds
+ *     e[0] < e[1] < ... < e[S-1] = L (stage n = layers [e[n-1], e[n])).
+ *   - Return value: PP_OK, or a negative PP_ERR_* for a problem the host can
+ *     see (then nothing was enqueued).  Problems in the data can only be seen
+ *     on the device: they are OR-ed (atomically) as PP_FAULT_* bits into the
+ *     caller's int32 `*status` (device memory, cleared by the caller).  When
+ *     a call sets a fault bit its outputs are unspecified, but no kernel
+ *     reads or writes out of bounds because of bad data.
+ *   - Limits: 1 <= S <= min(L, D, PP_MAX_STAGES); L <= PP_MAX_LAYERS;
+ *     D <= PP_MAX_DEVICES; M >= 1; N >= 1.
+ */
+#ifndef PP_H
+#define PP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PP_OK 0
+#define PP_ERR_INVALID_ARG (-1) /* NULL required pointer, size out of range  */
+#define PP_ERR_WORKSPACE (-2)   /* workspace NULL, misaligned or too small   */
+#define PP_ERR_HIP (-3)         /* a kernel launch failed                    */
+
+#define PP_FAULT_BANDWIDTH 1 /* an off-diagonal bandwidth is <= 0            */
+#define PP_FAULT_NEGATIVE 2  /* a negative time or size                      */
+#define PP_FAULT_ORDERING 4  /* an ordering row is not distinct devices<D    */
+#define PP_FAULT_BOUNDS 8    /* bounds not strictly increasing up to L       */
+#define PP_FAULT_OVERFLOW 16 /* a value reached 2^62                         */
+
+#define PP_MAX_STAGES 64
+#define PP_MAX_LAYERS 2048
+#define PP_MAX_DEVICES 1024
+
+/* Winner record written by pp_best_plan (device memory, 536 bytes). */
+typedef struct {
+    int64_t best_index; /* lowest candidate index with the minimum T       */
+    int64_t T;          /* its per-iteration time (us)                     */
+    int64_t C;          /* its per-microbatch bottleneck (us); W = M * C   */
+    int32_t S;
+    int32_t bounds[PP_MAX_STAGES]; /* entries 0..S-1                       */
+    int32_t order[PP_MAX_STAGES];  /* entries 0..S-1                       */
+} pp_result;
+
+/*
+ * Cost tables, once per problem.
+ * Stage compute time is the sum of its layers' forward+backward times
+ * (Lemma 1, definition of C), hence the prefix sums.  Transfer time between
+ * consecutive stages is size / bandwidth of the link that joins their GPUs
+ * (Sec. III-B, c^f over b_{v,v'} and c^b over b_{v',v}, one GPU per stage),
+ * here ceil(bytes / bw) per direction.
+ *   fwd_us, bwd_us        [L]   per-layer per-microbatch times
+ *   act_fwd_bytes         [L]   bytes sent forward across the boundary after
+ *                               layer l; entry L-1 is ignored
+ *   act_bwd_bytes         [L]   bytes sent backward across it; NULL = same
+ *                               as act_fwd_bytes
+ *   bw_bytes_per_us       [D*D] bw[u*D+v] = bandwidth u -> v; diagonal ignored
+ *   PF, PB                [L+1] out
+ *   XF, XB                [D*D*L] out; entry L-1 of each row and the
+ *                               diagonal rows are 0
+ * Faults: BANDWIDTH, NEGATIVE, OVERFLOW.
+ */
+int pp_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
+                    const int64_t *act_fwd_bytes, const int64_t *act_bwd_bytes,
+                    const int64_t *bw_bytes_per_us, int64_t *PF, int64_t *PB,
+                    int64_t *XF, int64_t *XB, int32_t *status, void *stream);
+
+/*
+ * Bytes of device workspace pp_partition_dp and pp_best_plan need for a
+ * problem of this size (host function; 0 if the sizes are out of range).
+ * The workspace must be 256-byte aligned; its contents need not be kept
+ * between calls.
+ */
+size_t pp_workspace_bytes(int L, int D, int S, int64_t N);
+
+/*
+ * Min-max partition along every candidate ordering.
+ * Recursion for W(l, xi, r, i) of Sec. IV-B and the PRM listing (appendix)
+ * with one replica per stage (r = r' = 1, AllReduce term 0) and the common
+ * factor M divided out:
+ *   W[0][l] = P[l],   P = PF + PB
+ *   W[n][l] = min_{n <= k <= l-1} max( W[n-1][k],
+ *                                      XF[o[n-1]][o[n]][k-1] + XB[..][k-1],
+ *                                      P[l] - P[k] )
+ * The lowest minimising k is kept (strict-improvement update with k
+ * ascending), and the plan is read back from (S-1, L).
+ *   orderings   [N*S] int32, or NULL = all D! orderings in lexicographic
+ *               order, candidate index = lexicographic rank (needs S == D,
+ *               N == D!)
+ *   C_out       [N]   per-microbatch bottleneck W[S-1][L] of each candidate
+ *   bounds_out  [N*S] its plan
+ * Faults: ORDERING.
+ */
+int pp_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF,
+                    const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                    const int32_t *orderings, int64_t *C_out,
+                    int32_t *bounds_out, void *workspace,
+                    size_t workspace_bytes, int32_t *status, void *stream);
+
+/*
+ * Per-iteration time of given plans (any valid bounds, not only the DP's)
+ * under the pipeline execution scheduler (Alg. 1, Sec. IV-A): 2S-1 serial
+ * resources (stages and, between them, one channel for both directions);
+ * 4S-3 blocks per microbatch (the last stage's forward and backward are one
+ * block); block j serves microbatch t-j+1 in sweep t; every resource serves
+ * its work in (sweep, block) order, each item starting once its microbatch
+ * has left the preceding block and the resource is idle.  T is the finish of
+ * the last backward block on stage 0 (first term of the makespan objective,
+ * Eq. 2; nothing is replicated).
+ *   bounds  [N*S]   T_out  [N]
+ * Faults: ORDERING, BOUNDS, OVERFLOW ((M+4S-4) * largest block >= 2^62).
+ */
+int pp_schedule_makespan(int L, int D, int S, int64_t N, int M,
+                         const int64_t *PF, const int64_t *PB,
+                         const int64_t *XF, const int64_t *XB,
+                         const int32_t *orderings, const int32_t *bounds,
+                         int64_t *T_out, int32_t *status, void *stream);
+
+/*
+ * The whole path: partition DP per candidate, makespan of each plan, and the
+ * keep-the-minimum of the SPP listing (Alg. 3: replace only on strictly
+ * smaller T while scanning candidates in index order, so the lowest index
+ * wins ties).
+ *   out     one pp_result
+ *   T_all   [N] or NULL     C_all  [N] or NULL
+ * Faults: ORDERING, OVERFLOW.
+ */
+int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                 const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                 const int32_t *orderings, pp_result *out, int64_t *T_all,
+                 int64_t *C_all, void *workspace, size_t workspace_bytes,
+                 int32_t *status, void *stream);
+
+/* Text for a PP_ERR_* code (host function, static storage). */
+const char *pp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

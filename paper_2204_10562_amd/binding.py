@@ -1,0 +1,153 @@
+"""Thin Python binding of libpp (include/pp.h): argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks dtype, device
+and contiguity, and passes raw pointers plus the current HIP stream to the C entry
+point of the same name.  No step of the method runs in Python and there is no CPU
+fallback: if libpp.so is missing the import of the library fails loudly.
+"""
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+PP_OK = 0
+PP_ERR_INVALID_ARG = -1
+PP_ERR_WORKSPACE = -2
+PP_ERR_HIP = -3
+PP_FAULT_BANDWIDTH = 1
+PP_FAULT_NEGATIVE = 2
+PP_FAULT_ORDERING = 4
+PP_FAULT_BOUNDS = 8
+PP_FAULT_OVERFLOW = 16
+PP_MAX_STAGES = 64
+
+EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
+           "pp_best_plan", "pp_strerror")
+
+
+class PPResult(ctypes.Structure):
+    _fields_ = [
+        ("best_index", ctypes.c_int64),
+        ("T", ctypes.c_int64),
+        ("C", ctypes.c_int64),
+        ("S", ctypes.c_int32),
+        ("bounds", ctypes.c_int32 * PP_MAX_STAGES),
+        ("order", ctypes.c_int32 * PP_MAX_STAGES),
+    ]
+
+
+RESULT_BYTES = ctypes.sizeof(PPResult)
+_lib = None
+
+
+class PPError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__("libpp: %s (%d)" % (lib().pp_strerror(code).decode(), code))
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpp.so is not built (%s); run __graft_entry__.build() or "
+                               "python -m paper_2204_10562_amd.build" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        L.pp_prefix_costs.argtypes = [i32, i32] + [vp] * 9 + [vp, vp]
+        L.pp_prefix_costs.restype = i32
+        L.pp_workspace_bytes.argtypes = [i32, i32, i32, i64]
+        L.pp_workspace_bytes.restype = sz
+        L.pp_partition_dp.argtypes = [i32, i32, i32, i64] + [vp] * 7 + [vp, sz, vp, vp]
+        L.pp_partition_dp.restype = i32
+        L.pp_schedule_makespan.argtypes = [i32, i32, i32, i64, i32] + [vp] * 7 + [vp, vp]
+        L.pp_schedule_makespan.restype = i32
+        L.pp_best_plan.argtypes = [i32, i32, i32, i64, i32] + [vp] * 8 + [vp, sz, vp, vp]
+        L.pp_best_plan.restype = i32
+        L.pp_strerror.argtypes = [i32]
+        L.pp_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t, dtype, numel=None, name="tensor", optional=False):
+    if t is None:
+        if optional:
+            return None
+        raise ValueError(name + " is required")
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous %s tensor on the GPU" % (name, dtype))
+    if numel is not None and t.numel() < numel:
+        raise ValueError("%s has %d elements, needs %d" % (name, t.numel(), numel))
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc):
+    if rc != PP_OK:
+        raise PPError(rc)
+
+
+def pp_workspace_bytes(L, D, S, N):
+    return int(lib().pp_workspace_bytes(L, D, S, N))
+
+
+def pp_prefix_costs(L, D, fwd_us, bwd_us, act_fwd_bytes, act_bwd_bytes, bw_bytes_per_us,
+                    PF, PB, XF, XB, status):
+    i64 = torch.int64
+    _check(lib().pp_prefix_costs(
+        L, D, _ptr(fwd_us, i64, L, "fwd_us"), _ptr(bwd_us, i64, L, "bwd_us"),
+        _ptr(act_fwd_bytes, i64, L, "act_fwd_bytes"),
+        _ptr(act_bwd_bytes, i64, L, "act_bwd_bytes", optional=True),
+        _ptr(bw_bytes_per_us, i64, D * D, "bw_bytes_per_us"),
+        _ptr(PF, i64, L + 1, "PF"), _ptr(PB, i64, L + 1, "PB"),
+        _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(status, torch.int32, 1, "status"), _stream()))
+
+
+def pp_partition_dp(L, D, S, N, PF, PB, XF, XB, orderings, C_out, bounds_out, workspace, status):
+    i64, i32 = torch.int64, torch.int32
+    _check(lib().pp_partition_dp(
+        L, D, S, N, _ptr(PF, i64, L + 1, "PF"), _ptr(PB, i64, L + 1, "PB"),
+        _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(C_out, i64, N, "C_out"), _ptr(bounds_out, i32, N * S, "bounds_out"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+def pp_schedule_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out, status):
+    i64, i32 = torch.int64, torch.int32
+    _check(lib().pp_schedule_makespan(
+        L, D, S, N, M, _ptr(PF, i64, L + 1, "PF"), _ptr(PB, i64, L + 1, "PB"),
+        _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(bounds, i32, N * S, "bounds"), _ptr(T_out, i64, N, "T_out"),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+def pp_best_plan(L, D, S, N, M, PF, PB, XF, XB, orderings, out, T_all, C_all, workspace, status):
+    i64, i32 = torch.int64, torch.int32
+    _check(lib().pp_best_plan(
+        L, D, S, N, M, _ptr(PF, i64, L + 1, "PF"), _ptr(PB, i64, L + 1, "PB"),
+        _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(out, torch.uint8, RESULT_BYTES, "out"),
+        _ptr(T_all, i64, N, "T_all", optional=True), _ptr(C_all, i64, N, "C_all", optional=True),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+def read_result(out, S):
+    """Copy a device pp_result (uint8 tensor) to the host and unpack it."""
+    raw = bytes(out.cpu().numpy().tobytes()[:RESULT_BYTES])
+    r = PPResult.from_buffer_copy(raw)
+    return dict(best_index=int(r.best_index), T=int(r.T), C=int(r.C), S=int(r.S),
+                bounds=[int(r.bounds[i]) for i in range(S)],
+                order=[int(r.order[i]) for i in range(S)])

@@ -1,0 +1,93 @@
+// Entry points of libpp that only check arguments and enqueue kernels.
+#include "pp_common.h"
+
+static bool factorial_is(int D, int64_t N) {
+    int64_t f = 1;
+    for (int i = 2; i <= D; ++i) {
+        if (f > INT64_MAX / i) return false;
+        f *= i;
+    }
+    return f == N;
+}
+
+int pp_check_sizes(int L, int D, int S, int64_t N, const int32_t *orderings) {
+    if (L < 1 || L > PP_MAX_LAYERS || D < 1 || D > PP_MAX_DEVICES) return PP_ERR_INVALID_ARG;
+    if (S < 1 || S > L || S > D || S > PP_MAX_STAGES || N < 1) return PP_ERR_INVALID_ARG;
+    if (!orderings && (S != D || D > 20 || !factorial_is(D, N))) return PP_ERR_INVALID_ARG;
+    return PP_OK;
+}
+
+extern "C" size_t pp_workspace_bytes(int L, int D, int S, int64_t N) {
+    if (L < 1 || L > PP_MAX_LAYERS || D < 1 || D > PP_MAX_DEVICES) return 0;
+    if (S < 1 || S > L || S > D || S > PP_MAX_STAGES || N < 1) return 0;
+    return pp_layout(L, D, S, N).total;
+}
+
+static int check_ws(const void *ws, size_t bytes, const pp_ws_layout &lay) {
+    if (!ws || ((uintptr_t)ws & 255) || bytes < lay.total) return PP_ERR_WORKSPACE;
+    return PP_OK;
+}
+
+extern "C" int pp_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF,
+                               const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                               const int32_t *orderings, int64_t *C_out, int32_t *bounds_out,
+                               void *workspace, size_t workspace_bytes, int32_t *status,
+                               void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (!PF || !PB || !XF || !XB || !C_out || !bounds_out) return PP_ERR_INVALID_ARG;
+    pp_ws_layout lay = pp_layout(L, D, S, N);
+    rc = check_ws(workspace, workspace_bytes, lay);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    rc = pp_launch_pack(L, D, PF, PB, XF, XB, workspace, lay, st);
+    if (rc) return rc;
+    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings, C_out, bounds_out, workspace, lay,
+                        status, st);
+}
+
+extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                                    const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                                    const int32_t *orderings, const int32_t *bounds,
+                                    int64_t *T_out, int32_t *status, void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
+    return pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out, status,
+                              (hipStream_t)stream);
+}
+
+extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                            const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                            const int32_t *orderings, pp_result *out, int64_t *T_all,
+                            int64_t *C_all, void *workspace, size_t workspace_bytes,
+                            int32_t *status, void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !out) return PP_ERR_INVALID_ARG;
+    pp_ws_layout lay = pp_layout(L, D, S, N);
+    rc = check_ws(workspace, workspace_bytes, lay);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    int64_t *C = C_all ? C_all : (int64_t *)(base + lay.C);
+    int64_t *T = T_all ? T_all : (int64_t *)(base + lay.T);
+    int32_t *bounds = (int32_t *)(base + lay.bounds);
+    rc = pp_launch_pack(L, D, PF, PB, XF, XB, workspace, lay, st);
+    if (rc) return rc;
+    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings, C, bounds, workspace, lay, status, st);
+    if (rc) return rc;
+    rc = pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T, status, st);
+    if (rc) return rc;
+    return pp_launch_argmin(D, S, N, T, C, bounds, orderings, base + lay.part, out, st);
+}
+
+extern "C" const char *pp_strerror(int code) {
+    switch (code) {
+        case PP_OK: return "ok";
+        case PP_ERR_INVALID_ARG: return "invalid argument (NULL required pointer or size out of range)";
+        case PP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PP_ERR_HIP: return "kernel launch failed";
+        default: return "unknown error code";
+    }
+}

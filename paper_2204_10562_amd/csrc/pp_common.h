@@ -1,0 +1,93 @@
+// Shared declarations of the GPU library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pp.h"
+
+#define PP_INF64 INT64_MAX
+#define PP_INF32 0x7fffffff
+#define PP_CAP62 ((long long)1 << 62)
+
+static inline size_t pp_align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Number of key bits that hold a split index 0..L-1.
+static inline int pp_index_bits(int L) {
+    int K = 1;
+    while ((1 << K) < L) ++K;
+    return K;
+}
+
+// Header at the start of the workspace, filled by the pack kernels.
+struct pp_ws_header {
+    unsigned long long vmax;  // largest per-microbatch time any cell can take: max(P[L], max XF+XB)
+    int pad[62];
+};
+
+// Workspace carving, identical for pp_partition_dp and pp_best_plan.
+struct pp_ws_layout {
+    size_t hdr, p32, x32, arg, bounds, C, T, part, total;
+    int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
+};
+
+#define PP_ARGMIN_PARTS 1024
+#define PP_DP_SLOTS 2048
+
+static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
+    pp_ws_layout w;
+    size_t off = 0;
+    w.hdr = off;    off += pp_align256(sizeof(pp_ws_header));
+    w.p32 = off;    off += pp_align256((size_t)(L + 1) * 4);
+    w.x32 = off;    off += pp_align256((size_t)D * D * L * 4);
+    w.slots = (int)(N < PP_DP_SLOTS ? N : PP_DP_SLOTS);
+    w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 1) * 2);
+    w.bounds = off; off += pp_align256((size_t)N * S * 4);
+    w.C = off;      off += pp_align256((size_t)N * 8);
+    w.T = off;      off += pp_align256((size_t)N * 8);
+    w.part = off;   off += pp_align256((size_t)PP_ARGMIN_PARTS * 16);
+    w.total = off;
+    return w;
+}
+
+// Host-side checks shared by the entry points; returns PP_OK or PP_ERR_INVALID_ARG.
+int pp_check_sizes(int L, int D, int S, int64_t N, const int32_t *orderings);
+
+// Enqueue helpers implemented next to their kernels (all return PP_OK / PP_ERR_HIP).
+int pp_launch_pack(int L, int D, const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                   const int64_t *XB, void *ws, const pp_ws_layout &lay, hipStream_t st);
+int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
+                 const int64_t *XF, const int64_t *XB, const int32_t *orderings, int64_t *C_out,
+                 int32_t *bounds_out, void *ws, const pp_ws_layout &lay, int32_t *status,
+                 hipStream_t st);
+int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
+                       const int64_t *XF, const int64_t *XB, const int32_t *orderings,
+                       const int32_t *bounds, int64_t *T_out, int32_t *status, hipStream_t st);
+int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
+                     const int32_t *bounds, const int32_t *orderings, void *part, pp_result *out,
+                     hipStream_t st);
+
+__device__ __forceinline__ void pp_raise(int32_t *status, int bit) {
+    if (status) atomicOr(status, bit);
+}
+
+// Device o[n] of the candidate with lexicographic rank c among all D! orderings
+// (factorial number system: digit n = floor(c / (D-1-n)!) mod (D-n) selects the
+// digit-th smallest device not used by o[0..n-1]).  Walk n = 0, 1, ... in order with
+// `rem` starting at c and `used` at 0.
+__device__ __forceinline__ int pp_unrank_next(int D, int n, unsigned long long &rem,
+                                              unsigned &used) {
+    unsigned long long f = 1;
+    for (int i = 2; i <= D - 1 - n; ++i) f *= (unsigned long long)i;
+    int digit = (int)(rem / f);
+    rem -= (unsigned long long)digit * f;
+    int dev = 0;
+    for (int d = 0; d < D; ++d) {
+        if (!((used >> d) & 1u)) {
+            if (digit == 0) { dev = d; break; }
+            --digit;
+        }
+    }
+    used |= 1u << dev;
+    return dev;
+}

@@ -1,0 +1,80 @@
+"""Uploads a workload, runs libpp through the Python binding, downloads results."""
+import numpy as np
+import torch
+
+from paper_2204_10562_amd import binding as pp
+
+
+class GpuProblem:
+    def __init__(self, w, device="cuda:0"):
+        self.w = w
+        self.dev = torch.device(device)
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+        self.fwd, self.bwd = t(w.fwd), t(w.bwd)
+        self.actf, self.actb = t(w.actf), t(w.actb)
+        self.bw = t(w.bw.reshape(-1))
+        self.orderings = None if w.orderings is None else t(w.orderings.reshape(-1))
+        L, D = w.L, w.D
+        self.PF = torch.empty(L + 1, dtype=torch.int64, device=self.dev)
+        self.PB = torch.empty(L + 1, dtype=torch.int64, device=self.dev)
+        self.XF = torch.empty(D * D * L, dtype=torch.int64, device=self.dev)
+        self.XB = torch.empty(D * D * L, dtype=torch.int64, device=self.dev)
+        self.status = torch.zeros(1, dtype=torch.int32, device=self.dev)
+        self.ws = None
+
+    def workspace(self, N=None, S=None):
+        w = self.w
+        need = pp.pp_workspace_bytes(w.L, w.D, S or w.S, N or w.N)
+        assert need > 0
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        assert self.ws.data_ptr() % 256 == 0
+        return self.ws
+
+    def take_status(self):
+        s = int(self.status.item())
+        self.status.zero_()
+        return s
+
+    def prefix(self, actb_none=False):
+        w = self.w
+        pp.pp_prefix_costs(w.L, w.D, self.fwd, self.bwd, self.actf, None if actb_none else self.actb,
+                           self.bw, self.PF, self.PB, self.XF, self.XB, self.status)
+        return self.take_status()
+
+    def set_tables(self, PF, PB, XF, XB):
+        for dst, src in ((self.PF, PF), (self.PB, PB), (self.XF, XF), (self.XB, XB)):
+            dst.copy_(torch.from_numpy(np.ascontiguousarray(src)))
+
+    def dp(self, orderings="default", N=None, S=None):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        C = torch.empty(N, dtype=torch.int64, device=self.dev)
+        bounds = torch.empty(N * S, dtype=torch.int32, device=self.dev)
+        pp.pp_partition_dp(w.L, w.D, S, N, self.PF, self.PB, self.XF, self.XB, o, C, bounds,
+                           self.workspace(N, S), self.status)
+        return self.take_status(), C.cpu().numpy(), bounds.cpu().numpy().reshape(N, S)
+
+    def makespan(self, M, bounds, orderings="default", N=None, S=None):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        b = torch.from_numpy(np.ascontiguousarray(bounds, dtype=np.int32).reshape(-1)).to(self.dev)
+        T = torch.empty(N, dtype=torch.int64, device=self.dev)
+        pp.pp_schedule_makespan(w.L, w.D, S, N, M, self.PF, self.PB, self.XF, self.XB, o, b, T,
+                                self.status)
+        return self.take_status(), T.cpu().numpy()
+
+    def best(self, M, orderings="default", N=None, S=None, want_all=True):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        out = torch.zeros(pp.RESULT_BYTES, dtype=torch.uint8, device=self.dev)
+        T = torch.empty(N, dtype=torch.int64, device=self.dev) if want_all else None
+        C = torch.empty(N, dtype=torch.int64, device=self.dev) if want_all else None
+        pp.pp_best_plan(w.L, w.D, S, N, M, self.PF, self.PB, self.XF, self.XB, o, out, T, C,
+                        self.workspace(N, S), self.status)
+        res = pp.read_result(out, S)
+        return (self.take_status(), res, None if T is None else T.cpu().numpy(),
+                None if C is None else C.cpu().numpy())

@@ -1,0 +1,347 @@
+"""Bit-exact parity of the HIP path (through the C ABI) with the CPU oracle."""
+import itertools
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2204_10562_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from gpu_harness import GpuProblem
+    return GpuProblem
+
+
+def oracle_tables(ppo, w):
+    rc, PF, PB, XF, XB = ppo.prefix_costs(w.fwd, w.bwd, w.actf, w.actb, w.bw)
+    assert rc == 0
+    return PF, PB, XF, XB
+
+
+def sub_workload(w, idx):
+    """The same problem restricted to the candidates in idx (explicit orderings)."""
+    import copy
+    v = copy.copy(w)
+    v.orderings = np.ascontiguousarray(w.explicit_orderings()[idx])
+    v.N = len(idx)
+    return v
+
+
+# ------------------------------------------------------------------ prefix / tables
+
+@pytest.mark.parametrize("name", ["tiny", "transformer", "gpt", "hetero", "stress"])
+def test_prefix_costs_configs(ppo, G, name):
+    w = workloads.CONFIGS[name](N=64) if name in ("hetero", "stress") else workloads.CONFIGS[name]()
+    say("prefix_costs", name, "L", w.L, "D", w.D)
+    g = G(w)
+    assert g.prefix() == 0
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    np.testing.assert_array_equal(g.PF.cpu().numpy(), PF)
+    np.testing.assert_array_equal(g.PB.cpu().numpy(), PB)
+    np.testing.assert_array_equal(g.XF.cpu().numpy(), XF)
+    np.testing.assert_array_equal(g.XB.cpu().numpy(), XB)
+
+
+@pytest.mark.parametrize("seed,L,D", [(1, 1, 1), (2, 2, 2), (3, 257, 3), (4, 700, 5), (5, 2048, 2), (6, 63, 9)])
+def test_prefix_costs_ragged(ppo, G, seed, L, D):
+    w = workloads.random_small(seed, L, D, 1, 1, zero_frac=0.1, hi_time=10 ** 6, hi_act=10 ** 9)
+    say("prefix_costs ragged", seed, L, D)
+    g = G(w)
+    assert g.prefix() == 0
+    rc, PF, PB, XF, XB = ppo.prefix_costs(w.fwd, w.bwd, w.actf, w.actb, w.bw)
+    assert rc == 0
+    for a, b in ((g.PF, PF), (g.PB, PB), (g.XF, XF), (g.XB, XB)):
+        np.testing.assert_array_equal(a.cpu().numpy(), b)
+    # act_bwd = NULL means "same as forward"
+    assert g.prefix(actb_none=True) == 0
+    rc, PF, PB, XF, XB = ppo.prefix_costs(w.fwd, w.bwd, w.actf, None, w.bw)
+    np.testing.assert_array_equal(g.XB.cpu().numpy(), XB)
+
+
+def test_prefix_costs_faults(ppo, G):
+    base = workloads.random_small(9, 300, 3, 1, 1)
+    cases = []
+    a = base.bw.copy(); a[0, 2] = 0; cases.append(("bw0", dict(bw=a)))
+    a = base.bw.copy(); a[2, 1] = -5; cases.append(("bwneg", dict(bw=a)))
+    a = base.fwd.copy(); a[299] = -1; cases.append(("fwdneg", dict(fwd=a)))
+    a = base.actf.copy(); a[17] = -1; cases.append(("actneg", dict(actf=a)))
+    a = base.actf.copy(); a[299] = -1; cases.append(("act_last_ignored", dict(actf=a)))
+    a = base.bwd.copy(); a[5] = 1 << 61; a[280] = 1 << 61; cases.append(("overflow", dict(bwd=a)))
+    a = base.bw.copy(); a[1, 1] = -9; cases.append(("diag_ignored", dict(bw=a)))
+    import copy
+    for name, kw in cases:
+        w = copy.copy(base)
+        for k, v in kw.items():
+            setattr(w, k, v)
+        say("prefix fault", name)
+        want = ppo.prefix_costs(w.fwd, w.bwd, w.actf, w.actb, w.bw)[0]
+        assert G(w).prefix() == want, name
+
+
+# ------------------------------------------------------------------ partition DP
+
+def check_dp(ppo, g, w, tables=None, gpu_tables=False):
+    PF, PB, XF, XB = tables if tables is not None else oracle_tables(ppo, w)
+    if not gpu_tables:
+        g.set_tables(PF, PB, XF, XB)
+    st, C, bounds = g.dp()
+    rc, C0, b0 = ppo.partition_dp(w.L, w.D, w.S, w.N, PF, PB, XF, XB, w.orderings)
+    assert rc == 0 and st == 0
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(bounds, b0)
+    return C0, b0
+
+
+@pytest.mark.parametrize("name", ["tiny", "transformer", "gpt"])
+def test_dp_full_configs(ppo, G, name):
+    w = workloads.CONFIGS[name]()
+    say("partition_dp", name, "N", w.N)
+    g = G(w)
+    assert g.prefix() == 0
+    check_dp(ppo, g, w, gpu_tables=True)
+
+
+def test_dp_explicit_orderings_equal_default(ppo, G):
+    w = workloads.transformer()
+    say("partition_dp explicit-vs-default transformer")
+    g = G(w)
+    g.prefix()
+    st, C, b = g.dp()
+    import torch
+    o = torch.from_numpy(workloads.all_orderings(w.D).reshape(-1)).to(g.dev)
+    st2, C2, b2 = g.dp(orderings=o)
+    assert st == 0 and st2 == 0
+    np.testing.assert_array_equal(C, C2)
+    np.testing.assert_array_equal(b, b2)
+
+
+@pytest.mark.parametrize("name,N", [("hetero", 3000), ("stress", 600)])
+def test_dp_large_shapes_subset(ppo, G, name, N):
+    w = workloads.CONFIGS[name](N=N)
+    say("partition_dp", name, "N", N)
+    g = G(w)
+    assert g.prefix() == 0
+    check_dp(ppo, g, w, gpu_tables=True)
+
+
+SMALL = [  # seed, L, D, S, N
+    (101, 1, 1, 1, 3), (102, 2, 2, 2, 5), (103, 5, 3, 1, 7), (104, 7, 7, 7, 50), (105, 9, 4, 3, 70),
+    (106, 33, 5, 5, 130), (107, 64, 6, 4, 65), (108, 65, 6, 6, 64), (109, 127, 8, 8, 100),
+    (110, 128, 9, 8, 129), (111, 129, 8, 8, 100), (112, 200, 12, 12, 90), (113, 257, 16, 16, 70),
+    (114, 300, 20, 3, 40), (115, 513, 33, 33, 30), (116, 1000, 64, 64, 12), (117, 16, 16, 16, 200),
+]
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL)
+def test_dp_adversarial_small(ppo, G, seed, L, D, S, N):
+    # narrow ranges (ties everywhere), zero-length layers, asymmetric links, S < D
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500)
+    say("partition_dp small", seed, L, D, S, N)
+    g = G(w)
+    check_dp(ppo, g, w)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N,shift", [(201, 40, 4, 4, 50, 26), (202, 130, 5, 5, 40, 40), (203, 300, 6, 3, 30, 50)])
+def test_dp_wide_values(ppo, G, seed, L, D, S, N, shift):
+    # times too large for 32-bit keys: the int64 representation must give the same answers
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1, hi_time=9, hi_act=300)
+    w.fwd = w.fwd << shift
+    w.bwd = w.bwd << shift
+    w.actf = w.actf << (shift - 3)
+    w.actb = w.actb << (shift - 3)
+    say("partition_dp wide", seed, L, D, S, N, shift)
+    g = G(w)
+    check_dp(ppo, g, w)
+
+
+def test_dp_key_range_boundary(ppo, G):
+    # total time just below / at / above the 32-bit key limit 2^(31-K) - 1
+    L, D, S, N = 16, 3, 3, 6
+    K = 4
+    limit = (1 << (31 - K)) - 1
+    for total in (limit - 1, limit, limit + 1):
+        w = workloads.random_small(301, L, D, S, N)
+        w.fwd[:] = 0
+        w.bwd[:] = 1
+        w.bwd[0] = total - (L - 1)
+        say("partition_dp boundary", total)
+        g = G(w)
+        check_dp(ppo, g, w)
+
+
+def test_dp_bad_orderings_fault(ppo, G):
+    w = workloads.random_small(401, 20, 5, 4, 64)
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    for mutate in ("dup", "range", "neg"):
+        v = sub_workload(w, np.arange(w.N))
+        if mutate == "dup":
+            v.orderings[13, 2] = v.orderings[13, 0]
+        elif mutate == "range":
+            v.orderings[63, 3] = 5
+        else:
+            v.orderings[0, 0] = -1
+        say("partition_dp fault", mutate)
+        g = G(v)
+        g.set_tables(PF, PB, XF, XB)
+        st, C, b = g.dp()
+        rc, C0, b0 = ppo.partition_dp(v.L, v.D, v.S, v.N, PF, PB, XF, XB, v.orderings)
+        assert st == rc == ppo.FAULT_ORDERING
+
+
+# ------------------------------------------------------------------ makespan
+
+def random_bounds(rng, N, S, L):
+    b = np.empty((N, S), np.int32)
+    for c in range(N):
+        cuts = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False)) if S > 1 else []
+        b[c, :S - 1] = cuts
+        b[c, S - 1] = L
+    return b
+
+
+@pytest.mark.parametrize("name", ["tiny", "transformer", "gpt"])
+def test_makespan_full_configs(ppo, G, name):
+    w = workloads.CONFIGS[name]()
+    g = G(w)
+    assert g.prefix() == 0
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    rc, C0, b0 = ppo.partition_dp(w.L, w.D, w.S, w.N, PF, PB, XF, XB, None)
+    for M in w.Ms:
+        say("makespan", name, "M", M)
+        st, T = g.makespan(M, b0)
+        rc, T0 = ppo.schedule_makespan(w.L, w.D, w.S, w.N, M, PF, PB, XF, XB, None, b0)
+        assert st == 0 and rc == 0
+        np.testing.assert_array_equal(T, T0)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL)
+def test_makespan_any_valid_plan(ppo, G, seed, L, D, S, N):
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    b = random_bounds(rng, N, S, L)
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(PF, PB, XF, XB)
+    for M in (1, 2, 5, 13):
+        say("makespan small", seed, L, D, S, N, "M", M)
+        st, T = g.makespan(M, b)
+        rc, T0 = ppo.schedule_makespan(L, D, S, N, M, PF, PB, XF, XB, w.orderings, b)
+        assert st == 0 and rc == 0
+        np.testing.assert_array_equal(T, T0)
+
+
+@pytest.mark.parametrize("name,N,M", [("hetero", 500, 32), ("stress", 200, 128)])
+def test_makespan_large_shapes_subset(ppo, G, name, N, M):
+    w = workloads.CONFIGS[name](N=N)
+    rng = np.random.Generator(np.random.PCG64(5))
+    b = random_bounds(rng, N, w.S, w.L)
+    g = G(w)
+    assert g.prefix() == 0
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    say("makespan", name, N, M)
+    st, T = g.makespan(M, b)
+    rc, T0 = ppo.schedule_makespan(w.L, w.D, w.S, N, M, PF, PB, XF, XB, w.orderings, b)
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(T, T0)
+
+
+def test_makespan_faults(ppo, G):
+    w = workloads.random_small(501, 20, 5, 4, 40)
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    rng = np.random.Generator(np.random.PCG64(1))
+    good = random_bounds(rng, w.N, w.S, w.L)
+    g = G(w)
+    g.set_tables(PF, PB, XF, XB)
+    for name, row in (("zero", [0, 5, 9, 20]), ("equal", [5, 5, 9, 20]), ("short", [3, 5, 9, 19]),
+                      ("long", [3, 5, 9, 21]), ("huge", [3, 5, 1 << 20, 20]), ("desc", [9, 5, 3, 20])):
+        b = good.copy()
+        b[7] = row
+        say("makespan fault", name)
+        st, T = g.makespan(3, b)
+        rc, T0 = ppo.schedule_makespan(w.L, w.D, w.S, w.N, 3, PF, PB, XF, XB, w.orderings, b)
+        assert st == rc == ppo.FAULT_BOUNDS, name
+    # overflow guard: (M + 4S - 4) * largest block >= 2^62
+    PF2 = PF.copy(); PF2[1:] += 1 << 55
+    g.set_tables(PF2, PB, XF, XB)
+    for M, want in ((2, 0), (200, ppo.FAULT_OVERFLOW)):
+        say("makespan overflow", M)
+        st, T = g.makespan(M, good)
+        rc, T0 = ppo.schedule_makespan(w.L, w.D, w.S, w.N, M, PF2, PB, XF, XB, w.orderings, good)
+        assert st == rc == want
+        if want == 0:
+            np.testing.assert_array_equal(T, T0)
+
+
+# ------------------------------------------------------------------ whole path
+
+def check_best(ppo, g, w, M, tables):
+    PF, PB, XF, XB = tables
+    st, res, T, C = g.best(M)
+    rc, res0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, M, PF, PB, XF, XB, w.orderings)
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(T, T0)
+    np.testing.assert_array_equal(C, C0)
+    assert res == res0
+    # optional outputs may be omitted
+    st, res2, _, _ = g.best(M, want_all=False)
+    assert st == 0 and res2 == res0
+
+
+@pytest.mark.parametrize("name", ["tiny", "transformer", "gpt"])
+def test_best_plan_full_configs(ppo, G, name):
+    w = workloads.CONFIGS[name]()
+    g = G(w)
+    assert g.prefix() == 0
+    tables = oracle_tables(ppo, w)
+    for M in w.Ms:
+        say("best_plan", name, "M", M)
+        check_best(ppo, g, w, M, tables)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL)
+def test_best_plan_adversarial_small(ppo, G, seed, L, D, S, N):
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    for M in (1, 4):
+        say("best_plan small", seed, L, D, S, N, "M", M)
+        check_best(ppo, g, w, M, tables)
+
+
+def test_best_plan_ties_lowest_index(ppo, G):
+    w = workloads.tiny()
+    w.bw = np.full((4, 4), 16000, np.int64)
+    say("best_plan ties")
+    g = G(w)
+    assert g.prefix() == 0
+    tables = oracle_tables(ppo, w)
+    st, res, T, C = g.best(8)
+    assert (T == T[0]).all() and res["best_index"] == 0 and res["order"] == [0, 1, 2, 3]
+    check_best(ppo, g, w, 8, tables)
+    # duplicated candidates: the first copy wins
+    v = sub_workload(w, np.array([5, 3, 5, 3, 0, 0]))
+    g = G(v)
+    g.set_tables(*tables)
+    check_best(ppo, g, v, 4, tables)
+
+
+@pytest.mark.parametrize("name,N", [("hetero", 2000), ("stress", 300)])
+def test_best_plan_large_shapes_subset(ppo, G, name, N):
+    w = workloads.CONFIGS[name](N=N)
+    g = G(w)
+    assert g.prefix() == 0
+    tables = oracle_tables(ppo, w)
+    say("best_plan", name, N)
+    check_best(ppo, g, w, w.Ms[-1], tables)
