@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched pipeline-plan evaluator on one MI355X.
+
+One step = one pass of the whole hot path over the GPT-shaped workload (L=128, D=S=8,
+all 40320 device orderings): pp_prefix_costs once, then pp_best_plan (partition DP,
+max-plus makespan, candidate arg-min) for every microbatch count of the workload
+(M = 8, 16, 32, 64).  A "plan evaluated" is one (candidate, M) pair taken through the
+DP, the backtrack and the schedule.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line on stdout; details go to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+# published MI355X figures: 256 compute units x 4 SIMDs x 16 lanes at 2.4 GHz, one 32-bit
+# integer operation per lane per clock
+ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9
+OPS_PER_PAIR = 3  # subtract, max, min on 32-bit keys per (cell, split) pair
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="gpt", choices=["tiny", "transformer", "gpt", "hetero", "stress"])
+    ap.add_argument("--candidates", type=int, default=0, help="override N for the sampled workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+                 "use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from gpu_harness import GpuProblem
+    from paper_2204_10562_amd import binding as pp
+    from paper_2204_10562_amd import workloads
+
+    make = workloads.CONFIGS[args.workload]
+    w = make(N=args.candidates) if (args.candidates and args.workload in ("hetero", "stress")) else make()
+    g = GpuProblem(w)
+    L, D, S, N, Ms = w.L, w.D, w.S, w.N, w.Ms
+    dev = g.dev
+    ws = g.workspace()
+    out = torch.zeros(pp.RESULT_BYTES, dtype=torch.uint8, device=dev)
+    C = torch.empty(N, dtype=torch.int64, device=dev)
+    T = torch.empty(N, dtype=torch.int64, device=dev)
+    bounds = torch.empty(N * S, dtype=torch.int32, device=dev)
+    pairs = workloads.pair_evals_per_candidate(L, S) * N
+
+    def step():
+        pp.pp_prefix_costs(L, D, g.fwd, g.bwd, g.actf, g.actb, g.bw, g.PF, g.PB, g.XF, g.XB, g.status)
+        for M in Ms:
+            pp.pp_best_plan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert int(g.status.item()) == 0, "a data fault was raised"
+    ms_per_step = wall / args.steps * 1e3
+    plans_per_s = N * len(Ms) * args.steps / wall
+    winner = pp.read_result(out, S)
+
+    # per-entry-point durations with HIP events on the stream the kernels run on
+    def timed(fn, reps):
+        for _ in range(max(3, reps // 10)):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3  # seconds per call
+
+    reps = max(10, args.steps)
+    t_dp = timed(lambda: pp.pp_partition_dp(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C, bounds, ws, g.status), reps)
+    t_prefix = timed(lambda: pp.pp_prefix_costs(L, D, g.fwd, g.bwd, g.actf, g.actb, g.bw, g.PF, g.PB, g.XF, g.XB, g.status), reps)
+    t_mk = {M: timed(lambda M=M: pp.pp_schedule_makespan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, bounds, T, g.status), reps) for M in Ms}
+    t_best = {M: timed(lambda M=M: pp.pp_best_plan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status), reps) for M in Ms}
+    assert int(g.status.item()) == 0
+
+    achieved = OPS_PER_PAIR * pairs / t_dp
+    log("workload %s: L=%d D=S=%d N=%d M=%s" % (w.name, L, D, N, list(Ms)))
+    log("  pp_prefix_costs        %9.1f us" % (t_prefix * 1e6))
+    log("  pp_partition_dp        %9.1f us   %.3e pair-evals/s  %.3e cells/s  %.1f%% of int32 VALU peak"
+        % (t_dp * 1e6, pairs / t_dp, N * S * L / t_dp, 100 * achieved / ALU_PEAK_OPS))
+    for M in Ms:
+        log("  pp_schedule_makespan M=%-3d %7.1f us   %.3e block-ops/s" % (M, t_mk[M] * 1e6, N * M * (4 * S - 3) / t_mk[M]))
+    for M in Ms:
+        log("  pp_best_plan M=%-3d      %9.1f us   %.3e plans/s" % (M, t_best[M] * 1e6, N / t_best[M]))
+    log("  whole step             %9.1f us   %.3e plans/s" % (ms_per_step * 1e3, plans_per_s))
+    log("  winner:", winner)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ppo
+        ppo.build()
+        import numpy as np
+        rc, PF, PB, XF, XB = ppo.prefix_costs(w.fwd, w.bwd, w.actf, w.actb, w.bw)
+        # bounded sample: at most ~2^31 pair-evals per M (a few seconds on a handful of cores)
+        n_cpu = min(N, max(1, (1 << 31) // workloads.pair_evals_per_candidate(L, S)))
+        o_cpu = None if (w.orderings is None and n_cpu == N) else np.ascontiguousarray(w.explicit_orderings()[:n_cpu])
+        t0 = time.perf_counter()
+        for M in Ms:
+            rc, res0, T0, C0 = ppo.best_plan(L, D, S, n_cpu, M, PF, PB, XF, XB, o_cpu, want_all=False)
+        cpu_wall = time.perf_counter() - t0
+        if n_cpu == N:
+            assert res0 == winner, "GPU and oracle disagree on the best plan: %r vs %r" % (winner, res0)
+        cpu = {"value": n_cpu * len(Ms) / cpu_wall, "unit": "plans/s", "cores": ppo.get_num_threads(),
+               "kind": "oracle",
+               "sample": "first %d of %d candidates of the %s workload, all %d microbatch counts, %.1f s wall"
+                         % (n_cpu, N, w.name, len(Ms), cpu_wall)}
+        log("  oracle on %d host threads: %.3e plans/s (%s)" % (cpu["cores"], cpu["value"], cpu["sample"]))
+
+    line = {
+        "metric": "candidate plans evaluated/sec (partition DP + makespan + argmin), L=%d, D=%d" % (L, D),
+        "value": plans_per_s, "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "%s: L=%d, D=S=%d, N=%d orderings, M=%s" % (w.name, L, D, N, list(Ms)),
+                   "plans_per_step": N * len(Ms)},
+        "dp_cells_per_s": N * S * L / t_dp, "dp_pair_evals_per_s": pairs / t_dp,
+        "roofline": {"bound": "alu", "kernel": "pp_partition_dp", "achieved": achieved / 1e12,
+                     "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s (32-bit integer lane-ops)",
+                     "frac": achieved / ALU_PEAK_OPS, "traffic": None,
+                     "launch_us": t_dp * 1e6, "pair_evals_per_launch": pairs, "ops_per_pair": OPS_PER_PAIR},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -40,10 +40,11 @@ extern "C" int pp_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF
     rc = check_ws(workspace, workspace_bytes, lay);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    rc = pp_launch_pack(L, D, PF, PB, XF, XB, workspace, lay, st);
+    const int32_t *ord = NULL;
+    rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings, C_out, bounds_out, workspace, lay,
-                        status, st);
+    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, C_out,
+                        bounds_out, workspace, lay, status, st);
 }
 
 extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
@@ -73,13 +74,15 @@ extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t
     int64_t *C = C_all ? C_all : (int64_t *)(base + lay.C);
     int64_t *T = T_all ? T_all : (int64_t *)(base + lay.T);
     int32_t *bounds = (int32_t *)(base + lay.bounds);
-    rc = pp_launch_pack(L, D, PF, PB, XF, XB, workspace, lay, st);
+    const int32_t *ord = NULL;
+    rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings, C, bounds, workspace, lay, status, st);
+    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, C, bounds,
+                      workspace, lay, status, st);
     if (rc) return rc;
-    rc = pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T, status, st);
+    rc = pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, ord, bounds, T, status, st);
     if (rc) return rc;
-    return pp_launch_argmin(D, S, N, T, C, bounds, orderings, base + lay.part, out, st);
+    return pp_launch_argmin(D, S, N, T, C, bounds, ord, base + lay.part, out, st);
 }
 
 extern "C" const char *pp_strerror(int code) {

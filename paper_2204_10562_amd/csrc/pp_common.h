@@ -27,19 +27,24 @@ struct pp_ws_header {
 
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.
 struct pp_ws_layout {
-    size_t hdr, p32, x32, arg, bounds, C, T, part, total;
+    size_t hdr, p32, x32, xkt, ord, arg, bounds, C, T, part, total;
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
+    int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
 
 #define PP_ARGMIN_PARTS 1024
+#define PP_TILE_MAX_L 128
 #define PP_DP_SLOTS 2048
 
 static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     pp_ws_layout w;
     size_t off = 0;
     w.hdr = off;    off += pp_align256(sizeof(pp_ws_header));
-    w.p32 = off;    off += pp_align256((size_t)(L + 1) * 4);
+    w.nt = L <= PP_TILE_MAX_L ? (L + 7) / 8 : 0;
+    w.p32 = off;    off += pp_align256((size_t)(L + 17) * 4);  // padded to a whole tile
     w.x32 = off;    off += pp_align256((size_t)D * D * L * 4);
+    w.xkt = off;    off += pp_align256((size_t)D * D * 8 * w.nt * 4);
+    w.ord = off;    off += pp_align256((size_t)N * S * 4);
     w.slots = (int)(N < PP_DP_SLOTS ? N : PP_DP_SLOTS);
     w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 1) * 2);
     w.bounds = off; off += pp_align256((size_t)N * S * 4);
@@ -54,12 +59,17 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
 int pp_check_sizes(int L, int D, int S, int64_t N, const int32_t *orderings);
 
 // Enqueue helpers implemented next to their kernels (all return PP_OK / PP_ERR_HIP).
-int pp_launch_pack(int L, int D, const int64_t *PF, const int64_t *PB, const int64_t *XF,
-                   const int64_t *XB, void *ws, const pp_ws_layout &lay, hipStream_t st);
+// Fills the workspace tables (and, for orderings == NULL, the explicit list of all D!
+// orderings); returns in *ord the ordering array the later kernels must read.
+int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
+                   const int64_t *XF, const int64_t *XB, const int32_t *orderings, void *ws,
+                   const pp_ws_layout &lay, const int32_t **ord, hipStream_t st);
+// Exactly one of lex_ord (the library's own list of all D! orderings, known to be valid and
+// lexicographic) and user_ord (the caller's list, to be validated) is non-NULL.
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
-                 const int64_t *XF, const int64_t *XB, const int32_t *orderings, int64_t *C_out,
-                 int32_t *bounds_out, void *ws, const pp_ws_layout &lay, int32_t *status,
-                 hipStream_t st);
+                 const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
+                 const int32_t *user_ord, int64_t *C_out, int32_t *bounds_out, void *ws,
+                 const pp_ws_layout &lay, int32_t *status, hipStream_t st);
 int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
                        const int64_t *XF, const int64_t *XB, const int32_t *orderings,
                        const int32_t *bounds, int64_t *T_out, int32_t *status, hipStream_t st);
