@@ -55,7 +55,7 @@ extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const
     if (rc) return rc;
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
     return pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out, status,
-                              (hipStream_t)stream);
+                              NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
 extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
@@ -72,7 +72,8 @@ extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t
     hipStream_t st = (hipStream_t)stream;
     char *base = (char *)workspace;
     int64_t *C = C_all ? C_all : (int64_t *)(base + lay.C);
-    int64_t *T = T_all ? T_all : (int64_t *)(base + lay.T);
+    int64_t *T = T_all;
+    if (!T && S > 16) T = (int64_t *)(base + lay.T);  // the LDS kernel may need T in memory
     int32_t *bounds = (int32_t *)(base + lay.bounds);
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
@@ -80,9 +81,9 @@ extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t
     rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, C, bounds,
                       workspace, lay, status, st);
     if (rc) return rc;
-    rc = pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, ord, bounds, T, status, st);
-    if (rc) return rc;
-    return pp_launch_argmin(D, S, N, T, C, bounds, ord, base + lay.part, out, st);
+    pp_ws_header *hdr = (pp_ws_header *)(base + lay.hdr);
+    return pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, ord, bounds, T, status, C,
+                              base + lay.part, &hdr->ticket, out, st);
 }
 
 extern "C" const char *pp_strerror(int code) {

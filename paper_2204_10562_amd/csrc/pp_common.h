@@ -20,9 +20,13 @@ static inline int pp_index_bits(int L) {
 }
 
 // Header at the start of the workspace, filled by the pack kernels.
+// pmax[b] is the largest per-microbatch time pack block b saw (P[L], or an XF+XB entry of its
+// slice); the largest value a DP cell can take is the maximum over all PP_PACK_BLOCKS entries.
+#define PP_PACK_BLOCKS 64
 struct pp_ws_header {
-    unsigned long long vmax;  // largest per-microbatch time any cell can take: max(P[L], max XF+XB)
-    int pad[62];
+    unsigned long long pmax[PP_PACK_BLOCKS];
+    unsigned ticket;  // arrival counter of the arg-min, zeroed by the pack kernel
+    unsigned pad[63];
 };
 
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.
@@ -32,7 +36,6 @@ struct pp_ws_layout {
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
 
-#define PP_ARGMIN_PARTS 1024
 #define PP_TILE_MAX_L 128
 #define PP_DP_SLOTS 2048
 
@@ -50,7 +53,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.bounds = off; off += pp_align256((size_t)N * S * 4);
     w.C = off;      off += pp_align256((size_t)N * 8);
     w.T = off;      off += pp_align256((size_t)N * 8);
-    w.part = off;   off += pp_align256((size_t)PP_ARGMIN_PARTS * 16);
+    w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16);
     w.total = off;
     return w;
 }
@@ -70,12 +73,27 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
                  const int32_t *user_ord, int64_t *C_out, int32_t *bounds_out, void *ws,
                  const pp_ws_layout &lay, int32_t *status, hipStream_t st);
+// Makespan of every candidate's plan.  With part/ticket/C/out non-NULL the launch also finds
+// the candidate with the smallest T (lowest index on ties) and fills *out; *ticket must be 0
+// when the kernel starts.  T_out may then be NULL.
 int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
                        const int64_t *XF, const int64_t *XB, const int32_t *orderings,
-                       const int32_t *bounds, int64_t *T_out, int32_t *status, hipStream_t st);
+                       const int32_t *bounds, int64_t *T_out, int32_t *status, const int64_t *C,
+                       void *part, unsigned *ticket, pp_result *out, hipStream_t st);
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
-                     const int32_t *bounds, const int32_t *orderings, void *part, pp_result *out,
-                     hipStream_t st);
+                     const int32_t *bounds, const int32_t *orderings, void *part,
+                     unsigned *ticket, pp_result *out, hipStream_t st);
+size_t pp_argmin_part_bytes(int64_t N);
+
+// Largest time in the tables (all lanes of a full wave must call; result is uniform).
+__device__ __forceinline__ unsigned long long pp_vmax(const pp_ws_header *hdr) {
+    unsigned long long m = hdr->pmax[threadIdx.x & (PP_PACK_BLOCKS - 1)];
+    for (int off = 32; off; off >>= 1) {
+        unsigned long long o = __shfl_xor(m, off);
+        m = o > m ? o : m;
+    }
+    return m;
+}
 
 __device__ __forceinline__ void pp_raise(int32_t *status, int bit) {
     if (status) atomicOr(status, bit);

@@ -12,9 +12,12 @@
 // Otherwise cells are int64 with an explicit strict-less update.  Which one applies depends
 // on the data, which the host cannot see without synchronising, so both kernels are enqueued
 // and the one whose turn it is not returns at once.
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "pp_common.h"
+#include "pp_dp_generic.h"
 #include "pp_dp_tile.h"
 
 // ---------------------------------------------------------------- pack
@@ -28,20 +31,12 @@ struct pack_args {
     int *p32, *x32, *xkt, *ord;  // ord != NULL: write all D! orderings in lexicographic order
 };
 
-// P as int32, padded with P[L] up to a whole tile.
-__device__ void pack_p(const pack_args &a, int tid, int nthreads) {
-    for (int l = tid; l <= a.L + 16; l += nthreads) {
-        int q = l < a.L ? l : a.L;
-        a.p32[l] = (int)(a.PF[q] + a.PB[q]);
-    }
-}
-
 // x32[link*L + k] = XF + XB at cut position k (k layers before the cut), k = 1..L-1; entry 0
 // is 0.  Returns this thread's largest entry.
 __device__ unsigned long long pack_x(const pack_args &a, size_t first, size_t stride) {
     unsigned long long m = 0;
     for (size_t i = first; i < a.total; i += stride) {
-        int k = (int)(i % (size_t)a.L);
+        int k = a.total <= 0xffffffffu ? (int)((unsigned)i % (unsigned)a.L) : (int)(i % (size_t)a.L);
         long long x = 0;
         if (k >= 1) x = a.XF[i - 1] + a.XB[i - 1];
         a.x32[i] = (int)x;
@@ -53,28 +48,20 @@ __device__ unsigned long long pack_x(const pack_args &a, size_t first, size_t st
 
 // Tile layout of the same table as keys, for the register-tiled kernel:
 // xkt[(link*8 + b)*nt + j] = (x << K) | k for k = 8j + b, infinite for k == 0 or k >= L.
-__device__ void pack_xkt(const pack_args &a, size_t first, size_t stride) {
+__device__ void pack_xkt(const pack_args &a, unsigned first, unsigned stride) {
     if (!a.nt) return;
-    const size_t per_link = (size_t)8 * a.nt, n = (size_t)a.D * a.D * per_link;
-    for (size_t i = first; i < n; i += stride) {
-        size_t link = i / per_link;
+    const unsigned per_link = 8u * a.nt, n = (unsigned)a.D * a.D * per_link;  // D*D*128 < 2^32
+    for (unsigned i = first; i < n; i += stride) {
+        unsigned link = i / per_link;
         int r = (int)(i - link * per_link);
         int b = r / a.nt, j = r - b * a.nt, k = 8 * j + b;
         int key = PP_INF32;
         if (k >= 1 && k < a.L) {
-            long long x = a.XF[link * a.L + k - 1] + a.XB[link * a.L + k - 1];
+            long long x = a.XF[(size_t)link * a.L + k - 1] + a.XB[(size_t)link * a.L + k - 1];
             key = (int)(((unsigned)x << a.K) | (unsigned)k);
         }
         a.xkt[i] = key;
     }
-}
-
-__device__ unsigned long long wave_max(unsigned long long m) {
-    for (int off = 32; off; off >>= 1) {
-        unsigned long long o = __shfl_xor(m, off);
-        m = o > m ? o : m;
-    }
-    return m;
 }
 
 __device__ void unrank_rows(const pack_args &a, long long first, long long stride) {
@@ -85,43 +72,42 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
     }
 }
 
-// Small tables: block 0 packs everything and writes the header without atomics; the other
-// blocks (if any) write the explicit ordering list.
-__global__ __launch_bounds__(256) void k_prep_small(pack_args a) {
+// Blocks 0..PP_PACK_BLOCKS-1 pack a slice of the tables each and record the largest time of
+// their slice in the header (no atomics, nothing to initialise); further blocks, if any, write
+// the explicit list of all D! orderings.
+__global__ __launch_bounds__(256) void k_prep(pack_args a) {
     __shared__ unsigned long long sh[4];
     const int tid = threadIdx.x;
-    if (blockIdx.x == 0) {
-        pack_p(a, tid, 256);
-        unsigned long long m = wave_max(pack_x(a, tid, 256));
-        pack_xkt(a, tid, 256);
+    if (blockIdx.x < PP_PACK_BLOCKS) {
+        const unsigned first = blockIdx.x * 256 + tid, stride = PP_PACK_BLOCKS * 256;
+        unsigned long long m = 0;
+        if (blockIdx.x == 0) {
+            // P as int32, padded with P[L] up to a whole tile
+            for (int l = tid; l <= a.L + 16; l += 256) {
+                int q = l < a.L ? l : a.L;
+                a.p32[l] = (int)(a.PF[q] + a.PB[q]);
+            }
+            long long pl = a.PF[a.L] + a.PB[a.L];
+            m = pl < 0 ? ~0ull : (unsigned long long)pl;
+            if (tid == 0) a.hdr->ticket = 0;
+        }
+        unsigned long long mx = pack_x(a, first, stride);
+        m = mx > m ? mx : m;
+        pack_xkt(a, first, stride);
+        for (int off = 32; off; off >>= 1) {
+            unsigned long long o = __shfl_xor(m, off);
+            m = o > m ? o : m;
+        }
         if ((tid & 63) == 0) sh[tid >> 6] = m;
         __syncthreads();
         if (tid == 0) {
             for (int w = 1; w < 4; ++w) m = sh[w] > m ? sh[w] : m;
-            long long pl = a.PF[a.L] + a.PB[a.L];
-            unsigned long long up = pl < 0 ? ~0ull : (unsigned long long)pl;
-            a.hdr->vmax = up > m ? up : m;
+            a.hdr->pmax[blockIdx.x] = m;
         }
-    } else if (a.ord) {
-        unrank_rows(a, (long long)(blockIdx.x - 1) * 256 + tid, (long long)(gridDim.x - 1) * 256);
+    } else {
+        unrank_rows(a, (long long)(blockIdx.x - PP_PACK_BLOCKS) * 256 + tid,
+                    (long long)(gridDim.x - PP_PACK_BLOCKS) * 256);
     }
-}
-
-// Large tables: header seeded by one kernel, entries folded in with atomicMax by the next.
-__global__ __launch_bounds__(256) void k_pack_p(pack_args a) {
-    pack_p(a, threadIdx.x, 256);
-    if (threadIdx.x == 0) {
-        long long pl = a.PF[a.L] + a.PB[a.L];
-        a.hdr->vmax = pl < 0 ? ~0ull : (unsigned long long)pl;
-    }
-}
-
-__global__ __launch_bounds__(256) void k_pack_x(pack_args a) {
-    const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x, stride = (size_t)gridDim.x * 256;
-    unsigned long long m = wave_max(pack_x(a, first, stride));
-    pack_xkt(a, first, stride);
-    if ((threadIdx.x & 63) == 0 && m) atomicMax(&a.hdr->vmax, m);
-    if (a.ord) unrank_rows(a, (long long)first, (long long)stride);
 }
 
 int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
@@ -139,141 +125,19 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
     a.xkt = (int *)(base + lay.xkt);
     a.ord = orderings ? NULL : (int *)(base + lay.ord);
     *ord = orderings ? orderings : (const int32_t *)(base + lay.ord);
-    if (a.total <= (size_t)1 << 16) {
-        int grid = 1;
-        if (a.ord) grid += (int)((N + 255) / 256 < 1024 ? (N + 255) / 256 : 1024);
-        hipLaunchKernelGGL(k_prep_small, dim3(grid), dim3(256), 0, st, a);
-        return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
-    }
-    hipLaunchKernelGGL(k_pack_p, dim3(1), dim3(256), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-    size_t work = a.total > (size_t)N ? a.total : (size_t)N;
-    int grid = (int)((work + 255) / 256 < 2048 ? (work + 255) / 256 : 2048);
-    hipLaunchKernelGGL(k_pack_x, dim3(grid), dim3(256), 0, st, a);
+    int grid = PP_PACK_BLOCKS;
+    if (a.ord) grid += (int)((N + 255) / 256 < 1024 ? (N + 255) / 256 : 1024);
+    hipLaunchKernelGGL(k_prep, dim3(grid), dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
 // ---------------------------------------------------------------- generic kernel
 
-struct dp_args {
-    int L, D, S, K;
-    long long N;
-    unsigned long long fit_limit;  // keys are usable iff hdr->vmax < fit_limit
-    const long long *PF, *PB, *XF, *XB;
-    const int *ord;  // [N][S] explicit orderings
-    int validate;    // the list came from the caller: check every row
-    const pp_ws_header *hdr;
-    const int *p32, *x32;
-    unsigned short *arg;  // [gridDim.x][S][L+1] backtrack tables, one per resident workgroup
-    long long *C_out;
-    int *bounds_out;
-    int32_t *status;
-};
-
-// Loads candidate c's ordering into s_o[0..S-1]; returns false (uniformly) if it is not a
-// list of distinct devices below D.  Must be called by the whole workgroup.
-__device__ bool load_ordering(const dp_args &a, long long c, int *s_o, int *s_ok) {
-    const int tid = threadIdx.x;
-    if (tid == 0) *s_ok = 1;
-    for (int n = tid; n < a.S; n += blockDim.x) s_o[n] = a.ord[c * a.S + n];
-    __syncthreads();
-    if (a.validate) {
-        for (int n = tid; n < a.S; n += blockDim.x) {
-            int d = s_o[n];
-            bool bad = d < 0 || d >= a.D;
-            for (int q = 0; q < n; ++q) bad |= (s_o[q] == d);
-            if (bad) *s_ok = 0;
-        }
-    }
-    __syncthreads();
-    return *s_ok != 0;
-}
-
-template <bool WIDE>
+// Both representations in one launch; which one runs depends on the data.
 __global__ __launch_bounds__(256) void k_dp_generic(dp_args a) {
-    const bool fits = a.hdr->vmax < a.fit_limit;
-    if (fits == WIDE) return;
-
-    using V = typename std::conditional<WIDE, long long, int>::type;
-    const V INF = WIDE ? (V)PP_INF64 : (V)PP_INF32;
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ int s_o[PP_MAX_STAGES];
-    __shared__ int s_ok;
-    const int L = a.L, S = a.S, K = a.K, tid = threadIdx.x, B = blockDim.x;
-    const int kmask = (1 << K) - 1;
-    V *sP = (V *)smem;      // WIDE: P[l];  keys: (P[l] << K) - l
-    V *sW = sP + (L + 1);   // row n-1, then row n: W[.][l] (keys: time << K in the high bits)
-    V *sG = sW + (L + 1);   // g[k] = max(W[n-1][k], X_n[k])  (keys: | k)
-    unsigned short *arg = a.arg + (size_t)blockIdx.x * S * (L + 1);
-
-    for (int l = tid; l <= L; l += B) {
-        if (WIDE) sP[l] = (V)(a.PF[l] + a.PB[l]);
-        else sP[l] = (V)((a.p32[l] << K) - l);
-    }
-
-    for (long long c = blockIdx.x; c < a.N; c += gridDim.x) {
-        __syncthreads();
-        if (!load_ordering(a, c, s_o, &s_ok)) {
-            if (tid == 0) { pp_raise(a.status, PP_FAULT_ORDERING); a.C_out[c] = PP_INF64; }
-            for (int n = tid; n < S; n += B) a.bounds_out[c * S + n] = 0;
-            continue;
-        }
-        // one stage holding the first l layers
-        for (int l = tid; l <= L; l += B) sW[l] = l ? (WIDE ? sP[l] : sP[l] + l) : INF;
-
-        for (int n = 1; n < S; ++n) {
-            __syncthreads();
-            const size_t link = ((size_t)s_o[n - 1] * a.D + s_o[n]) * L;
-            for (int k = n + tid; k < L; k += B) {
-                if (WIDE) {
-                    V x = (V)(a.XF[link + k - 1] + a.XB[link + k - 1]);
-                    sG[k] = sW[k] > x ? sW[k] : x;
-                } else {
-                    int xk = (a.x32[link + k] << K) | k;
-                    int wk = ((int)sW[k] & ~kmask) | k;
-                    sG[k] = (V)(wk > xk ? wk : xk);
-                }
-            }
-            __syncthreads();
-            // only W[S-1][L] is needed of the last row
-            const int lfirst = (n == S - 1) ? L : n + 1;
-            for (int l = lfirst + tid; l <= L; l += B) {
-                if (WIDE) {
-                    const V Pl = sP[l];
-                    V best = INF;
-                    int bk = 0;
-                    for (int k = n; k < l; ++k) {
-                        V d = Pl - sP[k];
-                        V t = sG[k] > d ? sG[k] : d;
-                        if (t < best) { best = t; bk = k; }
-                    }
-                    sW[l] = best;
-                    arg[n * (L + 1) + l] = (unsigned short)bk;
-                } else {
-                    const int Pl = (int)sP[l] + l;
-                    int best = PP_INF32;
-                    for (int k = n; k < l; ++k) {
-                        int d = Pl - (int)sP[k];
-                        int t = (int)sG[k] > d ? (int)sG[k] : d;
-                        best = t < best ? t : best;
-                    }
-                    sW[l] = (V)best;
-                    arg[n * (L + 1) + l] = (unsigned short)(best & kmask);
-                }
-            }
-        }
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            a.C_out[c] = WIDE ? (long long)sW[L] : (long long)((int)sW[L] >> K);
-            int e = L;
-            for (int n = S - 1; n >= 1; --n) {
-                a.bounds_out[c * S + n] = e;
-                e = arg[n * (L + 1) + e];
-            }
-            a.bounds_out[c * S] = e;
-        }
-    }
+    if (pp_vmax(a.hdr) < a.fit_limit) dp_generic_body<false>(a, smem);
+    else dp_generic_body<true>(a, smem);
 }
 
 // Consecutive candidates one wave of the tiled kernel walks.  For all D! orderings in
@@ -325,39 +189,40 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     a.C_out = (long long *)C_out;
     a.bounds_out = bounds_out;
     a.status = status;
-    int block = (L + 63) / 64 * 64;
-    if (block > 256) block = 256;
-    const int grid = lay.slots;
+    a.nblocks = lay.slots;
 
     if (lay.nt) {
-        // 32-bit keys, L <= 128: register-tiled kernel, one wave per candidate
+        // L <= 128: register-tiled kernel, one wave per candidate (falls back to the generic
+        // int64 body inside the same launch when the times do not fit 32-bit keys)
         dp_tile_args t;
         t.L = L; t.D = D; t.S = S; t.K = a.K; t.N = N;
-        t.fit_limit = a.fit_limit;
         t.validate = a.validate;
-        t.hdr = a.hdr; t.p32 = a.p32;
         t.xkt = (const int *)(base + lay.xkt);
-        t.ord = a.ord;
-        t.C_out = a.C_out; t.bounds_out = bounds_out; t.status = status;
         int cus = 256;
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess)
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const size_t lds_wave = (size_t)S * (8 * lay.nt + 4) * 4;
+        const size_t lds_wave = pp_dp_tile_lds_per_wave(S, lay.nt);
         int wpb = 4;  // waves per workgroup, limited by 64 KiB of LDS
         while (wpb > 1 && lds_wave * wpb > 64 * 1024) wpb >>= 1;
-        if (lds_wave * wpb > 64 * 1024) return PP_ERR_INVALID_ARG;  // cannot happen: S*132*4 <= 33 KiB
-        const int waves_per_simd = lay.nt >= 15 ? 2 : (lay.nt >= 13 ? 3 : 4);
+        if (lds_wave * wpb > 64 * 1024) return PP_ERR_INVALID_ARG;  // cannot happen for S <= 64
+        const int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
         const long long slots = (long long)cus * 4 * waves_per_simd;
         t.chunk = choose_chunk(N, S, D, lex_ord != NULL, slots);
+        // tuning overrides for experiments: PP_DP_CHUNK (candidates per wave), PP_DP_WPB (waves
+        // per workgroup); the results do not depend on either
+        if (const char *e = getenv("PP_DP_CHUNK")) { long long v = atoll(e); if (v >= 1) t.chunk = v; }
+        if (const char *e = getenv("PP_DP_WPB")) {
+            int v = atoi(e);
+            if (v >= 1 && v <= 4 && lds_wave * v <= 64 * 1024) wpb = v;
+        }
         const long long nchunks = (N + t.chunk - 1) / t.chunk;
-        int rc = pp_launch_dp_tile(t, lay.nt, (int)((nchunks + wpb - 1) / wpb), wpb, st);
-        if (rc) return rc;
-    } else {
-        hipLaunchKernelGGL(k_dp_generic<false>, dim3(grid), dim3(block), (size_t)3 * (L + 1) * 4, st, a);
-        if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+        const int grid = (int)((nchunks + wpb - 1) / wpb);
+        if (a.nblocks > grid) a.nblocks = grid;
+        t.g = a;
+        return pp_launch_dp_tile(t, lay.nt, grid, wpb, st);
     }
-    hipLaunchKernelGGL(k_dp_generic<true>, dim3(grid), dim3(block), (size_t)3 * (L + 1) * 8, st, a);
-    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-    return PP_OK;
+    int block = 256;
+    hipLaunchKernelGGL(k_dp_generic, dim3(a.nblocks), dim3(block), (size_t)3 * (L + 1) * 8, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }

@@ -2,23 +2,27 @@
 #pragma once
 
 #include "pp_common.h"
+#include "pp_dp_generic.h"
 
-#define DPT_THREADS 256
+#define DPT_ARENA_ROWS 64  // backtrack rows a wave keeps before it must write plans out
+#define DPT_PENDING 64     // candidates whose plans are written out together (one per lane)
 
 struct dp_tile_args {
     int L, D, S, K;
     long long N;
-    long long chunk;               // consecutive candidates walked by one wave
-    unsigned long long fit_limit;  // keys are usable iff hdr->vmax < fit_limit
-    int validate;                  // orderings came from the caller: check them
-    const pp_ws_header *hdr;
-    const int *p32;   // P[min(l, L)] for l = 0..8*NT
+    long long chunk;  // consecutive candidates walked by one wave
+    int validate;     // orderings came from the caller: check them
     const int *xkt;   // [link][b][j] keys ((XF+XB) << K) | k for k = 8j+b, infinite if k == 0 or k >= L
-    const int *ord;   // [N][S] explicit orderings
-    long long *C_out;
-    int *bounds_out;
-    int32_t *status;
+    dp_args g;        // tables, outputs and the generic fallback's arguments
 };
+
+// LDS bytes one wave needs: S key rows, the backtrack arena, the pending candidates' row slots.
+__host__ __device__ static inline size_t pp_dp_tile_lds_per_wave(int S, int nt) {
+    size_t rows = (size_t)S * (8 * nt + 4) * 4;
+    size_t arena = (size_t)DPT_ARENA_ROWS * (8 * nt + 4);
+    size_t slots = (size_t)DPT_PENDING * S;
+    return (rows + arena + slots + 15) & ~(size_t)15;
+}
 
 // grid workgroups of wpb waves; wave w walks candidates [w*chunk, (w+1)*chunk)
 int pp_launch_dp_tile(const dp_tile_args &a, int nt, int grid, int wpb, hipStream_t st);

@@ -11,18 +11,24 @@
 // computes its NT(NT+1)/2 values once (invalid pairs k >= l hold the infinite key) and keeps
 // them in registers for the lifetime of the wave.  A row then costs, per (cell, split) pair,
 // one max and half a three-operand min, plus a 3-step DPP min over the 8 lanes that share a
-// cell and 2 operations per split to build g.  Rows live in LDS (their low key bits are the
-// backtrack table), one private slice per wave, so there are no barriers.
+// cell and 2 operations per split to build g.  The rows of the current candidate live in LDS,
+// one private slice per wave, so there are no barriers.
 //
 // Row n of a candidate depends only on the first n+1 devices of its ordering.  A wave walks
 // a contiguous chunk of candidates and recomputes only the rows from the first position in
 // which the ordering differs from the previous candidate's; with all D! orderings in
 // lexicographic order most rows are shared.
+//
+// Reading a plan back is a chain of S-1 dependent lookups, far longer than the arithmetic of
+// a candidate that recomputes one or two rows.  So every computed row also leaves its split
+// indices (one byte per cell) in an arena in LDS, every finished candidate records which
+// arena rows make up its path, and the plans of up to 64 finished candidates are read back
+// together, one candidate per lane.
 #include "pp_common.h"
 #include "pp_dp_tile.h"
 
-#define DPP_QUAD_XOR1 0xB1   // quad_perm:[1,0,3,2]
-#define DPP_QUAD_XOR2 0x4E   // quad_perm:[2,3,0,1]
+#define DPP_QUAD_XOR1 0xB1     // quad_perm:[1,0,3,2]
+#define DPP_QUAD_XOR2 0x4E     // quad_perm:[2,3,0,1]
 #define DPP_HALF_MIRROR 0x141  // row_half_mirror: lane b <-> 7-b within each 8 lanes
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
@@ -42,18 +48,38 @@ __device__ __forceinline__ int min_over_b(int v) {
     return v;
 }
 
-template <int NT>
-__global__ __launch_bounds__(DPT_THREADS) void k_dp_tile(dp_tile_args a) {
-    if (!(a.hdr->vmax < a.fit_limit)) return;  // the int64 kernel takes over
+__device__ __forceinline__ void lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
-    extern __shared__ int lds[];
-    constexpr int RS = 8 * NT + 4;  // row stride in dwords: index k (0 = infinite) .. 8NT
+template <int NT>
+__global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (!(pp_vmax(a.g.hdr) < a.g.fit_limit)) {
+        dp_generic_body<true>(a.g, smem);  // times too large for 32-bit keys
+        return;
+    }
+
+    constexpr int RS = 8 * NT + 4;  // key row stride in dwords: index k (0 = infinite) .. 8NT
+    constexpr int RB = 8 * NT + 4;  // arena row stride in bytes: split index of cell l at [l]
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int la = lane >> 3, lb = lane & 7;
     const int S = a.S, K = a.K, L = a.L, D = a.D;
     const int kmask = (1 << K) - 1;
-    int *rows = lds + wib * S * RS;
+    unsigned char *mine = smem + (size_t)wib * pp_dp_tile_lds_per_wave(S, NT);
+    int *rows = (int *)mine;
+    unsigned char *arena = mine + (size_t)S * RS * 4;
+    unsigned char *slots = arena + (size_t)DPT_ARENA_ROWS * RB;  // [pending][S] arena row of row n
+    long long *C_out = a.g.C_out;
+    int *bounds_out = a.g.bounds_out;
+    const int *ord = a.g.ord;
+
+    const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + wib;
+    const long long c0 = wave * a.chunk;
+    const long long c1 = c0 + a.chunk < a.N ? c0 + a.chunk : a.N;
+    if (c0 >= c1) return;
 
     // candidate-independent part: Dp[i][j] = ((P[l] - P[k]) << K) | k, or infinite if k >= l
     int Dp[NT * (NT + 1) / 2];
@@ -61,14 +87,13 @@ __global__ __launch_bounds__(DPT_THREADS) void k_dp_tile(dp_tile_args a) {
         int Pl[NT], Pk[NT];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            Pl[i] = a.p32[8 * i + la + 1] << K;
-            Pk[i] = (a.p32[8 * i + lb] << K) - (8 * i + lb);
+            Pl[i] = a.g.p32[8 * i + la + 1] << K;
+            Pk[i] = (a.g.p32[8 * i + lb] << K) - (8 * i + lb);
         }
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
-            for (int j = 0; j <= i; ++j)
-            {
+            for (int j = 0; j <= i; ++j) {
                 int d = (j < i || lb <= la) ? Pl[i] - Pk[j] : PP_INF32;
                 asm volatile("" : "+v"(d));  // keep the masked value, not the mask, in the loop
                 Dp[i * (i + 1) / 2 + j] = d;
@@ -80,22 +105,63 @@ __global__ __launch_bounds__(DPT_THREADS) void k_dp_tile(dp_tile_args a) {
         }
         // index 0 (no layers before the split) is infeasible in every row
         for (int n = lane; n < S; n += 64) rows[n * RS] = PP_INF32;
+        lds_sync();
     }
 
-    const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + wib;
-    const long long c0 = wave * a.chunk;
-    const long long c1 = c0 + a.chunk < a.N ? c0 + a.chunk : a.N;
-    if (c0 >= c1) return;
     const unsigned long long smask = S >= 64 ? ~0ull : ((1ull << S) - 1);
+    const int top_lane = ((L - 1) & 7) * 8;  // a lane that owns cell L (in tile NT-1)
+
+    // finished candidates pend0 .. pend0+pending-1 wait for their plans to be written out;
+    // lane q keeps the key of cell (S-1, L) of pending candidate q (-1: its ordering was bad)
+    long long pend0 = c0;
+    int pending = 0, v_top = 0;
+    int arena_used = 0;
+    bool fresh = true;  // the arena was emptied: the next candidate must recompute every row
+    int v_cur = 0;  // lane n: arena row holding the split indices of row n of the current path
+
+    // Writes out C and the plans of all pending candidates, one per lane.
+    auto flush = [&]() {
+        lds_sync();
+        const bool live = lane < pending;
+        const long long cq = pend0 + lane;
+        const bool bad = live && v_top < 0;
+        if (__ballot(bad) && lane == 0) pp_raise(a.g.status, PP_FAULT_ORDERING);
+        if (live) C_out[cq] = bad ? PP_INF64 : (long long)(v_top >> K);
+        int e = L;
+        for (int n = S - 1; n >= 0; --n) {
+            if (live) bounds_out[cq * S + n] = bad ? 0 : e;
+            if (n == 0) break;
+            // split index stored with cell (n, e): the key itself for the last row
+            int nxt = v_top & kmask;
+            if (n < S - 1 && live && !bad) nxt = arena[(int)slots[lane * S + n] * RB + e];
+            e = (live && !bad) ? nxt : 0;
+        }
+        pend0 += pending;
+        pending = 0;
+        arena_used = 0;
+        fresh = true;
+    };
+
+    if (S == 1) {
+        // a single stage: nothing to compute, C = P[L]
+        const int key = rows[L];
+        for (long long c = c0; c < c1; ++c) {
+            int d = lane == 0 ? ord[c] : 0;
+            const bool bad = a.validate && (d < 0 || d >= D);
+            if (lane == pending) v_top = __builtin_amdgcn_readfirstlane(bad) ? -1 : key;
+            if (++pending == DPT_PENDING) flush();
+        }
+        if (pending) flush();
+        return;
+    }
 
     // Lane n carries device o[n] of the candidate (v_o) and the link index o[n-1]*D + o[n]
-    // that row n needs (v_link).  `first` is the first row to recompute: rows below it are
-    // still valid from the previous candidate of this wave.
+    // that row n needs (v_link).
     int v_prev = 0;
     bool have_prev = false;
-    int v_o = lane < S ? a.ord[c0 * S + lane] : 0;
+    int v_o = lane < S ? ord[c0 * S + lane] : 0;
 
-    // Looks at candidate ordering v (previous one in v_prev): returns the first row to
+    // Looks at candidate ordering v (previous valid one in v_prev): returns the first row to
     // compute, or -1 if the ordering is not a list of distinct devices below D.
     auto inspect = [&](int v) -> int {
         int p = 0;
@@ -111,7 +177,9 @@ __global__ __launch_bounds__(DPT_THREADS) void k_dp_tile(dp_tile_args a) {
             }
             if (__ballot(bad)) return -1;
         }
-        return p > 1 ? p : 1;
+        // rows below p are reused, so their split indices must still be in the arena
+        p = (p > 1 && !fresh) ? p : 1;
+        return p < S - 1 ? p : S - 1;  // the last row is always recomputed
     };
     auto links = [&](int v) -> int {
         int up = __shfl_up(v, 1);
@@ -123,97 +191,137 @@ __global__ __launch_bounds__(DPT_THREADS) void k_dp_tile(dp_tile_args a) {
         for (int j = 0; j < NT; ++j) x[j] = xp[j];
     };
 
+    // first candidate of the chunk (bad ones are recorded and skipped)
+    long long c = c0;
     int first = inspect(v_o);
-    int v_link = first >= 0 ? links(v_o) : 0;
+    while (first < 0) {
+        if (lane == pending) v_top = -1;
+        if (++pending == DPT_PENDING) flush();
+        if (++c >= c1) break;
+        v_o = lane < S ? ord[c * S + lane] : 0;
+        first = inspect(v_o);
+    }
+    if (c >= c1) {
+        if (pending) flush();
+        return;
+    }
+    int v_link = links(v_o);
     int xk[NT];
-    if (first >= 1 && first < S) fetch_x(xk, __builtin_amdgcn_readlane(v_link, first));
+    fetch_x(xk, __builtin_amdgcn_readlane(v_link, first));
 
-    for (long long c = c0; c < c1; ++c) {
-        // ordering of the next candidate, needed only after this one's rows
+    for (;;) {
+        // c is a valid candidate whose rows first..S-1 are to be computed; xk holds (or is
+        // about to receive) the channel keys of row `first`
+        fresh = false;
         const bool more = c + 1 < c1;
-        int v_on = (more && lane < S) ? a.ord[(c + 1) * S + lane] : 0;
+        int v_on = (more && lane < S) ? ord[(c + 1) * S + lane] : 0;
+        int first_n = -2, v_link_n = 0;  // next candidate: -2 none, -1 bad ordering
+        bool flush_after = false;
 
-        if (first >= 0) {
-            for (int n = first; n < S; ++n) {
-                // next row's channel keys are fetched while this row is computed
-                int xn[NT];
-                if (n + 1 < S) fetch_x(xn, __builtin_amdgcn_readlane(v_link, n + 1));
-                const int *prow = rows + (n - 1) * RS;
-                int *nrow = rows + n * RS;
-                int g[NT];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    int w = prow[8 * j + lb];
-                    // previous row's time with this split's index in the low bits, then the channel
-                    int wk = (w & ~kmask) | (xk[j] & kmask);
-                    g[j] = imax(wk, xk[j]);
+        for (int n = first; n < S; ++n) {
+            // Fetch the channel keys of the row computed next while this one is computed.
+            // After the last row that is the first row of the next candidate (looked at
+            // here), or, if there is none, this row's keys once more.
+            int next_link = __builtin_amdgcn_readlane(v_link, n + 1 < S ? n + 1 : n);
+            if (n == S - 1 && more) {
+                v_prev = v_o;
+                have_prev = true;
+                first_n = inspect(v_on);
+                if (first_n >= 0) {
+                    // rows first_n..S-2 need arena rows; one more pending candidate needs a lane
+                    if (arena_used + (S - 1 - first_n) > DPT_ARENA_ROWS || pending + 2 > DPT_PENDING) {
+                        flush_after = true;
+                        first_n = 1;
+                    }
+                    v_link_n = links(v_on);
+                    next_link = __builtin_amdgcn_readlane(v_link_n, first_n);
                 }
-                if (n < S - 1) {
-                    int acc[NT];
+            }
+            int xn[NT];
+            fetch_x(xn, next_link);
+
+            const int *prow = rows + (n - 1) * RS;
+            int *nrow = rows + n * RS;
+            int g[NT];
 #pragma unroll
-                    for (int i = 0; i < NT; ++i) {
-                        int v = PP_INF32;
+            for (int j = 0; j < NT; ++j) g[j] = prow[8 * j + lb];
 #pragma unroll
-                        for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], Dp[i * (i + 1) / 2 + j]));
-                        acc[i] = v;
-                    }
+            for (int j = 0; j < NT; ++j) asm volatile("" : "+v"(g[j]));  // all reads in flight at once
 #pragma unroll
-                    for (int i = 0; i < NT; ++i) {
-                        acc[i] = min_over_b(acc[i]);
-                        asm volatile("" : "+v"(acc[i]));
-                    }
-                    if (lb == 0) {
+            for (int j = 0; j < NT; ++j) {
+                // previous row's time with this split's index in the low bits, then the channel
+                int wk = (g[j] & ~kmask) | (xk[j] & kmask);
+                g[j] = imax(wk, xk[j]);
+            }
+            if (n < S - 1) {
+                int acc[NT];
 #pragma unroll
-                        for (int i = 0; i < NT; ++i) nrow[8 * i + la + 1] = acc[i];
-                    }
-                } else {
-                    // only W[S-1][L] is needed of the last row; L lies in tile NT-1
-                    constexpr int i = NT - 1;
+                for (int i = 0; i < NT; ++i) {
                     int v = PP_INF32;
 #pragma unroll
                     for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], Dp[i * (i + 1) / 2 + j]));
-                    v = min_over_b(v);
-                    asm volatile("" : "+v"(v));
-                    if (lb == 0) nrow[8 * i + la + 1] = v;
+                    acc[i] = v;
                 }
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int j = 0; j < NT; ++j) xk[j] = xn[j];
+                for (int i = 0; i < NT; ++i) {
+                    acc[i] = min_over_b(acc[i]);
+                    asm volatile("" : "+v"(acc[i]));
+                }
+                const int slot = arena_used++;
+                if (lane == n) v_cur = slot;
+                if (lb == 0) {
+                    unsigned char *arow = arena + slot * RB;
+#pragma unroll
+                    for (int i = 0; i < NT; ++i) {
+                        nrow[8 * i + la + 1] = acc[i];
+                        arow[8 * i + la + 1] = (unsigned char)(acc[i] & kmask);
+                    }
+                }
+                lds_sync();
+            } else {
+                // only W[S-1][L] is needed of the last row; L lies in tile NT-1
+                constexpr int i = NT - 1;
+                int v = PP_INF32;
+#pragma unroll
+                for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], Dp[i * (i + 1) / 2 + j]));
+                v = min_over_b(v);
+                const int top = __builtin_amdgcn_readlane(v, top_lane);
+                // candidate finished: remember its key and the arena rows of its path
+                if (lane == pending) v_top = top;
+                if (lane < S) slots[pending * S + lane] = (unsigned char)v_cur;
+                ++pending;
             }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) xk[j] = xn[j];
         }
 
-        // look at the next candidate and start fetching its first row's channel keys, so
-        // that the fetch overlaps this candidate's read-back below
-        const bool ok = first >= 0;
-        int first_n = 0, v_link_n = 0;
-        if (more) {
-            if (ok) { v_prev = v_o; have_prev = true; } else { have_prev = false; }
-            first_n = inspect(v_on);
-            if (first_n >= 0) {
-                v_link_n = links(v_on);
-                if (first_n < S) fetch_x(xk, __builtin_amdgcn_readlane(v_link_n, first_n));
+        if (flush_after) flush();
+        // bad orderings after this candidate are recorded and skipped
+        while (first_n == -1) {
+            if (lane == pending) v_top = -1;
+            if (++pending == DPT_PENDING) flush();
+            ++c;
+            first_n = -2;
+            if (c + 1 < c1) {
+                v_on = lane < S ? ord[(c + 1) * S + lane] : 0;
+                first_n = inspect(v_on);  // compared with the last valid candidate
+                if (first_n >= 0) {
+                    if (arena_used + (S - 1 - first_n) > DPT_ARENA_ROWS || pending + 2 > DPT_PENDING) {
+                        flush();
+                        first_n = 1;
+                    }
+                    v_link_n = links(v_on);
+                    fetch_x(xk, __builtin_amdgcn_readlane(v_link_n, first_n));
+                }
             }
         }
-
-        if (ok) {
-            // bottleneck and plan: every lane follows the same chain, lane n keeps bound n
-            int e = L, mine = 0;
-            const int top = rows[(S - 1) * RS + L];
-            for (int m = S - 1; m >= 1; --m) {
-                if (lane == m) mine = e;
-                e = rows[m * RS + e] & kmask;
-            }
-            if (lane == 0) { mine = e; a.C_out[c] = (long long)(top >> K); }
-            if (lane < S) a.bounds_out[c * S + lane] = mine;
-        } else {
-            if (lane == 0) { pp_raise(a.status, PP_FAULT_ORDERING); a.C_out[c] = PP_INF64; }
-            if (lane < S) a.bounds_out[c * S + lane] = 0;
-        }
+        if (first_n < 0) break;  // no candidate left
+        ++c;
         v_o = v_on;
-        first = first_n;
         v_link = v_link_n;
+        first = first_n;
     }
+    if (pending) flush();
 }
 
 template <int NT>
@@ -223,7 +331,9 @@ static int launch_nt(const dp_tile_args &a, int grid, int wpb, size_t lds, hipSt
 }
 
 int pp_launch_dp_tile(const dp_tile_args &a, int nt, int grid, int wpb, hipStream_t st) {
-    const size_t lds = (size_t)wpb * a.S * (8 * nt + 4) * 4;
+    size_t lds = (size_t)wpb * pp_dp_tile_lds_per_wave(a.S, nt);
+    const size_t generic = (size_t)3 * (a.L + 1) * 8;  // the int64 fallback's rows
+    if (lds < generic) lds = generic;
     switch (nt) {
 #define CASE(n) case n: return launch_nt<n>(a, grid, wpb, lds, st);
         CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)

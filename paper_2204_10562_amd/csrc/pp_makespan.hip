@@ -10,202 +10,330 @@
 // where a resource's idle time is the latest finish of its two blocks j and 2R-j (finish
 // times on one resource never decrease).  Within a sweep the forward block of a resource
 // precedes its backward block.  All blocks of a sweep depend only on the sweep before (the
-// anti-diagonal t = m + j - 1 of the (block, microbatch) grid), so one lane can carry one
-// candidate with all lanes running the same uniform loop.
+// anti-diagonal t = m + j - 1 of the (block, microbatch) grid), so one lane carries one
+// candidate and all lanes run the same uniform loop.
+//
+// Two kernels: for S <= 16 the 4S-3 durations and finish times of a lane live in registers
+// (blocks fully unrolled, 32-bit when the bound (M+4S-4) * largest block of Lemma 1 fits,
+// else 64-bit, decided per wave); for larger S they live in the lane's own LDS column.
+// When asked to, each wave also reduces (T, candidate) to its minimum and the last wave to
+// finish reduces the per-wave minima to the winner record.
 #include "pp_common.h"
 
-// One lane per candidate; the lane's state (block durations, last finish per block) lives
-// in its own LDS column [row][lane], so there are no bank conflicts and no barriers.
-// blockDim.x = lanes in use (64, or fewer when 2 * (4S-3) rows of 64 would not fit in LDS).
-__global__ __launch_bounds__(64) void k_makespan_lds(
-    int L, int D, int S, long long N, int M, const long long *__restrict__ PF,
-    const long long *__restrict__ PB, const long long *__restrict__ XF,
-    const long long *__restrict__ XB, const int *__restrict__ orderings,
-    const int *__restrict__ bounds, long long *__restrict__ T_out, int32_t *status) {
-    extern __shared__ long long sm[];
-    const int lane = threadIdx.x, W = blockDim.x;
-    const int R = 2 * S - 1, J = 2 * R - 1;
-    // rows 0..J-1: duration of block j = row+1; rows J..2J-1: its latest finish time
-    long long *dur = sm + lane;
-    long long *fin = sm + (size_t)J * W + lane;
-    const long long c = (long long)blockIdx.x * W + lane;
-    const bool live = c < N;
-    int fault = 0;
-
-    if (live) {
-        // ordering must be distinct devices below D
-        if (orderings) {
-            for (int n = 0; n < S; ++n) {
-                int d = orderings[c * S + n];
-                bool bad = d < 0 || d >= D;
-                for (int q = 0; q < n; ++q) bad |= (orderings[c * S + q] == d);
-                if (bad) fault |= PP_FAULT_ORDERING;
-            }
-        }
-        int prev = 0;
-        for (int n = 0; n < S; ++n) {
-            int e = bounds[c * S + n];
-            if (e <= prev || e > L) fault |= PP_FAULT_BOUNDS;
-            prev = e;
-        }
-        if (prev != L) fault |= PP_FAULT_BOUNDS;
-    }
-    long long worst = 0;
-    {
-        unsigned long long rem = (unsigned long long)(live ? c : 0);
-        unsigned used = 0;
-        int e_prev = 0, o_prev = 0;
-        for (int n = 0; n < S; ++n) {
-            long long F = 0, Bk = 0, cf = 0, cb = 0;
-            int o_n = 0;
-            if (live && !fault) {
-                o_n = orderings ? orderings[c * S + n] : pp_unrank_next(D, n, rem, used);
-                int e = bounds[c * S + n];
-                F = PF[e] - PF[e_prev];
-                Bk = PB[e] - PB[e_prev];
-                if (n) {
-                    size_t at = ((size_t)o_prev * D + o_n) * L + (size_t)(e_prev - 1);
-                    cf = XF[at];
-                    cb = XB[at];
-                }
-                e_prev = e;
-                o_prev = o_n;
-            }
-            worst = max(worst, max(F + Bk, cf + cb));
-            const int r = 2 * n + 1;  // stage n is resource 2n+1, channel n is resource 2n
-            if (n == S - 1) {
-                dur[(size_t)(R - 1) * W] = F + Bk;  // merged forward+backward block
-            } else {
-                dur[(size_t)(r - 1) * W] = F;
-                dur[(size_t)((2 * R - r) - 1) * W] = Bk;
-            }
-            if (n) {
-                dur[(size_t)((r - 1) - 1) * W] = cf;
-                dur[(size_t)((2 * R - (r - 1)) - 1) * W] = cb;
-            }
-        }
-    }
-    // the schedule is no longer than (M + 4S - 4) * C (Lemma 1)
-    if (live && !fault && worst > (PP_CAP62 - 1) / ((long long)M + 4 * S - 4))
-        fault |= PP_FAULT_OVERFLOW;
-
-    for (int j = 1; j <= J; ++j) fin[(size_t)(j - 1) * W] = 0;
-
-    const int sweeps = M + 2 * R - 2;
-    for (int t = 1; t <= sweeps; ++t) {
-        const int jlo = max(1, t - M + 1), jhi = min(J, t);
-        const long long finR_prev = fin[(size_t)(R - 1) * W];
-        // forward blocks (and the merged block R), descending so that fin[j-1] is still the
-        // previous sweep's value
-        for (int j = min(jhi, R); j >= jlo; --j) {
-            long long idle = max(fin[(size_t)(j - 1) * W], fin[(size_t)((2 * R - j) - 1) * W]);
-            long long ready = j > 1 ? fin[(size_t)((j - 1) - 1) * W] : 0;
-            fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
-        }
-        // backward blocks: the resource may just have been used by this sweep's forward block
-        for (int j = jhi; j >= max(jlo, R + 1); --j) {
-            long long idle = max(fin[(size_t)(j - 1) * W], fin[(size_t)((2 * R - j) - 1) * W]);
-            long long ready = j == R + 1 ? finR_prev : fin[(size_t)((j - 1) - 1) * W];
-            fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
-        }
-    }
-    if (live) {
-        T_out[c] = fault ? PP_INF64 : fin[(size_t)(J - 1) * W];
-        if (fault) pp_raise(status, fault);
-    }
-}
-
-int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
-                       const int64_t *XF, const int64_t *XB, const int32_t *orderings,
-                       const int32_t *bounds, int64_t *T_out, int32_t *status, hipStream_t st) {
-    const int J = 4 * S - 3;
-    int W = 64;  // lanes per workgroup: as many as keep 2J rows of int64 within 64 KiB of LDS
-    while ((size_t)2 * J * W * 8 > 64 * 1024) W >>= 1;
-    size_t lds = (size_t)2 * J * W * 8;
-    unsigned grid = (unsigned)((N + W - 1) / W);
-    hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, L, D, S, (long long)N, M,
-                       (const long long *)PF, (const long long *)PB, (const long long *)XF,
-                       (const long long *)XB, orderings, bounds, (long long *)T_out, status);
-    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-    return PP_OK;
-}
-
-// ---------------------------------------------------------------- candidate arg-min
-
 struct tc_pair { long long T, c; };
+
+struct mk_args {
+    int L, D, S, M;
+    long long N;
+    const long long *PF, *PB, *XF, *XB;
+    const int *orderings;  // NULL = all D! orderings, candidate index = lexicographic rank
+    const int *bounds;
+    long long *T_out;      // may be NULL when only the winner is wanted
+    int32_t *status;
+    // arg-min (all NULL when not wanted)
+    tc_pair *part;         // one entry per wave
+    unsigned *ticket;      // zeroed before the launch
+    const long long *C;
+    pp_result *out;
+};
 
 __device__ __forceinline__ tc_pair tc_min(tc_pair a, tc_pair b) {
     return (b.T < a.T || (b.T == a.T && b.c < a.c)) ? b : a;
 }
 
-__device__ tc_pair block_tc_min(tc_pair v, tc_pair *sh) {
+__device__ __forceinline__ tc_pair wave_tc_min(tc_pair v) {
     for (int off = 32; off; off >>= 1) {
         tc_pair o;
         o.T = __shfl_xor(v.T, off);
         o.c = __shfl_xor(v.c, off);
         v = tc_min(v, o);
     }
-    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    if ((threadIdx.x & 63) == 0) sh[wave] = v;
-    __syncthreads();
-    if (threadIdx.x == 0)
-        for (int w = 1; w < nw; ++w) v = tc_min(v, sh[w]);
-    return v;  // valid in thread 0
+    return v;
 }
 
-__global__ __launch_bounds__(256) void k_argmin_partial(long long N, const long long *__restrict__ T,
-                                                        tc_pair *__restrict__ part) {
-    __shared__ tc_pair sh[4];
-    tc_pair v = {PP_INF64, INT64_MAX};
-    for (long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x; c < N;
-         c += (long long)gridDim.x * blockDim.x) {
-        tc_pair o = {T[c], c};
-        v = tc_min(v, o);
-    }
-    v = block_tc_min(v, sh);
-    if (threadIdx.x == 0) part[blockIdx.x] = v;
-}
-
-__global__ __launch_bounds__(256) void k_argmin_final(int parts, int D, int S,
-                                                      const tc_pair *__restrict__ part,
-                                                      const long long *__restrict__ C,
-                                                      const int *__restrict__ bounds,
-                                                      const int *__restrict__ orderings,
-                                                      pp_result *out) {
-    __shared__ tc_pair sh[4];
-    tc_pair v = {PP_INF64, INT64_MAX};
-    for (int i = threadIdx.x; i < parts; i += blockDim.x) v = tc_min(v, part[i]);
-    v = block_tc_min(v, sh);
-    if (threadIdx.x == 0) {
-        const bool none = v.T == PP_INF64;
-        out->best_index = none ? -1 : v.c;
-        out->T = v.T;
-        out->C = none ? PP_INF64 : C[v.c];
-        out->S = S;
-        unsigned long long rem = (unsigned long long)(none ? 0 : v.c);
-        unsigned used = 0;
-        for (int n = 0; n < PP_MAX_STAGES; ++n) {
-            int b = 0, o = 0;
-            if (n < S && !none) {
-                b = bounds[v.c * S + n];
-                o = orderings ? orderings[v.c * S + n] : pp_unrank_next(D, n, rem, used);
+// Checks candidate c's ordering and bounds and gathers its block durations through `put`
+// (called as put(block j (1-based), duration)).  Returns fault bits; on a fault or for a
+// dead lane all durations are 0.  `worst` gets the largest per-resource time f + b.
+// ST > 0 fixes the number of stages at compile time (block numbers become constants).
+template <int ST, typename Put>
+__device__ __forceinline__ int gather_durations(const mk_args &a, long long c, bool live,
+                                                long long &worst, Put put) {
+    const int S = ST ? ST : a.S, L = a.L, D = a.D, R = 2 * S - 1;
+    int fault = 0;
+    if (live) {
+        if (a.orderings) {
+            for (int n = 0; n < S; ++n) {
+                int d = a.orderings[c * S + n];
+                bool bad = d < 0 || d >= D;
+                for (int q = 0; q < n; ++q) bad |= (a.orderings[c * S + q] == d);
+                if (bad) fault |= PP_FAULT_ORDERING;
             }
-            out->bounds[n] = b;
-            out->order[n] = o;
+        }
+        int prev = 0;
+        for (int n = 0; n < S; ++n) {
+            int e = a.bounds[c * S + n];
+            if (e <= prev || e > L) fault |= PP_FAULT_BOUNDS;
+            prev = e;
+        }
+        if (prev != L) fault |= PP_FAULT_BOUNDS;
+    }
+    worst = 0;
+    unsigned long long rem = (unsigned long long)(live ? c : 0);
+    unsigned used = 0;
+    int e_prev = 0, o_prev = 0;
+#pragma unroll
+    for (int n = 0; n < S; ++n) {
+        long long F = 0, Bk = 0, cf = 0, cb = 0;
+        if (live && !fault) {
+            int o_n = a.orderings ? a.orderings[c * S + n] : pp_unrank_next(D, n, rem, used);
+            int e = a.bounds[c * S + n];
+            F = a.PF[e] - a.PF[e_prev];
+            Bk = a.PB[e] - a.PB[e_prev];
+            if (n) {
+                size_t at = ((size_t)o_prev * D + o_n) * L + (size_t)(e_prev - 1);
+                cf = a.XF[at];
+                cb = a.XB[at];
+            }
+            e_prev = e;
+            o_prev = o_n;
+        }
+        long long w = F + Bk > cf + cb ? F + Bk : cf + cb;
+        worst = w > worst ? w : worst;
+        const int r = 2 * n + 1;  // stage n is resource 2n+1, channel n is resource 2n
+        if (n == S - 1) {
+            put(R, F + Bk);  // merged forward+backward block of the last stage
+        } else {
+            put(r, F);
+            put(2 * R - r, Bk);
+        }
+        if (n) {
+            put(r - 1, cf);
+            put(2 * R - (r - 1), cb);
         }
     }
+    // the schedule is no longer than (M + 4S - 4) * C (Lemma 1)
+    if (live && !fault && worst > (PP_CAP62 - 1) / ((long long)a.M + 4 * S - 4))
+        fault |= PP_FAULT_OVERFLOW;
+    return fault;
+}
+
+// Writes T, raises faults, and (if wanted) takes part in the arg-min.
+__device__ __forceinline__ void finish(const mk_args &a, long long c, bool live, int fault,
+                                       long long T, long long wave_id, long long n_waves) {
+    if (live) {
+        if (fault) { T = PP_INF64; pp_raise(a.status, fault); }
+        if (a.T_out) a.T_out[c] = T;
+    }
+    if (!a.part) return;
+    const int lane = threadIdx.x & 63;
+    tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
+    v = wave_tc_min(v);
+    unsigned last = 0;
+    if (lane == 0) {
+        a.part[wave_id] = v;
+        __threadfence();
+        last = atomicAdd(a.ticket, 1u) == (unsigned)(n_waves - 1);
+    }
+    last = __builtin_amdgcn_readfirstlane(last);
+    if (!last) return;
+    // the last wave to arrive sees every partial minimum
+    __threadfence();
+    tc_pair w = {PP_INF64, INT64_MAX};
+    for (long long i = lane; i < n_waves; i += 64) {
+        tc_pair o;
+        o.T = __builtin_nontemporal_load(&a.part[i].T);
+        o.c = __builtin_nontemporal_load(&a.part[i].c);
+        w = tc_min(w, o);
+    }
+    w = wave_tc_min(w);
+    const bool none = w.T == PP_INF64;
+    const int S = a.S;
+    if (lane == 0) {
+        a.out->best_index = none ? -1 : w.c;
+        a.out->T = w.T;
+        a.out->C = none ? PP_INF64 : a.C[w.c];
+        a.out->S = S;
+    }
+    // lane n writes bound n and device n (lanes S.. write zeros)
+    int b = 0, o = 0;
+    if (lane < S && !none) {
+        b = a.bounds[w.c * S + lane];
+        if (a.orderings) {
+            o = a.orderings[w.c * S + lane];
+        } else {
+            unsigned long long rem = (unsigned long long)w.c;
+            unsigned used = 0;
+            for (int n = 0; n <= lane; ++n) o = pp_unrank_next(a.D, n, rem, used);
+        }
+    }
+    a.out->bounds[lane] = b;
+    a.out->order[lane] = o;
+}
+
+// ---------------------------------------------------------------- registers, S <= 16
+
+template <int S, typename V>
+__device__ __forceinline__ V sweep_regs(const long long (&dur64)[4 * S - 3 + 1], int M) {
+    constexpr int R = 2 * S - 1, J = 2 * R - 1;
+    V dur[J + 1], fin[J + 1];
+#pragma unroll
+    for (int j = 1; j <= J; ++j) { dur[j] = (V)dur64[j]; fin[j] = 0; }
+    const int sweeps = M + 2 * R - 2;
+    for (int t = 1; t <= sweeps; ++t) {
+        const int jlo = t - M + 1;  // block j works in this sweep iff jlo <= j <= t
+        const V finR_prev = fin[R];
+        // forward blocks and the merged block R, descending so that fin[j-1] is still the
+        // previous sweep's value
+#pragma unroll
+        for (int j = R; j >= 1; --j) {
+            V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+            V ready = j > 1 ? fin[j - 1] : (V)0;
+            V nv = (idle > ready ? idle : ready) + dur[j];
+            fin[j] = (j >= jlo && j <= t) ? nv : fin[j];
+        }
+        // backward blocks: the resource may just have been used by this sweep's forward block
+#pragma unroll
+        for (int j = J; j >= R + 1; --j) {
+            V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+            V ready = j == R + 1 ? finR_prev : fin[j - 1];
+            V nv = (idle > ready ? idle : ready) + dur[j];
+            fin[j] = (j >= jlo && j <= t) ? nv : fin[j];
+        }
+    }
+    return fin[J];
+}
+
+template <int S>
+__global__ __launch_bounds__(64) void k_makespan_regs(mk_args a) {
+    constexpr int J = 4 * S - 3;
+    const int lane = threadIdx.x;
+    const long long c = (long long)blockIdx.x * 64 + lane;
+    const bool live = c < a.N;
+    long long dur[J + 1];
+    long long worst;
+    int fault = gather_durations<S>(a, c, live, worst, [&](int j, long long d) { dur[j] = d; });
+    // 32-bit arithmetic if no finish time of any lane can reach 2^31
+    const bool narrow = fault || !live || worst <= (long long)0x7fffffff / ((long long)a.M + 4 * S - 4);
+    long long T;
+    if (__all(narrow)) T = (long long)sweep_regs<S, int>(dur, a.M);
+    else T = sweep_regs<S, long long>(dur, a.M);
+    finish(a, c, live, fault, T, blockIdx.x, gridDim.x);
+}
+
+// ---------------------------------------------------------------- LDS columns, any S
+
+// blockDim.x = lanes in use (64, or fewer when 2 * (4S-3) rows of 64 int64 would not fit in
+// 64 KiB of LDS); the lane's state lives in its own column [row][lane]: no bank conflicts, no
+// barriers.
+__global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
+    extern __shared__ long long sm[];
+    const int lane = threadIdx.x, W = blockDim.x;
+    const int S = a.S, M = a.M;
+    const int R = 2 * S - 1, J = 2 * R - 1;
+    // rows 0..J-1: duration of block j = row+1; rows J..2J-1: its latest finish time
+    long long *dur = sm + lane;
+    long long *fin = sm + (size_t)J * W + lane;
+    const long long c = (long long)blockIdx.x * W + lane;
+    const bool live = c < a.N;
+    long long worst;
+    int fault = gather_durations<0>(a, c, live, worst,
+                                    [&](int j, long long d) { dur[(size_t)(j - 1) * W] = d; });
+    for (int j = 1; j <= J; ++j) fin[(size_t)(j - 1) * W] = 0;
+
+    const int sweeps = M + 2 * R - 2;
+    for (int t = 1; t <= sweeps; ++t) {
+        const int jlo = max(1, t - M + 1), jhi = min(J, t);
+        const long long finR_prev = fin[(size_t)(R - 1) * W];
+        for (int j = min(jhi, R); j >= jlo; --j) {
+            long long idle = max(fin[(size_t)(j - 1) * W], fin[(size_t)((2 * R - j) - 1) * W]);
+            long long ready = j > 1 ? fin[(size_t)((j - 1) - 1) * W] : 0;
+            fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
+        }
+        for (int j = jhi; j >= max(jlo, R + 1); --j) {
+            long long idle = max(fin[(size_t)(j - 1) * W], fin[(size_t)((2 * R - j) - 1) * W]);
+            long long ready = j == R + 1 ? finR_prev : fin[(size_t)((j - 1) - 1) * W];
+            fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
+        }
+    }
+    // with fewer than 64 lanes the arg-min below would need another reduction; the host only
+    // asks for it when W == 64
+    finish(a, c, live, fault, fin[(size_t)(J - 1) * W], blockIdx.x, gridDim.x);
+}
+
+template <int S>
+static int launch_regs(const mk_args &a, hipStream_t st) {
+    unsigned grid = (unsigned)((a.N + 63) / 64);
+    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid), dim3(64), 0, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+// one tc_pair per wave of 64 candidates
+size_t pp_argmin_part_bytes(int64_t N) { return (size_t)((N + 63) / 64) * sizeof(tc_pair); }
+
+int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
+                       const int64_t *XF, const int64_t *XB, const int32_t *orderings,
+                       const int32_t *bounds, int64_t *T_out, int32_t *status,
+                       const int64_t *C, void *part, unsigned *ticket, pp_result *out,
+                       hipStream_t st) {
+    mk_args a;
+    a.L = L; a.D = D; a.S = S; a.M = M; a.N = N;
+    a.PF = (const long long *)PF; a.PB = (const long long *)PB;
+    a.XF = (const long long *)XF; a.XB = (const long long *)XB;
+    a.orderings = orderings; a.bounds = bounds;
+    a.T_out = (long long *)T_out; a.status = status;
+    a.part = (tc_pair *)part; a.ticket = ticket; a.C = (const long long *)C; a.out = out;
+    switch (S) {
+#define CASE(n) case n: return launch_regs<n>(a, st);
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+        CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
+#undef CASE
+    }
+    const int J = 4 * S - 3;
+    int W = 64;  // lanes per workgroup: as many as keep 2J rows of int64 within 64 KiB of LDS
+    while ((size_t)2 * J * W * 8 > 64 * 1024) W >>= 1;
+    size_t lds = (size_t)2 * J * W * 8;
+    unsigned grid = (unsigned)((N + W - 1) / W);
+    if (W != 64 && part) {
+        // narrow workgroups: T goes to memory and a separate pass finds the minimum
+        mk_args b = a;
+        b.part = NULL; b.ticket = NULL; b.C = NULL; b.out = NULL;
+        if (!b.T_out) return PP_ERR_INVALID_ARG;
+        hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, b);
+        if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+        return pp_launch_argmin(D, S, N, T_out, C, bounds, orderings, part, ticket, out, st);
+    }
+    hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+// ---------------------------------------------------------------- stand-alone arg-min
+
+// Each wave reduces a strided share of T and then joins the same last-wave reduction.
+__global__ __launch_bounds__(64) void k_argmin(mk_args a) {
+    const int lane = threadIdx.x;
+    tc_pair v = {PP_INF64, INT64_MAX};
+    for (long long c = (long long)blockIdx.x * 64 + lane; c < a.N; c += (long long)gridDim.x * 64) {
+        tc_pair o = {a.T_out[c], c};
+        v = tc_min(v, o);
+    }
+    // reuse finish(): it reduces over the wave, so hand it this lane's minimum as if it were
+    // the lane's own candidate; T_out must not be rewritten
+    mk_args b = a;
+    b.T_out = NULL;
+    finish(b, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
 }
 
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
-                     const int32_t *bounds, const int32_t *orderings, void *part, pp_result *out,
-                     hipStream_t st) {
-    int parts = (int)((N + 255) / 256);
-    if (parts > PP_ARGMIN_PARTS) parts = PP_ARGMIN_PARTS;
-    hipLaunchKernelGGL(k_argmin_partial, dim3(parts), dim3(256), 0, st, (long long)N,
-                       (const long long *)T, (tc_pair *)part);
-    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-    hipLaunchKernelGGL(k_argmin_final, dim3(1), dim3(256), 0, st, parts, D, S,
-                       (const tc_pair *)part, (const long long *)C, bounds, orderings, out);
-    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-    return PP_OK;
+                     const int32_t *bounds, const int32_t *orderings, void *part,
+                     unsigned *ticket, pp_result *out, hipStream_t st) {
+    mk_args a;
+    a.L = 0; a.D = D; a.S = S; a.M = 1; a.N = N;
+    a.PF = a.PB = a.XF = a.XB = NULL;
+    a.orderings = orderings; a.bounds = bounds;
+    a.T_out = (long long *)T; a.status = NULL;
+    a.part = (tc_pair *)part; a.ticket = ticket; a.C = (const long long *)C; a.out = out;
+    long long waves = (N + 63) / 64;
+    if (waves > 1024) waves = 1024;
+    hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves), dim3(64), 0, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
