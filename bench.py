@@ -22,6 +22,9 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 # integer operation per lane per clock
 ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9
 OPS_PER_PAIR = 3  # subtract, max, min on 32-bit keys per (cell, split) pair
+# HBM bytes per k_dp_tile<16> launch on the GPT workload: scaled FETCH_SIZE + WRITE_SIZE from
+# two rocprofv3 --pmc runs (profiles/dp_tile_gpt_hbm_traffic.txt)
+DP_TRAFFIC_BYTES = {"gpt": 3.44e6}
 
 
 def log(*a):
@@ -36,6 +39,9 @@ def main():
     ap.add_argument("--workload", default="gpt", choices=["tiny", "transformer", "gpt", "hetero", "stress"])
     ap.add_argument("--candidates", type=int, default=0, help="override N for the sampled workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="instead of the workload, run 10 plain device copies of this many MiB "
+                         "(reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -44,6 +50,17 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.calibrate_copy:
+        n = args.calibrate_copy * (1 << 20) // 8
+        src = torch.arange(n, dtype=torch.int64, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_MiB": args.calibrate_copy, "copies": 10,
+                          "bytes_read_per_copy": n * 8, "bytes_written_per_copy": n * 8}))
+        return
     from gpu_harness import GpuProblem
     from paper_2204_10562_amd import binding as pp
     from paper_2204_10562_amd import workloads
@@ -96,12 +113,18 @@ def main():
     t_mk = {M: timed(lambda M=M: pp.pp_schedule_makespan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, bounds, T, g.status), reps) for M in Ms}
     t_best = {M: timed(lambda M=M: pp.pp_best_plan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status), reps) for M in Ms}
     assert int(g.status.item()) == 0
+    # what the DP really evaluated (rows shared by consecutive candidates are computed once)
+    pp.pp_partition_dp(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C, bounds, ws, g.status)
+    torch.cuda.synchronize()
+    stats = pp.read_workspace_stats(ws)
+    pairs_exec = stats["pairs_executed"]
 
-    achieved = OPS_PER_PAIR * pairs / t_dp
+    achieved = OPS_PER_PAIR * pairs_exec / t_dp
     log("workload %s: L=%d D=S=%d N=%d M=%s" % (w.name, L, D, N, list(Ms)))
     log("  pp_prefix_costs        %9.1f us" % (t_prefix * 1e6))
-    log("  pp_partition_dp        %9.1f us   %.3e pair-evals/s  %.3e cells/s  %.1f%% of int32 VALU peak"
-        % (t_dp * 1e6, pairs / t_dp, N * S * L / t_dp, 100 * achieved / ALU_PEAK_OPS))
+    log("  pp_partition_dp        %9.1f us   nominal %.3e pair-evals/s  %.3e cells/s" % (t_dp * 1e6, pairs / t_dp, N * S * L / t_dp))
+    log("     executed %d of %d nominal pair-evals (%d rows): %.3e executed pair-evals/s = %.1f%% of int32 VALU peak at %d ops/pair"
+        % (pairs_exec, pairs, stats["rows_executed"], pairs_exec / t_dp, 100 * achieved / ALU_PEAK_OPS, OPS_PER_PAIR))
     for M in Ms:
         log("  pp_schedule_makespan M=%-3d %7.1f us   %.3e block-ops/s" % (M, t_mk[M] * 1e6, N * M * (4 * S - 3) / t_mk[M]))
     for M in Ms:
@@ -115,8 +138,8 @@ def main():
         ppo.build()
         import numpy as np
         rc, PF, PB, XF, XB = ppo.prefix_costs(w.fwd, w.bwd, w.actf, w.actb, w.bw)
-        # bounded sample: at most ~2^31 pair-evals per M (a few seconds on a handful of cores)
-        n_cpu = min(N, max(1, (1 << 31) // workloads.pair_evals_per_candidate(L, S)))
+        # bounded sample: at most ~2^32 pair-evals per M (a few seconds on a handful of cores)
+        n_cpu = min(N, max(1, (1 << 32) // workloads.pair_evals_per_candidate(L, S)))
         o_cpu = None if (w.orderings is None and n_cpu == N) else np.ascontiguousarray(w.explicit_orderings()[:n_cpu])
         t0 = time.perf_counter()
         for M in Ms:
@@ -137,11 +160,13 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": "%s: L=%d, D=S=%d, N=%d orderings, M=%s" % (w.name, L, D, N, list(Ms)),
                    "plans_per_step": N * len(Ms)},
-        "dp_cells_per_s": N * S * L / t_dp, "dp_pair_evals_per_s": pairs / t_dp,
+        "dp_cells_per_s": N * S * L / t_dp, "dp_nominal_pair_evals_per_s": pairs / t_dp,
+        "dp_executed_pair_evals_per_s": pairs_exec / t_dp,
         "roofline": {"bound": "alu", "kernel": "pp_partition_dp", "achieved": achieved / 1e12,
                      "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s (32-bit integer lane-ops)",
-                     "frac": achieved / ALU_PEAK_OPS, "traffic": None,
-                     "launch_us": t_dp * 1e6, "pair_evals_per_launch": pairs, "ops_per_pair": OPS_PER_PAIR},
+                     "frac": achieved / ALU_PEAK_OPS, "traffic": DP_TRAFFIC_BYTES.get(w.name),
+                     "launch_us": t_dp * 1e6, "pair_evals_executed_per_launch": pairs_exec,
+                     "pair_evals_nominal_per_launch": pairs, "ops_per_pair": OPS_PER_PAIR},
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

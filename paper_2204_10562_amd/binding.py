@@ -144,6 +144,18 @@ def pp_best_plan(L, D, S, N, M, PF, PB, XF, XB, orderings, out, T_all, C_all, wo
         _ptr(status, i32, 1, "status"), _stream()))
 
 
+PP_WS_PAIRS_EXECUTED = 1024
+PP_WS_ROWS_EXECUTED = 1536
+
+
+def read_workspace_stats(workspace):
+    """Diagnostic counters the last DP call left in the workspace header (see pp.h)."""
+    import numpy as np
+    head = workspace[:2048].cpu().numpy().view(np.uint64)
+    return dict(pairs_executed=int(head[PP_WS_PAIRS_EXECUTED // 8:PP_WS_PAIRS_EXECUTED // 8 + 64].sum()),
+                rows_executed=int(head[PP_WS_ROWS_EXECUTED // 8:PP_WS_ROWS_EXECUTED // 8 + 64].sum()))
+
+
 def read_result(out, S):
     """Copy a device pp_result (uint8 tensor) to the host and unpack it."""
     raw = bytes(out.cpu().numpy().tobytes()[:RESULT_BYTES])

@@ -5,7 +5,8 @@ import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-LIB_PATH = os.path.join(_PKG, "libpp.so")
+# PP_LIBPP selects another build of the library (experiments); the default is the in-tree one
+LIB_PATH = os.environ.get("PP_LIBPP") or os.path.join(_PKG, "libpp.so")
 
 HIPCC_FLAGS = [
     "-shared", "-fPIC", "--offload-arch=gfx950", "-O3", "-std=c++17",

@@ -24,10 +24,22 @@ static inline int pp_index_bits(int L) {
 // slice); the largest value a DP cell can take is the maximum over all PP_PACK_BLOCKS entries.
 #define PP_PACK_BLOCKS 64
 struct pp_ws_header {
-    unsigned long long pmax[PP_PACK_BLOCKS];
-    unsigned ticket;  // arrival counter of the arg-min, zeroed by the pack kernel
-    unsigned pad[63];
+    unsigned long long pmax[PP_PACK_BLOCKS];  // byte 0
+    unsigned ticket;  // byte 512: arrival counter of the arg-min, zeroed by the pack kernel
+    unsigned pad0[127];
+    // byte 1024: (cell, split) pairs the partition DP actually evaluated in this call (rows
+    // shared between candidates are counted once), spread over 64 counters to keep the
+    // atomics apart; byte 1536: DP rows computed (the single-cell last row counts too).
+    // Zeroed by the pack kernel; the totals are the sums of the 64 entries.
+    unsigned long long pairs_executed[64];
+    unsigned long long rows_executed[64];
 };
+
+__device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long long pairs,
+                                              unsigned long long rows, unsigned who) {
+    atomicAdd(&hdr->pairs_executed[who & 63], pairs);
+    atomicAdd(&hdr->rows_executed[who & 63], rows);
+}
 
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.
 struct pp_ws_layout {

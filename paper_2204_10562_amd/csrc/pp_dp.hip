@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256) void k_prep(pack_args a) {
             long long pl = a.PF[a.L] + a.PB[a.L];
             m = pl < 0 ? ~0ull : (unsigned long long)pl;
             if (tid == 0) a.hdr->ticket = 0;
+            if (tid < 64) { a.hdr->pairs_executed[tid] = 0; a.hdr->rows_executed[tid] = 0; }
         }
         unsigned long long mx = pack_x(a, first, stride);
         m = mx > m ? mx : m;
@@ -140,17 +141,36 @@ __global__ __launch_bounds__(256) void k_dp_generic(dp_args a) {
     else dp_generic_body<true>(a, smem);
 }
 
-// Consecutive candidates one wave of the tiled kernel walks.  For all D! orderings in
-// lexicographic order a chunk of k! candidates shares its first D-k devices, so rows
-// 1..D-k-1 are computed once per chunk and row n >= D-k once per distinct prefix; pick the k
-// that minimises (rounds of chunks over the resident waves) x (rows per chunk).
-static long long choose_chunk(int64_t N, int S, int D, bool lex, long long wave_slots) {
-    if (!lex) return (long long)((N + wave_slots - 1) / wave_slots);
-    long long best_chunk = 1;
-    double best_cost = 1e300;
+// Consecutive candidates one wave of the tiled kernel walks.
+//
+// Caller's list: split it evenly over the resident waves.  All D! orderings in
+// lexicographic order: consecutive candidates share ordering prefixes and with them DP rows,
+// so a wave that walks c candidates computes about c * r + (D - 2 - r) full rows, where
+// r = sum_{m=1}^{D-2} 1/m! is the average number of rows that change from one ordering to
+// the next; a chunk of k! candidates aligned to a multiple of k! shares its first D-k
+// devices and needs exactly (D-k-1) + sum_{n>=D-k} k!/(D-1-n)! rows.  The kernel is bound by
+// instruction issue, so a SIMD that holds w waves takes about w times as long as one that
+// holds a single wave would at full rate, except that a lone wave cannot hide its own LDS
+// and issue latencies and runs about 1.4 times slower per row.  Pick the size that minimises
+// (waves on the busiest SIMD) x (rows per wave) under that model.
+static long long choose_chunk(int64_t N, int D, bool lex, long long simds, int waves_per_simd) {
+    const long long slots = simds * waves_per_simd;
+    const long long even = (long long)((N + slots - 1) / slots);
+    if (!lex || D < 3) return even;
+    double r = 0, term = 1;
+    for (int m = 1; m <= D - 2; ++m) { term /= m; r += term; }
+    auto cost = [&](long long c, double rows) {
+        long long nwaves = (long long)((N + c - 1) / c);
+        long long per_simd = (nwaves + simds - 1) / simds;
+        if (per_simd > waves_per_simd)  // later waves start as earlier ones finish
+            return rows * (double)nwaves / (double)simds;
+        return rows * (per_simd <= 1 ? 1.4 : (double)per_simd);
+    };
+    long long best = even;
+    double best_cost = cost(even, even * r + (D - 2 - r) + 0.1 * even);
     long long f = 1;
-    for (int k = 0; k < D; ++k) {
-        if (k) f *= k;
+    for (int k = 1; k < D; ++k) {
+        f *= k;
         if (f > N) break;
         double rows = 0.1 * (double)f;  // last row: one cell per candidate
         for (int n = 1; n <= D - 2; ++n) {
@@ -161,13 +181,10 @@ static long long choose_chunk(int64_t N, int S, int D, bool lex, long long wave_
             }
             rows += nodes;
         }
-        long long nch = (long long)(N / f);
-        double rounds = (double)((nch + wave_slots - 1) / wave_slots);
-        double cost = rounds * rows;
-        if (cost < best_cost) { best_cost = cost; best_chunk = f; }
+        double c = cost(f, rows);
+        if (c < best_cost) { best_cost = c; best = f; }
     }
-    (void)S;
-    return best_chunk;
+    return best;
 }
 
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
@@ -182,7 +199,7 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     a.XF = (const long long *)XF; a.XB = (const long long *)XB;
     a.ord = lex_ord ? lex_ord : user_ord;
     a.validate = user_ord != NULL;
-    a.hdr = (const pp_ws_header *)(base + lay.hdr);
+    a.hdr = (pp_ws_header *)(base + lay.hdr);
     a.p32 = (const int *)(base + lay.p32);
     a.x32 = (const int *)(base + lay.x32);
     a.arg = (unsigned short *)(base + lay.arg);
@@ -207,8 +224,7 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         while (wpb > 1 && lds_wave * wpb > 64 * 1024) wpb >>= 1;
         if (lds_wave * wpb > 64 * 1024) return PP_ERR_INVALID_ARG;  // cannot happen for S <= 64
         const int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
-        const long long slots = (long long)cus * 4 * waves_per_simd;
-        t.chunk = choose_chunk(N, S, D, lex_ord != NULL, slots);
+        t.chunk = choose_chunk(N, D, lex_ord != NULL, (long long)cus * 4, waves_per_simd);
         // tuning overrides for experiments: PP_DP_CHUNK (candidates per wave), PP_DP_WPB (waves
         // per workgroup); the results do not depend on either
         if (const char *e = getenv("PP_DP_CHUNK")) { long long v = atoll(e); if (v >= 1) t.chunk = v; }

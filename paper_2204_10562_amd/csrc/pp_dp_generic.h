@@ -17,7 +17,7 @@ struct dp_args {
     const long long *PF, *PB, *XF, *XB;
     const int *ord;  // [N][S] explicit orderings
     int validate;    // the list came from the caller: check every row
-    const pp_ws_header *hdr;
+    pp_ws_header *hdr;
     const int *p32, *x32;
     unsigned short *arg;  // [nblocks][S][L+1] backtrack tables, one per working workgroup
     int nblocks;          // workgroups that take part (the rest of the grid returns)
@@ -67,6 +67,7 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
         else sP[l] = (V)((a.p32[l] << K) - l);
     }
 
+    unsigned long long pairs = 0, nrows = 0;  // work done by this workgroup (kept by thread 0)
     for (long long c = blockIdx.x; c < a.N; c += a.nblocks) {
         __syncthreads();
         if (!load_ordering(a, c, s_o, &s_ok)) {
@@ -128,7 +129,11 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
                 e = arg[n * (L + 1) + e];
             }
             a.bounds_out[c * S] = e;
+            for (int n = 1; n < S - 1; ++n) pairs += (unsigned long long)(L - n) * (L - n + 1) / 2;
+            if (S > 1) pairs += (unsigned long long)(L - S + 1);
+            nrows += S - 1;
         }
     }
+    if (tid == 0) pp_count_work(a.hdr, pairs, nrows, blockIdx.x);
 }
 

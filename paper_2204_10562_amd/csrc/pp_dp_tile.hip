@@ -115,6 +115,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     // lane q keeps the key of cell (S-1, L) of pending candidate q (-1: its ordering was bad)
     long long pend0 = c0;
     int pending = 0, v_top = 0;
+    unsigned long long pairs = 0, nrows = 0;  // work done by this wave
     int arena_used = 0;
     bool fresh = true;  // the arena was emptied: the next candidate must recompute every row
     int v_cur = 0;  // lane n: arena row holding the split indices of row n of the current path
@@ -267,6 +268,8 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                     acc[i] = min_over_b(acc[i]);
                     asm volatile("" : "+v"(acc[i]));
                 }
+                pairs += (unsigned long long)((L - n) * (L - n + 1) / 2);
+                ++nrows;
                 const int slot = arena_used++;
                 if (lane == n) v_cur = slot;
                 if (lb == 0) {
@@ -285,6 +288,8 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
 #pragma unroll
                 for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], Dp[i * (i + 1) / 2 + j]));
                 v = min_over_b(v);
+                pairs += (unsigned long long)(L - n);
+                ++nrows;
                 const int top = __builtin_amdgcn_readlane(v, top_lane);
                 // candidate finished: remember its key and the arena rows of its path
                 if (lane == pending) v_top = top;
@@ -322,6 +327,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         first = first_n;
     }
     if (pending) flush();
+    if (lane == 0) pp_count_work(a.g.hdr, pairs, nrows, (unsigned)wave);
 }
 
 template <int NT>

@@ -199,6 +199,33 @@ def test_dp_bad_orderings_fault(ppo, G):
         assert st == rc == ppo.FAULT_ORDERING
 
 
+def test_dp_work_counters(ppo, G):
+    from paper_2204_10562_amd import binding as pp
+    # generic kernel (L > 128): every row of every candidate is computed
+    w = workloads.random_small(601, 150, 6, 5, 37)
+    g = G(w)
+    g.set_tables(*oracle_tables(ppo, w))
+    say("work counters generic")
+    assert g.dp()[0] == 0
+    st = pp.read_workspace_stats(g.ws)
+    L, S, N = w.L, w.S, w.N
+    per = sum((L - n) * (L - n + 1) // 2 for n in range(1, S - 1)) + (L - S + 1)
+    assert st["pairs_executed"] == N * per and st["rows_executed"] == N * (S - 1)
+    # tiled kernel, all orderings in lexicographic order: shared rows are computed once,
+    # so the count lies between one row per distinct ordering prefix and the full count
+    w = workloads.transformer()
+    g = G(w)
+    assert g.prefix() == 0
+    say("work counters tiled")
+    assert g.dp()[0] == 0
+    st = pp.read_workspace_stats(g.ws)
+    L, S, N = w.L, w.S, w.N
+    full = N * (S - 1)
+    import math
+    trie = sum(math.factorial(8) // math.factorial(8 - n - 1) for n in range(1, S - 1)) + N
+    assert trie <= st["rows_executed"] < full // 2
+
+
 # ------------------------------------------------------------------ makespan
 
 def random_bounds(rng, N, S, L):
