@@ -172,32 +172,87 @@ __device__ __forceinline__ void finish(const mk_args &a, long long c, bool live,
 
 // ---------------------------------------------------------------- registers, S <= 16
 
+// One sweep restricted to blocks LO..HI (compile-time), no validity tests.
+template <int S, typename V, int LO, int HI>
+__device__ __forceinline__ void sweep_blocks(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1]) {
+    constexpr int R = 2 * S - 1, J = 2 * R - 1;
+    const V finR_prev = fin[R];
+    // forward blocks and the merged block R, descending so that fin[j-1] is still the
+    // previous sweep's value
+#pragma unroll
+    for (int j = R; j >= 1; --j) {
+        if (j < LO || j > HI) continue;
+        V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+        V ready = j > 1 ? fin[j - 1] : (V)0;
+        fin[j] = (idle > ready ? idle : ready) + dur[j];
+    }
+    // backward blocks: the resource may just have been used by this sweep's forward block
+#pragma unroll
+    for (int j = J; j >= R + 1; --j) {
+        if (j < LO || j > HI) continue;
+        V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+        V ready = j == R + 1 ? finR_prev : fin[j - 1];
+        fin[j] = (idle > ready ? idle : ready) + dur[j];
+    }
+}
+
+template <int S, typename V, int T>
+__device__ __forceinline__ void ramp_up(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1]) {
+    if constexpr (T <= 4 * S - 4) {
+        sweep_blocks<S, V, 1, T>(fin, dur);
+        ramp_up<S, V, T + 1>(fin, dur);
+    }
+}
+
+template <int S, typename V, int U>
+__device__ __forceinline__ void ramp_down(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1]) {
+    if constexpr (U <= 4 * S - 4) {
+        sweep_blocks<S, V, U + 1, 4 * S - 3>(fin, dur);
+        ramp_down<S, V, U + 1>(fin, dur);
+    }
+}
+
+// All M + 4S - 4 sweeps with the finish times in registers; returns the finish of the last
+// backward block on stage 0.  Block j works in sweep t iff t-M+1 <= j <= t.  When the
+// pipeline fills completely (M >= J-1) the sweeps split into a ramp-up (blocks 1..t), a
+// steady phase (all blocks) and a ramp-down (blocks t-M+1..J) whose block ranges are known at
+// compile time; otherwise every block update is selected by a per-lane compare.
 template <int S, typename V>
 __device__ __forceinline__ V sweep_regs(const long long (&dur64)[4 * S - 3 + 1], int M) {
     constexpr int R = 2 * S - 1, J = 2 * R - 1;
     V dur[J + 1], fin[J + 1];
 #pragma unroll
     for (int j = 1; j <= J; ++j) { dur[j] = (V)dur64[j]; fin[j] = 0; }
+    dur[0] = fin[0] = 0;
+    if constexpr (S <= 8) {
+        if (M >= J - 1) {
+            ramp_up<S, V, 1>(fin, dur);
+            for (int t = J; t <= M; ++t) sweep_blocks<S, V, 1, J>(fin, dur);
+            ramp_down<S, V, 1>(fin, dur);
+            return fin[J];
+        }
+    }
     const int sweeps = M + 2 * R - 2;
+    const unsigned width = (unsigned)(M - 1);
     for (int t = 1; t <= sweeps; ++t) {
-        const int jlo = t - M + 1;  // block j works in this sweep iff jlo <= j <= t
+        // j is in [t-M+1, t] iff (unsigned)(j - (t-M+1)) <= M-1; kept in a vector register so
+        // that the tests run on the vector unit next to the arithmetic
+        int jlo = t - M + 1;
+        asm volatile("" : "+v"(jlo));
         const V finR_prev = fin[R];
-        // forward blocks and the merged block R, descending so that fin[j-1] is still the
-        // previous sweep's value
 #pragma unroll
         for (int j = R; j >= 1; --j) {
             V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
             V ready = j > 1 ? fin[j - 1] : (V)0;
             V nv = (idle > ready ? idle : ready) + dur[j];
-            fin[j] = (j >= jlo && j <= t) ? nv : fin[j];
+            fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
         }
-        // backward blocks: the resource may just have been used by this sweep's forward block
 #pragma unroll
         for (int j = J; j >= R + 1; --j) {
             V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
             V ready = j == R + 1 ? finR_prev : fin[j - 1];
             V nv = (idle > ready ? idle : ready) + dur[j];
-            fin[j] = (j >= jlo && j <= t) ? nv : fin[j];
+            fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
         }
     }
     return fin[J];
