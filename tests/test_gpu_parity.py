@@ -372,3 +372,64 @@ def test_best_plan_large_shapes_subset(ppo, G, name, N):
     tables = oracle_tables(ppo, w)
     say("best_plan", name, N)
     check_best(ppo, g, w, w.Ms[-1], tables)
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+def plan_resource_times(w, PF, PB, XF, XB, orderings, bounds):
+    """Largest per-resource time (stage f+b, channel cf+cb) of every plan, vectorised."""
+    N, S = bounds.shape
+    P = PF + PB
+    e = np.concatenate([np.zeros((N, 1), np.int64), bounds.astype(np.int64)], axis=1)
+    comp = P[e[:, 1:]] - P[e[:, :-1]]
+    worst = comp.max(axis=1)
+    if S > 1:
+        link = orderings[:, :-1].astype(np.int64) * w.D + orderings[:, 1:].astype(np.int64)
+        at = link * w.L + (e[:, 1:-1] - 1)
+        chan = XF[at] + XB[at]
+        worst = np.maximum(worst, chan.max(axis=1))
+    return worst
+
+
+@pytest.mark.parametrize("name,stride", [("gpt", 1), ("hetero", 997), ("stress", 4099)])
+def test_whole_path_at_full_size(ppo, G, name, stride):
+    """The launch configuration bench.py times, at the configurations' full sizes: properties
+    that hold for every candidate, and the oracle on a sample (every stride-th candidate, the
+    winner and the 64 candidates with the smallest T)."""
+    w = workloads.CONFIGS[name]()
+    say("full size", name, "N", w.N)
+    g = G(w)
+    assert g.prefix() == 0
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    for a, b in ((g.PF, PF), (g.PB, PB), (g.XF, XF), (g.XB, XB)):
+        np.testing.assert_array_equal(a.cpu().numpy(), b)
+    M = w.Ms[-1]
+    st, C, bounds = g.dp()
+    assert st == 0
+    st, res, T, C2 = g.best(M)
+    assert st == 0
+    np.testing.assert_array_equal(C, C2)
+    orderings = w.explicit_orderings()
+    N, S, L = w.N, w.S, w.L
+    # every plan is a valid partition and C is its largest per-resource time
+    assert (bounds[:, -1] == L).all() and (bounds[:, 0] >= 1).all()
+    assert (np.diff(bounds.astype(np.int64), axis=1) >= 1).all()
+    np.testing.assert_array_equal(plan_resource_times(w, PF, PB, XF, XB, orderings, bounds), C)
+    total = int(PF[-1] + PB[-1])
+    assert (C >= -(-total // S)).all()
+    # Lemma 1: M*C <= T <= (M + 4S - 4)*C
+    assert (T >= M * C).all() and (T <= (M + 4 * S - 4) * C).all()
+    # the winner is the lowest index among the smallest T
+    best = int(np.argmin(T))
+    assert res["best_index"] == best and res["T"] == int(T[best]) and res["C"] == int(C[best])
+    assert res["bounds"] == bounds[best].tolist() and res["order"] == orderings[best].tolist()
+    # oracle on a sample
+    idx = np.unique(np.concatenate([np.arange(0, N, stride), [best], np.argsort(T, kind="stable")[:64]]))
+    sub = np.ascontiguousarray(orderings[idx])
+    rc, C0, b0 = ppo.partition_dp(L, w.D, S, len(idx), PF, PB, XF, XB, sub)
+    assert rc == 0
+    np.testing.assert_array_equal(C[idx], C0)
+    np.testing.assert_array_equal(bounds[idx], b0)
+    rc, T0 = ppo.schedule_makespan(L, w.D, S, len(idx), M, PF, PB, XF, XB, sub, b0)
+    assert rc == 0
+    np.testing.assert_array_equal(T[idx], T0)
