@@ -56,6 +56,7 @@ extern "C" {
 #define PP_MAX_STAGES 64
 #define PP_MAX_LAYERS 2048
 #define PP_MAX_DEVICES 1024
+#define PP_MAX_M_LIST 16 /* microbatch counts per pp_best_plan_multi call */
 
 /* Winner record written by pp_best_plan (device memory, 536 bytes). */
 typedef struct {
@@ -165,6 +166,26 @@ int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
                  const int32_t *orderings, pp_result *out, int64_t *T_all,
                  int64_t *C_all, void *workspace, size_t workspace_bytes,
                  int32_t *status, void *stream);
+
+/*
+ * pp_best_plan for several microbatch counts at once.  The partition (a
+ * plan's bounds and C) does not depend on M, because every term of the
+ * recursion for W carries the same factor M when nothing is replicated
+ * (Sec. IV-B); so the dynamic program runs once and only the schedule
+ * (Alg. 1) and the keep-the-minimum (Alg. 3) are repeated per M.
+ *   nM      number of microbatch counts, 1..PP_MAX_M_LIST
+ *   M_list  [nM] HOST array, every entry >= 1
+ *   out     [nM] pp_result, out[q] = winner for M_list[q]
+ *   T_all   [nM*N] (T of candidate c for M_list[q] at q*N + c) or NULL
+ *   C_all   [N] or NULL
+ * Same workspace size and faults as pp_best_plan.
+ */
+int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM,
+                       const int32_t *M_list, const int64_t *PF,
+                       const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                       const int32_t *orderings, pp_result *out, int64_t *T_all,
+                       int64_t *C_all, void *workspace, size_t workspace_bytes,
+                       int32_t *status, void *stream);
 
 /* Text for a PP_ERR_* code (host function, static storage). */
 const char *pp_strerror(int code);

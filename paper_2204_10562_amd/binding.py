@@ -24,7 +24,7 @@ PP_FAULT_OVERFLOW = 16
 PP_MAX_STAGES = 64
 
 EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
-           "pp_best_plan", "pp_strerror")
+           "pp_best_plan", "pp_best_plan_multi", "pp_strerror")
 
 
 class PPResult(ctypes.Structure):
@@ -67,6 +67,8 @@ def lib():
         L.pp_schedule_makespan.restype = i32
         L.pp_best_plan.argtypes = [i32, i32, i32, i64, i32] + [vp] * 8 + [vp, sz, vp, vp]
         L.pp_best_plan.restype = i32
+        L.pp_best_plan_multi.argtypes = [i32, i32, i32, i64, i32] + [vp] * 9 + [vp, sz, vp, vp]
+        L.pp_best_plan_multi.restype = i32
         L.pp_strerror.argtypes = [i32]
         L.pp_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -144,6 +146,22 @@ def pp_best_plan(L, D, S, N, M, PF, PB, XF, XB, orderings, out, T_all, C_all, wo
         _ptr(status, i32, 1, "status"), _stream()))
 
 
+def pp_best_plan_multi(L, D, S, N, M_list, PF, PB, XF, XB, orderings, out, T_all, C_all, workspace,
+                       status):
+    """M_list is a host sequence of ints; out holds len(M_list) pp_result records."""
+    i64, i32 = torch.int64, torch.int32
+    nM = len(M_list)
+    Ms = (ctypes.c_int32 * nM)(*[int(m) for m in M_list])
+    _check(lib().pp_best_plan_multi(
+        L, D, S, N, nM, ctypes.cast(Ms, ctypes.c_void_p), _ptr(PF, i64, L + 1, "PF"),
+        _ptr(PB, i64, L + 1, "PB"), _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(out, torch.uint8, RESULT_BYTES * nM, "out"),
+        _ptr(T_all, i64, N * nM, "T_all", optional=True), _ptr(C_all, i64, N, "C_all", optional=True),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
 PP_WS_PAIRS_EXECUTED = 1024
 PP_WS_ROWS_EXECUTED = 1536
 
@@ -156,9 +174,9 @@ def read_workspace_stats(workspace):
                 rows_executed=int(head[PP_WS_ROWS_EXECUTED // 8:PP_WS_ROWS_EXECUTED // 8 + 64].sum()))
 
 
-def read_result(out, S):
-    """Copy a device pp_result (uint8 tensor) to the host and unpack it."""
-    raw = bytes(out.cpu().numpy().tobytes()[:RESULT_BYTES])
+def read_result(out, S, index=0):
+    """Copy a device pp_result (uint8 tensor, record number `index`) to the host and unpack it."""
+    raw = bytes(out.cpu().numpy().tobytes()[index * RESULT_BYTES:(index + 1) * RESULT_BYTES])
     r = PPResult.from_buffer_copy(raw)
     return dict(best_index=int(r.best_index), T=int(r.T), C=int(r.C), S=int(r.S),
                 bounds=[int(r.bounds[i]) for i in range(S)],

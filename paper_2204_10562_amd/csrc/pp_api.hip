@@ -54,26 +54,27 @@ extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const
     int rc = pp_check_sizes(L, D, S, N, orderings);
     if (rc) return rc;
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
-    return pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out, status,
-                              NULL, NULL, NULL, NULL, (hipStream_t)stream);
+    return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
+                              status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
-extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
-                            const int64_t *PB, const int64_t *XF, const int64_t *XB,
-                            const int32_t *orderings, pp_result *out, int64_t *T_all,
-                            int64_t *C_all, void *workspace, size_t workspace_bytes,
-                            int32_t *status, void *stream) {
+extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const int32_t *M_list,
+                                  const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                                  const int64_t *XB, const int32_t *orderings, pp_result *out,
+                                  int64_t *T_all, int64_t *C_all, void *workspace,
+                                  size_t workspace_bytes, int32_t *status, void *stream) {
     int rc = pp_check_sizes(L, D, S, N, orderings);
     if (rc) return rc;
-    if (M < 1 || !PF || !PB || !XF || !XB || !out) return PP_ERR_INVALID_ARG;
+    if (nM < 1 || nM > PP_MAX_M_LIST || !M_list || !PF || !PB || !XF || !XB || !out)
+        return PP_ERR_INVALID_ARG;
+    for (int q = 0; q < nM; ++q)
+        if (M_list[q] < 1) return PP_ERR_INVALID_ARG;
     pp_ws_layout lay = pp_layout(L, D, S, N);
     rc = check_ws(workspace, workspace_bytes, lay);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     char *base = (char *)workspace;
     int64_t *C = C_all ? C_all : (int64_t *)(base + lay.C);
-    int64_t *T = T_all;
-    if (!T && S > 16) T = (int64_t *)(base + lay.T);  // the LDS kernel may need T in memory
     int32_t *bounds = (int32_t *)(base + lay.bounds);
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
@@ -82,8 +83,19 @@ extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t
                       workspace, lay, status, st);
     if (rc) return rc;
     pp_ws_header *hdr = (pp_ws_header *)(base + lay.hdr);
-    return pp_launch_makespan(L, D, S, N, M, PF, PB, XF, XB, ord, bounds, T, status, C,
-                              base + lay.part, &hdr->ticket, out, st);
+    return pp_launch_makespan(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, T_all,
+                              (int64_t *)(base + lay.T), status, C, base + lay.part, hdr->ticket,
+                              out, st);
+}
+
+extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                            const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                            const int32_t *orderings, pp_result *out, int64_t *T_all,
+                            int64_t *C_all, void *workspace, size_t workspace_bytes,
+                            int32_t *status, void *stream) {
+    if (M < 1) return PP_ERR_INVALID_ARG;
+    return pp_best_plan_multi(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, out, T_all, C_all,
+                              workspace, workspace_bytes, status, stream);
 }
 
 extern "C" const char *pp_strerror(int code) {

@@ -25,8 +25,8 @@ static inline int pp_index_bits(int L) {
 #define PP_PACK_BLOCKS 64
 struct pp_ws_header {
     unsigned long long pmax[PP_PACK_BLOCKS];  // byte 0
-    unsigned ticket;  // byte 512: arrival counter of the arg-min, zeroed by the pack kernel
-    unsigned pad0[127];
+    unsigned ticket[65];  // byte 512: arrival counters of the arg-min, zeroed by the pack kernel
+    unsigned pad0[63];
     // byte 1024: (cell, split) pairs the partition DP actually evaluated in this call (rows
     // shared between candidates are counted once), spread over 64 counters to keep the
     // atomics apart; byte 1536: DP rows computed (the single-cell last row counts too).
@@ -65,7 +65,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.bounds = off; off += pp_align256((size_t)N * S * 4);
     w.C = off;      off += pp_align256((size_t)N * 8);
     w.T = off;      off += pp_align256((size_t)N * 8);
-    w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16);
+    w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16 * PP_MAX_M_LIST);
     w.total = off;
     return w;
 }
@@ -85,17 +85,19 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
                  const int32_t *user_ord, int64_t *C_out, int32_t *bounds_out, void *ws,
                  const pp_ws_layout &lay, int32_t *status, hipStream_t st);
-// Makespan of every candidate's plan.  With part/ticket/C/out non-NULL the launch also finds
-// the candidate with the smallest T (lowest index on ties) and fills *out; *ticket must be 0
-// when the kernel starts.  T_out may then be NULL.
-int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
-                       const int64_t *XF, const int64_t *XB, const int32_t *orderings,
-                       const int32_t *bounds, int64_t *T_out, int32_t *status, const int64_t *C,
-                       void *part, unsigned *ticket, pp_result *out, hipStream_t st);
+// Makespan of every candidate's plan for each of the nM microbatch counts in Ms (host array).
+// With part/ticket/C/out non-NULL the launch also finds, per microbatch count, the candidate
+// with the smallest T (lowest index on ties) and fills out[q]; *ticket must be 0 when the
+// kernel starts (it is 0 again when it ends).  T_out ([nM][N]) may then be NULL; T_scratch
+// ([N]) is needed for S > 16 in that case.
+int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
+                       const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                       const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
+                       int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
+                       unsigned *ticket, pp_result *out, hipStream_t st);
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
                      unsigned *ticket, pp_result *out, hipStream_t st);
-size_t pp_argmin_part_bytes(int64_t N);
 
 // Largest time in the tables (all lanes of a full wave must call; result is uniform).
 __device__ __forceinline__ unsigned long long pp_vmax(const pp_ws_header *hdr) {

@@ -14,8 +14,12 @@
 // candidate and all lanes run the same uniform loop.
 //
 // Two kernels: for S <= 16 the 4S-3 durations and finish times of a lane live in registers
-// (blocks fully unrolled, 32-bit when the bound (M+4S-4) * largest block of Lemma 1 fits,
-// else 64-bit, decided per wave); for larger S they live in the lane's own LDS column.
+// (blocks unrolled; when the pipeline fills, the block ranges of the ramp-up, steady and
+// ramp-down sweeps are compile-time constants, otherwise each update is selected by a
+// per-lane test of the sweep's window of working blocks; 32-bit when the bound
+// (M+4S-4) * largest block of Lemma 1 fits, else 64-bit, decided per wave; several
+// microbatch counts run side by side in one launch); for larger S they live in the lane's
+// own LDS column.
 // When asked to, each wave also reduces (T, candidate) to its minimum and the last wave to
 // finish reduces the per-wave minima to the winner record.
 #include "pp_common.h"
@@ -23,18 +27,19 @@
 struct tc_pair { long long T, c; };
 
 struct mk_args {
-    int L, D, S, M;
+    int L, D, S, nM;
+    int Ms[PP_MAX_M_LIST];  // microbatch counts; the plans are evaluated once per entry
     long long N;
     const long long *PF, *PB, *XF, *XB;
     const int *orderings;  // NULL = all D! orderings, candidate index = lexicographic rank
     const int *bounds;
-    long long *T_out;      // may be NULL when only the winner is wanted
+    long long *T_out;      // [nM][N]; may be NULL when only the winners are wanted
     int32_t *status;
     // arg-min (all NULL when not wanted)
-    tc_pair *part;         // one entry per wave
-    unsigned *ticket;      // zeroed before the launch
+    tc_pair *part;         // [nM][waves]
+    unsigned *ticket;      // 1 + 64 counters, all 0 when the kernel starts and again when it ends
     const long long *C;
-    pp_result *out;
+    pp_result *out;        // [nM]
 };
 
 __device__ __forceinline__ tc_pair tc_min(tc_pair a, tc_pair b) {
@@ -111,63 +116,86 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
             put(2 * R - (r - 1), cb);
         }
     }
-    // the schedule is no longer than (M + 4S - 4) * C (Lemma 1)
-    if (live && !fault && worst > (PP_CAP62 - 1) / ((long long)a.M + 4 * S - 4))
-        fault |= PP_FAULT_OVERFLOW;
     return fault;
 }
 
-// Writes T, raises faults, and (if wanted) takes part in the arg-min.
-__device__ __forceinline__ void finish(const mk_args &a, long long c, bool live, int fault,
-                                       long long T, long long wave_id, long long n_waves) {
+// The schedule is no longer than (M + 4S - 4) * C (Lemma 1): fault if that bound reaches 2^62.
+__device__ __forceinline__ int overflow_fault(long long worst, int M, int S) {
+    return worst > (PP_CAP62 - 1) / ((long long)M + 4 * S - 4) ? PP_FAULT_OVERFLOW : 0;
+}
+
+// Writes T of microbatch count q, raises faults, and (if wanted) leaves the wave's minimum.
+__device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool live, int fault,
+                                     long long T, long long wave_id, long long n_waves) {
     if (live) {
         if (fault) { T = PP_INF64; pp_raise(a.status, fault); }
-        if (a.T_out) a.T_out[c] = T;
+        if (a.T_out) a.T_out[(long long)q * a.N + c] = T;
     }
     if (!a.part) return;
-    const int lane = threadIdx.x & 63;
     tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
     v = wave_tc_min(v);
+    if ((threadIdx.x & 63) == 0) a.part[(long long)q * n_waves + wave_id] = v;
+}
+
+// After a wave has emitted its minima: the last of the `arrivals` waves of the launch to get
+// here reduces all of them (n_waves per microbatch count) to the winner records.
+__device__ __forceinline__ void conclude(const mk_args &a, long long n_waves, long long arrivals) {
+    if (!a.part) return;
+    const int lane = threadIdx.x & 63;
     unsigned last = 0;
     if (lane == 0) {
-        a.part[wave_id] = v;
+        // Arrival counting in two levels, so that thousands of waves do not queue on one
+        // address: wave w counts on sub-counter w % 64; whoever completes a sub-counter counts
+        // on the top counter; whoever completes that one has seen every wave arrive.
+        const unsigned long long w = (unsigned long long)blockIdx.y * gridDim.x + blockIdx.x;
+        const unsigned sub = (unsigned)(w & 63);
+        const unsigned quota = (unsigned)((arrivals - sub + 63) / 64);
+        const unsigned groups = arrivals < 64 ? (unsigned)arrivals : 64u;
         __threadfence();
-        last = atomicAdd(a.ticket, 1u) == (unsigned)(n_waves - 1);
+        if (atomicAdd(a.ticket + 1 + sub, 1u) == quota - 1) {
+            __threadfence();
+            last = atomicAdd(a.ticket, 1u) == groups - 1;
+        }
     }
     last = __builtin_amdgcn_readfirstlane(last);
     if (!last) return;
-    // the last wave to arrive sees every partial minimum
     __threadfence();
-    tc_pair w = {PP_INF64, INT64_MAX};
-    for (long long i = lane; i < n_waves; i += 64) {
-        tc_pair o;
-        o.T = __builtin_nontemporal_load(&a.part[i].T);
-        o.c = __builtin_nontemporal_load(&a.part[i].c);
-        w = tc_min(w, o);
-    }
-    w = wave_tc_min(w);
-    const bool none = w.T == PP_INF64;
     const int S = a.S;
-    if (lane == 0) {
-        a.out->best_index = none ? -1 : w.c;
-        a.out->T = w.T;
-        a.out->C = none ? PP_INF64 : a.C[w.c];
-        a.out->S = S;
-    }
-    // lane n writes bound n and device n (lanes S.. write zeros)
-    int b = 0, o = 0;
-    if (lane < S && !none) {
-        b = a.bounds[w.c * S + lane];
-        if (a.orderings) {
-            o = a.orderings[w.c * S + lane];
-        } else {
-            unsigned long long rem = (unsigned long long)w.c;
-            unsigned used = 0;
-            for (int n = 0; n <= lane; ++n) o = pp_unrank_next(a.D, n, rem, used);
+    for (int q = 0; q < a.nM; ++q) {
+        tc_pair w = {PP_INF64, INT64_MAX};
+        const tc_pair *part = a.part + (long long)q * n_waves;
+        for (long long i = lane; i < n_waves; i += 64) {
+            tc_pair o;
+            o.T = __builtin_nontemporal_load(&part[i].T);
+            o.c = __builtin_nontemporal_load(&part[i].c);
+            w = tc_min(w, o);
         }
+        w = wave_tc_min(w);
+        const bool none = w.T == PP_INF64;
+        pp_result *out = a.out + q;
+        if (lane == 0) {
+            out->best_index = none ? -1 : w.c;
+            out->T = w.T;
+            out->C = none ? PP_INF64 : a.C[w.c];
+            out->S = S;
+        }
+        // lane n writes bound n and device n (lanes S.. write zeros)
+        int b = 0, o = 0;
+        if (lane < S && !none) {
+            b = a.bounds[w.c * S + lane];
+            if (a.orderings) {
+                o = a.orderings[w.c * S + lane];
+            } else {
+                unsigned long long rem = (unsigned long long)w.c;
+                unsigned used = 0;
+                for (int n = 0; n <= lane; ++n) o = pp_unrank_next(a.D, n, rem, used);
+            }
+        }
+        out->bounds[lane] = b;
+        out->order[lane] = o;
     }
-    a.out->bounds[lane] = b;
-    a.out->order[lane] = o;
+    a.ticket[lane] = 0;  // ready for the next launch
+    if (lane == 0) a.ticket[64] = 0;
 }
 
 // ---------------------------------------------------------------- registers, S <= 16
@@ -266,13 +294,18 @@ __global__ __launch_bounds__(64) void k_makespan_regs(mk_args a) {
     const bool live = c < a.N;
     long long dur[J + 1];
     long long worst;
-    int fault = gather_durations<S>(a, c, live, worst, [&](int j, long long d) { dur[j] = d; });
+    const int fault = gather_durations<S>(a, c, live, worst, [&](int j, long long d) { dur[j] = d; });
+    // blockIdx.y selects the microbatch count: the counts run side by side, not in a loop
+    const int q = blockIdx.y;
+    const int M = a.Ms[q];
+    const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
     // 32-bit arithmetic if no finish time of any lane can reach 2^31
-    const bool narrow = fault || !live || worst <= (long long)0x7fffffff / ((long long)a.M + 4 * S - 4);
+    const bool narrow = fq || !live || worst <= (long long)0x7fffffff / ((long long)M + 4 * S - 4);
     long long T;
-    if (__all(narrow)) T = (long long)sweep_regs<S, int>(dur, a.M);
-    else T = sweep_regs<S, long long>(dur, a.M);
-    finish(a, c, live, fault, T, blockIdx.x, gridDim.x);
+    if (__all(narrow)) T = (long long)sweep_regs<S, int>(dur, M);
+    else T = sweep_regs<S, long long>(dur, M);
+    emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x);
+    conclude(a, gridDim.x, (long long)gridDim.x * gridDim.y);
 }
 
 // ---------------------------------------------------------------- LDS columns, any S
@@ -283,7 +316,7 @@ __global__ __launch_bounds__(64) void k_makespan_regs(mk_args a) {
 __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
     extern __shared__ long long sm[];
     const int lane = threadIdx.x, W = blockDim.x;
-    const int S = a.S, M = a.M;
+    const int S = a.S;
     const int R = 2 * S - 1, J = 2 * R - 1;
     // rows 0..J-1: duration of block j = row+1; rows J..2J-1: its latest finish time
     long long *dur = sm + lane;
@@ -291,8 +324,11 @@ __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
     const long long c = (long long)blockIdx.x * W + lane;
     const bool live = c < a.N;
     long long worst;
-    int fault = gather_durations<0>(a, c, live, worst,
-                                    [&](int j, long long d) { dur[(size_t)(j - 1) * W] = d; });
+    const int fault = gather_durations<0>(a, c, live, worst,
+                                          [&](int j, long long d) { dur[(size_t)(j - 1) * W] = d; });
+  for (int q = 0; q < a.nM; ++q) {
+    const int M = a.Ms[q];
+    const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
     for (int j = 1; j <= J; ++j) fin[(size_t)(j - 1) * W] = 0;
 
     const int sweeps = M + 2 * R - 2;
@@ -310,28 +346,29 @@ __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
             fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
         }
     }
-    // with fewer than 64 lanes the arg-min below would need another reduction; the host only
-    // asks for it when W == 64
-    finish(a, c, live, fault, fin[(size_t)(J - 1) * W], blockIdx.x, gridDim.x);
+    // with fewer than 64 lanes the arg-min would need another reduction; the host only asks
+    // for it when W == 64
+    emit(a, q, c, live, fq, fin[(size_t)(J - 1) * W], blockIdx.x, gridDim.x);
+  }
+    conclude(a, gridDim.x, gridDim.x);
 }
 
 template <int S>
 static int launch_regs(const mk_args &a, hipStream_t st) {
     unsigned grid = (unsigned)((a.N + 63) / 64);
-    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid), dim3(64), 0, st, a);
+    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, a.nM), dim3(64), 0, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
-// one tc_pair per wave of 64 candidates
-size_t pp_argmin_part_bytes(int64_t N) { return (size_t)((N + 63) / 64) * sizeof(tc_pair); }
-
-int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF, const int64_t *PB,
-                       const int64_t *XF, const int64_t *XB, const int32_t *orderings,
-                       const int32_t *bounds, int64_t *T_out, int32_t *status,
-                       const int64_t *C, void *part, unsigned *ticket, pp_result *out,
-                       hipStream_t st) {
+int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
+                       const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                       const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
+                       int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
+                       unsigned *ticket, pp_result *out, hipStream_t st) {
     mk_args a;
-    a.L = L; a.D = D; a.S = S; a.M = M; a.N = N;
+    a.L = L; a.D = D; a.S = S; a.N = N;
+    a.nM = nM;
+    for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;
     a.XF = (const long long *)XF; a.XB = (const long long *)XB;
     a.orderings = orderings; a.bounds = bounds;
@@ -349,13 +386,21 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
     size_t lds = (size_t)2 * J * W * 8;
     unsigned grid = (unsigned)((N + W - 1) / W);
     if (W != 64 && part) {
-        // narrow workgroups: T goes to memory and a separate pass finds the minimum
-        mk_args b = a;
-        b.part = NULL; b.ticket = NULL; b.C = NULL; b.out = NULL;
-        if (!b.T_out) return PP_ERR_INVALID_ARG;
-        hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, b);
-        if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-        return pp_launch_argmin(D, S, N, T_out, C, bounds, orderings, part, ticket, out, st);
+        // narrow workgroups: per microbatch count, T goes to memory and a separate pass finds
+        // the minimum
+        for (int q = 0; q < nM; ++q) {
+            mk_args b = a;
+            b.nM = 1; b.Ms[0] = Ms[q];
+            b.part = NULL; b.ticket = NULL; b.C = NULL; b.out = NULL;
+            b.T_out = T_out ? (long long *)T_out + (long long)q * N : (long long *)T_scratch;
+            if (!b.T_out) return PP_ERR_INVALID_ARG;
+            hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, b);
+            if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+            int rc = pp_launch_argmin(D, S, N, (const int64_t *)b.T_out, C, bounds, orderings, part,
+                                      ticket, out + q, st);
+            if (rc) return rc;
+        }
+        return PP_OK;
     }
     hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
@@ -371,18 +416,21 @@ __global__ __launch_bounds__(64) void k_argmin(mk_args a) {
         tc_pair o = {a.T_out[c], c};
         v = tc_min(v, o);
     }
-    // reuse finish(): it reduces over the wave, so hand it this lane's minimum as if it were
-    // the lane's own candidate; T_out must not be rewritten
+    // emit() reduces over the wave: hand it this lane's minimum as if it were the lane's own
+    // candidate; T_out must not be rewritten
     mk_args b = a;
     b.T_out = NULL;
-    finish(b, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
+    emit(b, 0, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
+    conclude(b, gridDim.x, gridDim.x);
 }
 
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
                      unsigned *ticket, pp_result *out, hipStream_t st) {
     mk_args a;
-    a.L = 0; a.D = D; a.S = S; a.M = 1; a.N = N;
+    a.L = 0; a.D = D; a.S = S; a.N = N;
+    a.nM = 1;
+    for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = 1;
     a.PF = a.PB = a.XF = a.XB = NULL;
     a.orderings = orderings; a.bounds = bounds;
     a.T_out = (long long *)T; a.status = NULL;

@@ -78,3 +78,17 @@ class GpuProblem:
         res = pp.read_result(out, S)
         return (self.take_status(), res, None if T is None else T.cpu().numpy(),
                 None if C is None else C.cpu().numpy())
+
+    def best_multi(self, Ms, orderings="default", N=None, S=None, want_all=True):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        nM = len(Ms)
+        out = torch.zeros(pp.RESULT_BYTES * nM, dtype=torch.uint8, device=self.dev)
+        T = torch.empty(N * nM, dtype=torch.int64, device=self.dev) if want_all else None
+        C = torch.empty(N, dtype=torch.int64, device=self.dev) if want_all else None
+        pp.pp_best_plan_multi(w.L, w.D, S, N, list(Ms), self.PF, self.PB, self.XF, self.XB, o, out, T, C,
+                              self.workspace(N, S), self.status)
+        res = [pp.read_result(out, S, q) for q in range(nM)]
+        return (self.take_status(), res, None if T is None else T.cpu().numpy().reshape(nM, N),
+                None if C is None else C.cpu().numpy())

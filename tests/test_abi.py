@@ -70,3 +70,8 @@ def test_host_side_argument_errors_enqueue_nothing(libpp):
     assert libpp.pp_partition_dp(16, 4, 4, 24, one, one, one, one, z, one, one, ctypes.c_void_p(264), 1 << 30, z, z) == -2
     assert libpp.pp_schedule_makespan(16, 4, 4, 24, 0, one, one, one, one, z, one, one, z, z) == -1
     assert libpp.pp_best_plan(16, 4, 4, 24, 4, one, one, one, one, z, z, z, z, one, 1 << 30, z, z) == -1
+    Ms = (ctypes.c_int32 * 2)(4, 0)
+    mp = ctypes.cast(Ms, ctypes.c_void_p)
+    assert libpp.pp_best_plan_multi(16, 4, 4, 24, 2, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1  # M = 0
+    assert libpp.pp_best_plan_multi(16, 4, 4, 24, 17, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1
+    assert libpp.pp_best_plan_multi(16, 4, 4, 24, 0, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1

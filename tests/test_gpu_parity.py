@@ -374,6 +374,54 @@ def test_best_plan_large_shapes_subset(ppo, G, name, N):
     check_best(ppo, g, w, w.Ms[-1], tables)
 
 
+def check_best_multi(ppo, g, w, Ms, tables):
+    PF, PB, XF, XB = tables
+    st, res, T, C = g.best_multi(Ms)
+    assert st == 0
+    for q, M in enumerate(Ms):
+        rc, res0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, M, PF, PB, XF, XB, w.orderings)
+        assert rc == 0
+        np.testing.assert_array_equal(T[q], T0)
+        np.testing.assert_array_equal(C, C0)
+        assert res[q] == res0
+    st, res2, _, _ = g.best_multi(Ms, want_all=False)
+    assert st == 0 and res2 == res
+
+
+@pytest.mark.parametrize("name", ["tiny", "transformer", "gpt"])
+def test_best_plan_multi_full_configs(ppo, G, name):
+    w = workloads.CONFIGS[name]()
+    g = G(w)
+    assert g.prefix() == 0
+    say("best_plan_multi", name, w.Ms)
+    check_best_multi(ppo, g, w, w.Ms, oracle_tables(ppo, w))
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL)
+def test_best_plan_multi_adversarial_small(ppo, G, seed, L, D, S, N):
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    Ms = (1, 2, 3, 5, 8, 13, 21, 34, 55, 89, 144, 4, 6, 7, 9, 10)  # 16 = the most one call takes
+    say("best_plan_multi small", seed, L, D, S, N)
+    check_best_multi(ppo, g, w, Ms, tables)
+
+
+def test_best_plan_multi_overflow_is_per_M(ppo, G):
+    w = workloads.random_small(701, 20, 5, 4, 40)
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    PF2 = PF.copy(); PF2[1:] += 1 << 55
+    g = G(w)
+    g.set_tables(PF2, PB, XF, XB)
+    say("best_plan_multi overflow")
+    st, res, T, C = g.best_multi((2, 200))
+    assert st == ppo.FAULT_OVERFLOW
+    rc, res0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, 2, PF2, PB, XF, XB, w.orderings)
+    assert rc == 0 and res[0] == res0
+    np.testing.assert_array_equal(T[0], T0)
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 
 def plan_resource_times(w, PF, PB, XF, XB, orderings, bounds):
