@@ -119,7 +119,9 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
                 }
             }
         }
-        __threadfence();
+        // the backtrack table was written by the whole workgroup and is read by thread 0: a
+        // workgroup-scope fence is enough (and much cheaper than a device-scope one)
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
         __syncthreads();
         if (tid == 0) {
             a.C_out[c] = WIDE ? (long long)sW[L] : (long long)((int)sW[L] >> K);

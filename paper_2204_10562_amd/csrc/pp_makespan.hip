@@ -134,7 +134,16 @@ __device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool 
     if (!a.part) return;
     tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
     v = wave_tc_min(v);
-    if ((threadIdx.x & 63) == 0) a.part[(long long)q * n_waves + wave_id] = v;
+    if ((threadIdx.x & 63) == 0) {
+        // Device-scope exchanges instead of plain stores plus a release fence: a fence at
+        // device scope writes back the whole L2 of the wave's XCD, and thousands of waves doing
+        // that one after another cost more than the schedule itself.  An exchange is performed
+        // at the coherent point, and its return value tells when.
+        tc_pair *slot = a.part + ((long long)q * n_waves + wave_id);
+        long long r0 = __hip_atomic_exchange(&slot->T, v.T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        long long r1 = __hip_atomic_exchange(&slot->c, v.c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" ::"v"(r0), "v"(r1));  // both have returned before anything below is issued
+    }
 }
 
 // After a wave has emitted its minima: the last of the `arrivals` waves of the launch to get
@@ -151,23 +160,20 @@ __device__ __forceinline__ void conclude(const mk_args &a, long long n_waves, lo
         const unsigned sub = (unsigned)(w & 63);
         const unsigned quota = (unsigned)((arrivals - sub + 63) / 64);
         const unsigned groups = arrivals < 64 ? (unsigned)arrivals : 64u;
-        __threadfence();
-        if (atomicAdd(a.ticket + 1 + sub, 1u) == quota - 1) {
-            __threadfence();
-            last = atomicAdd(a.ticket, 1u) == groups - 1;
-        }
+        // this wave's exchanges in emit() have returned, so they precede these increments
+        if (__hip_atomic_fetch_add(a.ticket + 1 + sub, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == quota - 1)
+            last = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == groups - 1;
     }
     last = __builtin_amdgcn_readfirstlane(last);
     if (!last) return;
-    __threadfence();
     const int S = a.S;
     for (int q = 0; q < a.nM; ++q) {
         tc_pair w = {PP_INF64, INT64_MAX};
         const tc_pair *part = a.part + (long long)q * n_waves;
         for (long long i = lane; i < n_waves; i += 64) {
             tc_pair o;
-            o.T = __builtin_nontemporal_load(&part[i].T);
-            o.c = __builtin_nontemporal_load(&part[i].c);
+            o.T = __hip_atomic_load(&part[i].T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            o.c = __hip_atomic_load(&part[i].c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             w = tc_min(w, o);
         }
         w = wave_tc_min(w);
@@ -194,8 +200,9 @@ __device__ __forceinline__ void conclude(const mk_args &a, long long n_waves, lo
         out->bounds[lane] = b;
         out->order[lane] = o;
     }
-    a.ticket[lane] = 0;  // ready for the next launch
-    if (lane == 0) a.ticket[64] = 0;
+    // ready for the next launch (ordered by the kernel boundary)
+    __hip_atomic_store(a.ticket + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) __hip_atomic_store(a.ticket + 64, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------- registers, S <= 16
