@@ -64,11 +64,44 @@ __device__ void pack_xkt(const pack_args &a, unsigned first, unsigned stride) {
     }
 }
 
+// Row c of the explicit list = the ordering of lexicographic rank c.  Its factorial-number
+// digits come out least significant first by dividing by 1, 2, 3, ...: digit n (counted from
+// the front) = (c / (D-1-n)!) mod (D-n); digit n selects the digit-th smallest unused device.
+// 32-bit arithmetic when D! fits (D <= 12).
 __device__ void unrank_rows(const pack_args &a, long long first, long long stride) {
+    const int D = a.D;
     for (long long c = first; c < a.N; c += stride) {
-        unsigned long long rem = (unsigned long long)c;
+        unsigned long long digits = 0;  // 5 bits per digit: digits 0..11 here, 12..19 in digits_hi
+        unsigned long long digits_hi = 0;
+        if (D <= 12) {
+            unsigned rem = (unsigned)c;
+            for (int i = 1; i <= D; ++i) {  // i = D - n
+                unsigned q = rem / (unsigned)i;
+                unsigned long long dg = rem - q * (unsigned)i;
+                rem = q;
+                digits |= dg << (5 * (D - i));
+            }
+        } else {
+            unsigned long long rem = (unsigned long long)c;
+            for (int i = 1; i <= D; ++i) {
+                unsigned long long q = rem / (unsigned long long)i;
+                unsigned long long dg = rem - q * (unsigned long long)i;
+                rem = q;
+                int n = D - i;
+                if (n < 12) digits |= dg << (5 * n);
+                else digits_hi |= dg << (5 * (n - 12));
+            }
+        }
         unsigned used = 0;
-        for (int n = 0; n < a.S; ++n) a.ord[c * a.S + n] = pp_unrank_next(a.D, n, rem, used);
+        for (int n = 0; n < D; ++n) {
+            int digit = (int)(((n < 12 ? digits >> (5 * n) : digits_hi >> (5 * (n - 12)))) & 31);
+            // digit-th zero bit of `used`
+            unsigned freeb = ~used;
+            for (int k = 0; k < digit; ++k) freeb &= freeb - 1;
+            int dev = __builtin_ctz(freeb);
+            used |= 1u << dev;
+            a.ord[c * D + n] = dev;
+        }
     }
 }
 

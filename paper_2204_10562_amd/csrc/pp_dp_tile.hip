@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
             if (n == 0) break;
             // split index stored with cell (n, e): the key itself for the last row
             int nxt = v_top & kmask;
-            if (n < S - 1 && live && !bad) nxt = arena[(int)slots[lane * S + n] * RB + e];
+            if (n < S - 1 && live && !bad) nxt = arena[(int)slots[lane * S + n] * RB + e] & kmask;
             e = (live && !bad) ? nxt : 0;
         }
         pend0 += pending;
@@ -219,10 +219,11 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         int first_n = -2, v_link_n = 0;  // next candidate: -2 none, -1 bad ordering
         bool flush_after = false;
 
-        for (int n = first; n < S; ++n) {
-            // Fetch the channel keys of the row computed next while this one is computed.
-            // After the last row that is the first row of the next candidate (looked at
-            // here), or, if there is none, this row's keys once more.
+        // One DP row.  xc holds this row's channel keys; the keys of the row computed next are
+        // fetched into xf while this one is computed.  After the candidate's last row that is
+        // the first row of the next candidate (looked at here), or, if there is none, this
+        // row's keys once more.
+        auto row = [&](int n, int (&xc)[NT], int (&xf)[NT]) __attribute__((always_inline)) {
             int next_link = __builtin_amdgcn_readlane(v_link, n + 1 < S ? n + 1 : n);
             if (n == S - 1 && more) {
                 v_prev = v_o;
@@ -238,8 +239,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                     next_link = __builtin_amdgcn_readlane(v_link_n, first_n);
                 }
             }
-            int xn[NT];
-            fetch_x(xn, next_link);
+            fetch_x(xf, next_link);
 
             const int *prow = rows + (n - 1) * RS;
             int *nrow = rows + n * RS;
@@ -250,9 +250,11 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
             for (int j = 0; j < NT; ++j) asm volatile("" : "+v"(g[j]));  // all reads in flight at once
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
-                // previous row's time with this split's index in the low bits, then the channel
-                int wk = (g[j] & ~kmask) | (xk[j] & kmask);
-                g[j] = imax(wk, xk[j]);
+                // previous row's time with this split's index (the low bits of the channel
+                // key) in the low bits, then the larger of that and the channel key
+                int wk;
+                asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(wk) : "s"(kmask), "v"(xc[j]), "v"(g[j]));
+                g[j] = imax(wk, xc[j]);
             }
             if (n < S - 1) {
                 int acc[NT];
@@ -277,7 +279,8 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
 #pragma unroll
                     for (int i = 0; i < NT; ++i) {
                         nrow[8 * i + la + 1] = acc[i];
-                        arow[8 * i + la + 1] = (unsigned char)(acc[i] & kmask);
+                        // low byte of the key: the split index in its low K <= 7 bits
+                        arow[8 * i + la + 1] = (unsigned char)acc[i];
                     }
                 }
                 lds_sync();
@@ -296,8 +299,19 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                 if (lane < S) slots[pending * S + lane] = (unsigned char)v_cur;
                 ++pending;
             }
+        };
+        // rows alternate between the two key buffers, so that no row has to copy them; only a
+        // candidate with an odd number of rows moves the last fetch into xk once
+        int xn[NT];
+        for (int n = first;;) {
+            row(n, xk, xn);
+            if (++n >= S) {
 #pragma unroll
-            for (int j = 0; j < NT; ++j) xk[j] = xn[j];
+                for (int j = 0; j < NT; ++j) xk[j] = xn[j];
+                break;
+            }
+            row(n, xn, xk);
+            if (++n >= S) break;
         }
 
         if (flush_after) flush();

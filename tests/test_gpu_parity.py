@@ -126,6 +126,23 @@ def test_dp_explicit_orderings_equal_default(ppo, G):
     np.testing.assert_array_equal(b, b2)
 
 
+def test_dp_nine_devices_default_orderings(ppo, G):
+    # 9! = 362880 candidates generated on the device in lexicographic order
+    import math
+    w = workloads.random_small(801, 14, 9, 9, 1, hi_time=30, hi_act=2000)
+    w.orderings = None
+    w.N = math.factorial(9)
+    say("partition_dp D=9 all orderings")
+    g = G(w)
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    g.set_tables(PF, PB, XF, XB)
+    st, C, bounds = g.dp()
+    rc, C0, b0 = ppo.partition_dp(w.L, w.D, w.S, w.N, PF, PB, XF, XB, workloads.all_orderings(9))
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(bounds, b0)
+
+
 @pytest.mark.parametrize("name,N", [("hetero", 3000), ("stress", 600)])
 def test_dp_large_shapes_subset(ppo, G, name, N):
     w = workloads.CONFIGS[name](N=N)
