@@ -49,7 +49,7 @@ struct pp_ws_layout {
 };
 
 #define PP_TILE_MAX_L 128
-#define PP_DP_SLOTS 2048
+#define PP_DP_SLOTS 4096
 
 static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     pp_ws_layout w;
@@ -61,7 +61,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.xkt = off;    off += pp_align256((size_t)D * D * 8 * w.nt * 4);
     w.ord = off;    off += pp_align256((size_t)N * S * 4);
     w.slots = (int)(N < PP_DP_SLOTS ? N : PP_DP_SLOTS);
-    w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 1) * 2);
+    w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 128) * 2);  // rows padded to 128 cells
     w.bounds = off; off += pp_align256((size_t)N * S * 4);
     w.C = off;      off += pp_align256((size_t)N * 8);
     w.T = off;      off += pp_align256((size_t)N * 8);

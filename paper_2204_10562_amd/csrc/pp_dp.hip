@@ -271,6 +271,17 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         t.g = a;
         return pp_launch_dp_tile(t, lay.nt, grid, wpb, st);
     }
+    // L > 128: super-tiled kernel, one persistent wave per candidate slot.  PP_DP_GENERIC=1
+    // selects the plain one-workgroup-per-candidate kernel instead (for comparison).
+    const char *e = getenv("PP_DP_GENERIC");
+    if (!(e && atoi(e) == 1)) {
+        int cus = 256;
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess)
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        long long waves = lay.slots < N ? lay.slots : N;
+        return pp_launch_dp_big(a, (int)waves, cus, st);
+    }
     int block = 256;
     hipLaunchKernelGGL(k_dp_generic, dim3(a.nblocks), dim3(block), (size_t)3 * (L + 1) * 8, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;

@@ -1,0 +1,246 @@
+// Partition DP for 128 < L <= 2048 with 32-bit keys: one wavefront per candidate, the
+// (cell, split) plane tiled in 128 x 128 super-tiles, each of them spread over the 64 lanes as
+// 16 x 16 blocks of 8 x 8.
+//
+// Recursion for W(l, xi, r, i) of Sec. IV-B / the PRM listing with one replica per stage:
+//   W[n][l] = min_{n<=k<l} max(g_n[k], P[l] - P[k]),   g_n[k] = max(W[n-1][k], X_n[k]).
+//
+// Same key representation and lane layout as the kernel for L <= 128 (lane (a, b) owns cells
+// 128I + 8i + a + 1 and splits 128J + 8j + b; a cell is (time << K) | k, so max keeps the
+// split index and min returns the smallest time with the lowest split), but the difference
+// term ((P[l] - P[k]) << K) | k is too large to keep in registers for the whole plane, so it
+// is formed on the fly: subtract, max and half a three-operand min per pair.  Only super-tiles
+// on or below the diagonal are visited; the last super-row has NTL <= 16 cell tiles, fixed at
+// compile time, so a model of 300 layers does not pay for 384.
+//
+// Per wave in LDS: two rows of keys (the row being read, rewritten in place as g, and the row
+// being produced).  Split indices go to a per-wave table in global memory while the next row's
+// g is built (one coalesced pass), and the plan is read back from there with cache-bypassing
+// loads.  Waves are persistent and walk candidates wave, wave + nwaves, ...
+#include "pp_common.h"
+#include "pp_dp_generic.h"
+
+#define DPP_QUAD_XOR1 0xB1     // quad_perm:[1,0,3,2]
+#define DPP_QUAD_XOR2 0x4E     // quad_perm:[2,3,0,1]
+#define DPP_HALF_MIRROR 0x141  // row_half_mirror: lane b <-> 7-b within each 8 lanes
+
+struct dp_big_args {
+    int NI;      // super-rows: ceil(L / 128)
+    int waves;   // working waves (each owns one backtrack table)
+    size_t arg_stride;  // entries of one wave's backtrack table: S * Lp
+    dp_args g;
+};
+
+__device__ __forceinline__ int bmin(int a, int b) { return a < b ? a : b; }
+__device__ __forceinline__ int bmax(int a, int b) { return a > b ? a : b; }
+
+template <int CTRL>
+__device__ __forceinline__ int big_dpp_min(int v) {
+    int o = __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, true);
+    return bmin(v, o);
+}
+
+__device__ __forceinline__ int big_min_over_b(int v) {
+    v = big_dpp_min<DPP_QUAD_XOR1>(v);
+    v = big_dpp_min<DPP_QUAD_XOR2>(v);
+    v = big_dpp_min<DPP_HALF_MIRROR>(v);
+    return v;
+}
+
+__device__ __forceinline__ void big_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// One super-tile: NTI cell tiles x NTJ split tiles.  G and Pk point at split 128J of the g
+// row and of the table (P[k] << K) - k.  DIAG: the super-tile lies on the diagonal (I == J):
+// blocks above the block diagonal are skipped, blocks on it are valid for lanes with b <= a.
+template <int NTI, int NTJ, bool DIAG>
+__device__ __forceinline__ void big_tile(int (&acc)[16], const int (&Pl)[16], const int *G,
+                                         const int *Pk, int la, int lb) {
+    int g[NTJ], pk[NTJ];
+#pragma unroll
+    for (int j = 0; j < NTJ; ++j) { g[j] = G[8 * j + lb]; pk[j] = Pk[8 * j + lb]; }
+#pragma unroll
+    for (int j = 0; j < NTJ; ++j) asm volatile("" : "+v"(g[j]), "+v"(pk[j]));  // all reads in flight
+#pragma unroll
+    for (int i = 0; i < NTI; ++i) {
+        int v = acc[i];
+#pragma unroll
+        for (int j = 0; j < NTJ; ++j) {
+            if (DIAG && j > i) continue;
+            int d = Pl[i] - pk[j];
+            if (DIAG && j == i) d = lb <= la ? d : PP_INF32;
+            v = bmin(v, bmax(g[j], d));
+        }
+        acc[i] = v;
+    }
+}
+
+// One super-row of NTI cell tiles: all super-tiles J <= I, then the reduction over the 8 lanes
+// that share a cell, then the cells go to the next row.
+template <int NTI>
+__device__ __forceinline__ void big_super_row(int I, const int *G, const int *sPk, int *nxt,
+                                              int la, int lb) {
+    int acc[16], Pl[16];
+#pragma unroll
+    for (int i = 0; i < NTI; ++i) {
+        const int l = 128 * I + 8 * i + la + 1;
+        Pl[i] = sPk[l] + l;  // P[l] << K
+        acc[i] = PP_INF32;
+    }
+    for (int J = 0; J < I; ++J) big_tile<NTI, 16, false>(acc, Pl, G + 128 * J, sPk + 128 * J, la, lb);
+    big_tile<NTI, NTI, true>(acc, Pl, G + 128 * I, sPk + 128 * I, la, lb);
+#pragma unroll
+    for (int i = 0; i < NTI; ++i) {
+        acc[i] = big_min_over_b(acc[i]);
+        asm volatile("" : "+v"(acc[i]));
+    }
+    if (lb == 0) {
+#pragma unroll
+        for (int i = 0; i < NTI; ++i) nxt[128 * I + 8 * i + la + 1] = acc[i];
+    }
+}
+
+template <int NTL>
+__global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const dp_args &a = b.g;
+    if (!(pp_vmax(a.hdr) < a.fit_limit)) {
+        dp_generic_body<true>(a, smem);  // times too large for 32-bit keys
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wpb = blockDim.x >> 6;
+    const int la = lane >> 3, lb = lane & 7;
+    const int S = a.S, K = a.K, L = a.L, D = a.D, NI = b.NI;
+    const int Lp = 128 * NI, RS = Lp + 4;
+    const int kmask = (1 << K) - 1;
+    int *sPk = (int *)smem;                       // (P[k] << K) - k, k = 0..Lp (P padded with P[L])
+    int *bufA = sPk + RS + (size_t)wib * 2 * RS;  // this wave's two rows
+    int *bufB = bufA + RS;
+    const long long wave = (long long)blockIdx.x * wpb + wib;
+
+    for (int k = threadIdx.x; k <= Lp; k += blockDim.x) sPk[k] = (a.p32[k < L ? k : L] << K) - k;
+    __syncthreads();
+    if (wave >= b.waves) return;
+    unsigned short *arg = a.arg + (size_t)wave * b.arg_stride;
+    unsigned long long pairs = 0, nrows = 0;
+
+    for (long long c = wave; c < a.N; c += b.waves) {
+        // ordering: lane n holds device o[n]
+        const int v_o = lane < S ? a.ord[c * S + lane] : 0;
+        bool bad = false;
+        if (a.validate) {
+            bad = lane < S && (v_o < 0 || v_o >= D);
+            for (int q = 0; q + 1 < S; ++q) {
+                int oq = __builtin_amdgcn_readlane(v_o, q);
+                bad |= (lane > q && lane < S && oq == v_o);
+            }
+        }
+        if (__ballot(bad)) {
+            if (lane == 0) { pp_raise(a.status, PP_FAULT_ORDERING); a.C_out[c] = PP_INF64; }
+            if (lane < S) a.bounds_out[c * S + lane] = 0;
+            continue;
+        }
+        const int v_link = __shfl_up(v_o, 1) * D + v_o;
+
+        // row 0: one stage holding the first l layers
+        int *cur = bufA, *nxt = bufB;
+        for (int l = lane; l <= Lp; l += 64) cur[l] = l ? sPk[l] + l : PP_INF32;
+        big_lds_sync();
+        int top = cur[L];  // S == 1: C = P[L]
+
+        for (int n = 1; n < S; ++n) {
+            const int *xrow = a.x32 + (size_t)__builtin_amdgcn_readlane(v_link, n) * L;
+            // Rewrite the previous row in place as g; on the way its split indices (the low
+            // key bits) go to the backtrack table.
+            unsigned short *arow = arg + (size_t)(n - 1) * Lp;
+            for (int k = lane; k < Lp; k += 64) {
+                const int w = cur[k];
+                if (n >= 2) arow[k] = (unsigned short)(w & kmask);
+                int xk = PP_INF32;
+                if (k >= 1 && k < L) xk = (xrow[k] << K) | k;
+                int wk = (w & ~kmask) | (xk & kmask);
+                cur[k] = bmax(wk, xk);
+            }
+            big_lds_sync();
+            if (n < S - 1) {
+                for (int I = 0; I + 1 < NI; ++I) big_super_row<16>(I, cur, sPk, nxt, la, lb);
+                big_super_row<NTL>(NI - 1, cur, sPk, nxt, la, lb);
+                if (lane == 0) nxt[0] = PP_INF32;
+                big_lds_sync();
+                int *t = cur; cur = nxt; nxt = t;
+                pairs += (unsigned long long)(L - n) * (L - n + 1) / 2;
+            } else {
+                // only W[S-1][L] is needed of the last row
+                const int PL = sPk[L] + L;
+                int v = PP_INF32;
+                for (int k = lane; k < L; k += 64) v = bmin(v, bmax(cur[k], PL - sPk[k]));
+                for (int off = 32; off; off >>= 1) v = bmin(v, __shfl_xor(v, off));
+                top = v;
+                pairs += (unsigned long long)(L - n);
+            }
+            ++nrows;
+        }
+
+        // plan: every lane follows the same chain through the backtrack table, lane n keeps
+        // bound n.  The table was written by other lanes of this wave: wait for the stores,
+        // then read past the L1 cache (which may hold lines of an earlier candidate).
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        int e = L, mine = 0;
+        for (int m = S - 1; m >= 1; --m) {
+            if (lane == m) mine = e;
+            if (m == S - 1) {
+                e = top & kmask;
+            } else {
+                const size_t at = (size_t)m * Lp + e;
+                const unsigned *word = (const unsigned *)(arg + (at & ~(size_t)1));
+                unsigned w2 = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                e = (int)((at & 1) ? (w2 >> 16) : (w2 & 0xffffu));
+            }
+        }
+        if (lane == 0) { mine = e; a.C_out[c] = (long long)(top >> K); }
+        if (lane < S) a.bounds_out[c * S + lane] = mine;
+    }
+    if (lane == 0) pp_count_work(a.hdr, pairs, nrows, (unsigned)wave);
+}
+
+template <int NTL>
+static int launch_big(const dp_big_args &b, int grid, int wpb, size_t lds, hipStream_t st) {
+    hipLaunchKernelGGL(k_dp_big<NTL>, dim3(grid), dim3(64 * wpb), lds, st, b);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, hipStream_t st) {
+    dp_big_args b;
+    b.g = g;
+    b.NI = (g.L + 127) / 128;
+    const int Lp = 128 * b.NI, RS = Lp + 4;
+    b.arg_stride = (size_t)g.S * Lp;
+    const int ntl = (g.L - 128 * (b.NI - 1) + 7) / 8;
+    int wpb = 4;  // waves per workgroup: table + two rows per wave within 64 KiB of LDS
+    while (wpb > 1 && (size_t)(1 + 2 * wpb) * RS * 4 > 64 * 1024) wpb >>= 1;
+    size_t lds = (size_t)(1 + 2 * wpb) * RS * 4;
+    const size_t generic = (size_t)3 * (g.L + 1) * 8;  // the int64 fallback's rows
+    if (lds < generic) lds = generic;
+    if (lds > 64 * 1024) return PP_ERR_INVALID_ARG;
+    // resident waves: 4 per SIMD by registers, and what 160 KiB of LDS per CU allow
+    long long per_cu = (long long)(160 * 1024 / lds) * wpb;
+    if (per_cu > 16) per_cu = 16;
+    if (per_cu < 1) per_cu = 1;
+    long long waves = per_cu * cus;
+    if (waves > max_waves) waves = max_waves;
+    if (waves < 1) waves = 1;
+    b.waves = (int)waves;
+    const int grid = (int)((waves + wpb - 1) / wpb);
+    b.g.nblocks = g.nblocks < grid ? g.nblocks : grid;
+    switch (ntl) {
+#define CASE(n) case n: return launch_big<n>(b, grid, wpb, lds, st);
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+        CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
+#undef CASE
+    }
+    return PP_ERR_INVALID_ARG;
+}
