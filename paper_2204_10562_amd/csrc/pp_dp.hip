@@ -256,7 +256,11 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         int wpb = 4;  // waves per workgroup, limited by 64 KiB of LDS
         while (wpb > 1 && lds_wave * wpb > 64 * 1024) wpb >>= 1;
         if (lds_wave * wpb > 64 * 1024) return PP_ERR_INVALID_ARG;  // cannot happen for S <= 64
-        const int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
+        t.hoist = 1;
+        if (const char *e = getenv("PP_DP_HOIST")) t.hoist = atoi(e) != 0;
+        int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
+        if (!t.hoist) waves_per_simd = 4;
+        if (const char *e = getenv("PP_DP_WPS")) { int v = atoi(e); if (v >= 1 && v <= 8) waves_per_simd = v; }
         t.chunk = choose_chunk(N, D, lex_ord != NULL, (long long)cus * 4, waves_per_simd);
         // tuning overrides for experiments: PP_DP_CHUNK (candidates per wave), PP_DP_WPB (waves
         // per workgroup); the results do not depend on either

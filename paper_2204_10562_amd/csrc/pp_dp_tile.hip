@@ -53,7 +53,7 @@ __device__ __forceinline__ void lds_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int NT>
+template <int NT, bool HOIST>
 __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     extern __shared__ __align__(16) unsigned char smem[];
     if (!(pp_vmax(a.g.hdr) < a.g.fit_limit)) {
@@ -82,22 +82,26 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     if (c0 >= c1) return;
 
     // candidate-independent part: Dp[i][j] = ((P[l] - P[k]) << K) | k, or infinite if k >= l
-    int Dp[NT * (NT + 1) / 2];
+    // (HOIST = false keeps only P[l] << K and (P[k] << K) - k and subtracts in the loop:
+    // more arithmetic per pair, far fewer registers, more resident waves)
+    int Dp[HOIST ? NT * (NT + 1) / 2 : 1];
+    int Pl[NT], Pk[NT];
     {
-        int Pl[NT], Pk[NT];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             Pl[i] = a.g.p32[8 * i + la + 1] << K;
             Pk[i] = (a.g.p32[8 * i + lb] << K) - (8 * i + lb);
         }
+        if (HOIST) {
 #pragma unroll
-        for (int i = 0; i < NT; ++i)
+            for (int i = 0; i < NT; ++i)
 #pragma unroll
-            for (int j = 0; j <= i; ++j) {
-                int d = (j < i || lb <= la) ? Pl[i] - Pk[j] : PP_INF32;
-                asm volatile("" : "+v"(d));  // keep the masked value, not the mask, in the loop
-                Dp[i * (i + 1) / 2 + j] = d;
-            }
+                for (int j = 0; j <= i; ++j) {
+                    int d = (j < i || lb <= la) ? Pl[i] - Pk[j] : PP_INF32;
+                    asm volatile("" : "+v"(d));  // keep the masked value, not the mask, in the loop
+                    Dp[i * (i + 1) / 2 + j] = d;
+                }
+        }
         // row 0: one stage holding the first l layers (same for every candidate)
         if (lb == 0) {
 #pragma unroll
@@ -108,6 +112,12 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         lds_sync();
     }
 
+    // the difference key of block (i, j)
+    auto dkey = [&](int i, int j) __attribute__((always_inline)) -> int {
+        if (HOIST) return Dp[i * (i + 1) / 2 + j];
+        int d = Pl[i] - Pk[j];
+        return (j < i || lb <= la) ? d : PP_INF32;
+    };
     const unsigned long long smask = S >= 64 ? ~0ull : ((1ull << S) - 1);
     const int top_lane = ((L - 1) & 7) * 8;  // a lane that owns cell L (in tile NT-1)
 
@@ -241,6 +251,11 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
             }
             fetch_x(xf, next_link);
 
+            if (!HOIST) {
+                // the differences are formed per row; do not let them be hoisted out again
+#pragma unroll
+                for (int j = 0; j < NT; ++j) asm volatile("" : "+v"(Pk[j]));
+            }
             const int *prow = rows + (n - 1) * RS;
             int *nrow = rows + n * RS;
             int g[NT];
@@ -262,7 +277,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                 for (int i = 0; i < NT; ++i) {
                     int v = PP_INF32;
 #pragma unroll
-                    for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], Dp[i * (i + 1) / 2 + j]));
+                    for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], dkey(i, j)));
                     acc[i] = v;
                 }
 #pragma unroll
@@ -289,7 +304,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                 constexpr int i = NT - 1;
                 int v = PP_INF32;
 #pragma unroll
-                for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], Dp[i * (i + 1) / 2 + j]));
+                for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], dkey(i, j)));
                 v = min_over_b(v);
                 pairs += (unsigned long long)(L - n);
                 ++nrows;
@@ -346,7 +361,8 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
 
 template <int NT>
 static int launch_nt(const dp_tile_args &a, int grid, int wpb, size_t lds, hipStream_t st) {
-    hipLaunchKernelGGL(k_dp_tile<NT>, dim3(grid), dim3(64 * wpb), lds, st, a);
+    if (a.hoist) hipLaunchKernelGGL((k_dp_tile<NT, true>), dim3(grid), dim3(64 * wpb), lds, st, a);
+    else hipLaunchKernelGGL((k_dp_tile<NT, false>), dim3(grid), dim3(64 * wpb), lds, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
