@@ -531,3 +531,97 @@ int ppo_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
     free(T); free(C); free(bounds); free(own);
     return fault;
 }
+
+/* ------------------------------------------------------------------ */
+/* Recursive device ordering (Alg. 2)                                   */
+/* ------------------------------------------------------------------ */
+
+/* Stoer-Wagner minimum cut of the subgraph induced by verts[0..nv-1] (ascending device
+ * indices).  side[i] = 1 marks the vertices of one side of the lightest cut found. */
+static int min_cut(int D, const int64_t *bw, const int *verts, int nv, char *side) {
+    int64_t *W = (int64_t *)malloc((size_t)nv * nv * sizeof(int64_t));
+    int64_t *wsum = (int64_t *)malloc((size_t)nv * sizeof(int64_t));
+    int *low = (int *)malloc((size_t)nv * sizeof(int));      /* lowest device index in the group */
+    int *next = (int *)malloc((size_t)nv * sizeof(int));     /* member list of a merged vertex */
+    int *tail = (int *)malloc((size_t)nv * sizeof(int));
+    char *active = (char *)malloc((size_t)nv), *inA = (char *)malloc((size_t)nv);
+    if (!W || !wsum || !low || !next || !tail || !active || !inA) {
+        free(W); free(wsum); free(low); free(next); free(tail); free(active); free(inA);
+        return PPO_ERR_NOMEM;
+    }
+    for (int i = 0; i < nv; ++i) {
+        for (int j = 0; j < nv; ++j)
+            W[(size_t)i * nv + j] = i == j ? 0 : bw[(size_t)verts[i] * D + verts[j]] + bw[(size_t)verts[j] * D + verts[i]];
+        low[i] = verts[i]; next[i] = -1; tail[i] = i; active[i] = 1;
+    }
+    int64_t best = INF;
+    for (int remaining = nv; remaining > 1; --remaining) {
+        /* one phase: grow A from the lowest-index vertex by maximum adjacency */
+        int start = -1;
+        for (int i = 0; i < nv; ++i)
+            if (active[i] && (start < 0 || low[i] < low[start])) start = i;
+        for (int i = 0; i < nv; ++i) { inA[i] = 0; wsum[i] = W[(size_t)start * nv + i]; }
+        inA[start] = 1;
+        int s = start, t = start;
+        for (int added = 1; added < remaining; ++added) {
+            int pick = -1;
+            for (int i = 0; i < nv; ++i) {
+                if (!active[i] || inA[i]) continue;
+                if (pick < 0 || wsum[i] > wsum[pick] || (wsum[i] == wsum[pick] && low[i] < low[pick])) pick = i;
+            }
+            inA[pick] = 1;
+            s = t; t = pick;
+            if (added + 1 < remaining)
+                for (int i = 0; i < nv; ++i) wsum[i] += W[(size_t)pick * nv + i];
+        }
+        /* cut of the phase: the last vertex against the rest */
+        if (wsum[t] < best) {
+            best = wsum[t];
+            for (int i = 0; i < nv; ++i) side[i] = 0;
+            for (int i = t; i >= 0; i = next[i]) side[i] = 1;
+        }
+        /* merge t into s */
+        for (int i = 0; i < nv; ++i) {
+            W[(size_t)s * nv + i] += W[(size_t)t * nv + i];
+            W[(size_t)i * nv + s] = W[(size_t)s * nv + i];
+        }
+        W[(size_t)s * nv + s] = 0;
+        if (low[t] < low[s]) low[s] = low[t];
+        next[tail[s]] = t; tail[s] = tail[t];
+        active[t] = 0;
+    }
+    free(W); free(wsum); free(low); free(next); free(tail); free(active); free(inA);
+    return PPO_OK;
+}
+
+static int rdo(int D, const int64_t *bw, const int *verts, int nv, int32_t *order, int rank_lo) {
+    if (nv == 1) { order[rank_lo] = verts[0]; return PPO_OK; }
+    char *side = (char *)malloc((size_t)nv);
+    int *g1 = (int *)malloc((size_t)nv * sizeof(int)), *g2 = (int *)malloc((size_t)nv * sizeof(int));
+    int rc = (side && g1 && g2) ? min_cut(D, bw, verts, nv, side) : PPO_ERR_NOMEM;
+    if (rc == PPO_OK) {
+        /* G1 = the side with the lowest device index (verts is ascending, so verts[0]) */
+        int n1 = 0, n2 = 0;
+        for (int i = 0; i < nv; ++i) {
+            if (side[i] == side[0]) g1[n1++] = verts[i];
+            else g2[n2++] = verts[i];
+        }
+        rc = rdo(D, bw, g1, n1, order, rank_lo);
+        if (rc == PPO_OK) rc = rdo(D, bw, g2, n2, order, rank_lo + n1);
+    }
+    free(side); free(g1); free(g2);
+    return rc;
+}
+
+int ppo_rdo_order(int D, const int64_t *bw, int32_t *order_out) {
+    if (D < 1 || !bw || !order_out) return PPO_ERR_INVALID_ARG;
+    for (int u = 0; u < D; ++u)
+        for (int v = 0; v < D; ++v)
+            if (u != v && bw[(size_t)u * D + v] < 0) return PPO_ERR_INVALID_ARG;
+    int *verts = (int *)malloc((size_t)D * sizeof(int));
+    if (!verts) return PPO_ERR_NOMEM;
+    for (int i = 0; i < D; ++i) verts[i] = i;
+    int rc = rdo(D, bw, verts, D, order_out, 0);
+    free(verts);
+    return rc;
+}

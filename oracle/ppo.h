@@ -105,6 +105,19 @@ int64_t ppo_pe_makespan(int S, int M, const int64_t *F, const int64_t *B,
                         const int64_t *cf, const int64_t *cb,
                         int64_t *start_out, int64_t *finish_out);
 
+/* Recursive device ordering (Alg. 2, Sec. IV-B): find a minimum cut of the
+ * GPU graph, order the two sides recursively, first side first.  The graph
+ * is undirected with weight bw[u][v] + bw[v][u] on edge {u, v} (twice the
+ * bandwidth for a symmetric matrix).  The minimum cut is found with the
+ * Stoer-Wagner algorithm (the routine the paper cites): vertices of the
+ * current subgraph in ascending index order; every phase starts from the
+ * remaining vertex of lowest index (a merged vertex counts as its lowest
+ * member), adds the most tightly connected vertex, ties to the lowest index;
+ * a later phase replaces the best cut only if strictly lighter.  The side
+ * that holds the lowest-index vertex comes first.  order_out[rank] = device.
+ * Returns PPO_OK or PPO_ERR_*. */
+int ppo_rdo_order(int D, const int64_t *bw_bytes_per_us, int32_t *order_out);
+
 /* threads the candidate loops use (OpenMP), and a setter */
 int ppo_get_num_threads(void);
 void ppo_set_num_threads(int n);

@@ -156,3 +156,14 @@ def pe_makespan(F, B, cf, cb, M, want_times=False):
     fi = np.full((J, M), -1, np.int64) if want_times else None
     T = int(lib().ppo_pe_makespan(S, M, _p(F), _p(B), _p(cf), _p(cb), _p(st), _p(fi)))
     return (T, st, fi) if want_times else T
+
+
+def rdo_order(bw):
+    """Recursive device ordering of a D x D bandwidth matrix -> list of devices by rank."""
+    bw = _i64(bw)
+    D = bw.shape[0]
+    order = np.empty(D, np.int32)
+    rc = lib().ppo_rdo_order(D, _p(bw), _p(order))
+    if rc != 0:
+        raise RuntimeError("ppo_rdo_order failed: %d" % rc)
+    return order.tolist()
