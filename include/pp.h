@@ -187,6 +187,26 @@ int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM,
                        int64_t *C_all, void *workspace, size_t workspace_bytes,
                        int32_t *status, void *stream);
 
+/*
+ * Recursive device ordering (Alg. 2, Sec. IV-B): one heuristic ordering of the
+ * D devices, meant as an extra candidate row (or the only one when D! is out
+ * of reach).  HOST function, host pointers, no GPU work: the device graph is
+ * split at a minimum cut, each side is ordered recursively, and the ranks of
+ * the first side precede those of the second, so that weak links end up
+ * between far-apart ranks.
+ *   bw_bytes_per_us  [D*D] host, the matrix pp_prefix_costs takes; the graph is
+ *                    undirected with weight bw[u][v] + bw[v][u] on edge {u,v};
+ *                    diagonal ignored; entries must lie in [0, 2^62 / D^2]
+ *   order_out        [D] host, order_out[rank] = device
+ * The minimum cut is Stoer-Wagner's (the routine the paper cites), made
+ * deterministic: a merged vertex counts as its lowest device; a phase starts
+ * at the lowest remaining vertex and adds the most tightly connected one,
+ * ties to the lowest; a later phase replaces the lightest cut so far only if
+ * strictly lighter; the side that holds the lowest device is ordered first.
+ * Returns PP_OK or PP_ERR_INVALID_ARG.
+ */
+int pp_rdo_order(int D, const int64_t *bw_bytes_per_us, int32_t *order_out);
+
 /* Text for a PP_ERR_* code (host function, static storage). */
 const char *pp_strerror(int code);
 

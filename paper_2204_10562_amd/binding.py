@@ -24,7 +24,7 @@ PP_FAULT_OVERFLOW = 16
 PP_MAX_STAGES = 64
 
 EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
-           "pp_best_plan", "pp_best_plan_multi", "pp_strerror")
+           "pp_best_plan", "pp_best_plan_multi", "pp_rdo_order", "pp_strerror")
 
 
 class PPResult(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib():
         L.pp_best_plan.restype = i32
         L.pp_best_plan_multi.argtypes = [i32, i32, i32, i64, i32] + [vp] * 9 + [vp, sz, vp, vp]
         L.pp_best_plan_multi.restype = i32
+        L.pp_rdo_order.argtypes = [i32, vp, vp]
+        L.pp_rdo_order.restype = i32
         L.pp_strerror.argtypes = [i32]
         L.pp_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -160,6 +162,14 @@ def pp_best_plan_multi(L, D, S, N, M_list, PF, PB, XF, XB, orderings, out, T_all
         _ptr(T_all, i64, N * nM, "T_all", optional=True), _ptr(C_all, i64, N, "C_all", optional=True),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
         _ptr(status, i32, 1, "status"), _stream()))
+
+
+def pp_rdo_order(D, bw_bytes_per_us):
+    """Host function: bw is a host sequence/array of D*D ints; returns the devices by rank."""
+    bw = (ctypes.c_int64 * (D * D))(*[int(x) for x in bw_bytes_per_us])
+    order = (ctypes.c_int32 * D)()
+    _check(lib().pp_rdo_order(D, ctypes.cast(bw, ctypes.c_void_p), ctypes.cast(order, ctypes.c_void_p)))
+    return list(order)
 
 
 PP_WS_PAIRS_EXECUTED = 1024
