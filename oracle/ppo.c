@@ -533,6 +533,77 @@ int ppo_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
 }
 
 /* ------------------------------------------------------------------ */
+/* Stage-count search (outer loop of Alg. 3)                            */
+/* ------------------------------------------------------------------ */
+
+int ppo_best_plan_stages(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                         const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                         const int32_t *orderings, ppo_result *out, int64_t *T_all,
+                         int64_t *C_all, int32_t *bounds_all) {
+    int rc = check_common(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !out) return PPO_ERR_INVALID_ARG;
+    int32_t *own = NULL;
+    if (!orderings) {
+        own = all_orderings(D, N);
+        if (!own) return PPO_ERR_NOMEM;
+        orderings = own;
+    }
+    const int tri = S * (S + 1) / 2;
+    int64_t *T = (int64_t *)malloc((size_t)N * S * sizeof(int64_t));
+    int64_t *C = (int64_t *)malloc((size_t)N * S * sizeof(int64_t));
+    int32_t *bounds = (int32_t *)malloc((size_t)N * tri * sizeof(int32_t));
+    int32_t *pre = (int32_t *)malloc((size_t)N * S * sizeof(int32_t));
+    int32_t *bxi = (int32_t *)malloc((size_t)N * S * sizeof(int32_t));
+    int64_t *Txi = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+    int64_t *Cxi = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+    int fault = (T && C && bounds && pre && bxi && Txi && Cxi) ? 0 : PPO_ERR_NOMEM;
+    /* for every stage count xi: the plan (PRM) and its schedule (PE) on the first xi
+     * devices of every candidate's ordering */
+    for (int xi = 1; xi <= S && fault == 0; ++xi) {
+        for (int64_t c = 0; c < N; ++c)
+            for (int n = 0; n < xi; ++n) pre[c * xi + n] = orderings[c * S + n];
+        fault = ppo_partition_dp(L, D, xi, N, PF, PB, XF, XB, pre, Cxi, bxi);
+        if (fault == 0)
+            fault = ppo_schedule_makespan(L, D, xi, N, M, PF, PB, XF, XB, pre, bxi, Txi);
+        if (fault) break;
+        for (int64_t c = 0; c < N; ++c) {
+            T[c * S + xi - 1] = Txi[c];
+            C[c * S + xi - 1] = Cxi[c];
+            for (int n = 0; n < xi; ++n)
+                bounds[c * tri + xi * (xi - 1) / 2 + n] = bxi[c * xi + n];
+        }
+    }
+    if (fault == 0) {
+        /* T_SPP <- T_PE only if T_PE < T_SPP: candidates in index order, and for each
+         * candidate the stage counts in the listing's order 1, 2, ... */
+        int64_t T_best = INF, best = -1;
+        int xi_best = 0;
+        for (int64_t c = 0; c < N; ++c)
+            for (int xi = 1; xi <= S; ++xi)
+                if (T[c * S + xi - 1] < T_best) {
+                    T_best = T[c * S + xi - 1];
+                    best = c;
+                    xi_best = xi;
+                }
+        memset(out, 0, sizeof(*out));
+        out->best_index = best;
+        out->S = xi_best;
+        out->T = T_best;
+        out->C = best >= 0 ? C[best * S + xi_best - 1] : INF;
+        for (int n = 0; n < xi_best && best >= 0; ++n) {
+            out->bounds[n] = bounds[best * tri + xi_best * (xi_best - 1) / 2 + n];
+            out->order[n] = orderings[best * S + n];
+        }
+        if (T_all) memcpy(T_all, T, (size_t)N * S * sizeof(int64_t));
+        if (C_all) memcpy(C_all, C, (size_t)N * S * sizeof(int64_t));
+        if (bounds_all) memcpy(bounds_all, bounds, (size_t)N * tri * sizeof(int32_t));
+    }
+    free(T); free(C); free(bounds); free(pre); free(bxi); free(Txi); free(Cxi); free(own);
+    return fault;
+}
+
+/* ------------------------------------------------------------------ */
 /* Recursive device ordering (Alg. 2)                                   */
 /* ------------------------------------------------------------------ */
 

@@ -90,6 +90,22 @@ int ppo_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
                   const int32_t *orderings, ppo_result *out, int64_t *T_all,
                   int64_t *C_all);
 
+/* ppo_best_plan with the stage count searched as well (outer loop of the SPP
+ * listing, Alg. 3): every candidate row holds S devices; with xi stages
+ * (1 <= xi <= S) the pipeline runs on the first xi of them, partitioned by
+ * the recursion for W with xi stages (one replica per stage) and timed by
+ * Alg. 1.  Keep-the-minimum with strict '<', scanning candidates in index
+ * order and, per candidate, xi = 1, 2, ..., S as the listing does: the winner
+ * has the smallest T, then the lowest candidate index, then the fewest stages.
+ *   T_all, C_all   [N*S]  value for (c, xi) at c*S + xi-1           (or NULL)
+ *   bounds_all     [N*S(S+1)/2]  plan of (c, xi) at c*S(S+1)/2 + xi(xi-1)/2,
+ *                  xi entries                                        (or NULL)
+ *   out->S is the winning stage count; bounds/order hold that many entries. */
+int ppo_best_plan_stages(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                         const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                         const int32_t *orderings, ppo_result *out, int64_t *T_all,
+                         int64_t *C_all, int32_t *bounds_all);
+
 /* Execution-ordering phase of Alg. 1 alone, for a pipeline of S stages and
  * M microbatches.  rounds_out[t*(4S-3) + (j-1)] = microbatch (1-based) that
  * block j handles in sweep t, or 0.  Returns the number of sweeps, or a

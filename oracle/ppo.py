@@ -129,6 +129,25 @@ def best_plan(L, D, S, N, M, PF, PB, XF, XB, orderings, want_all=True):
     return rc, out, T_all, C_all
 
 
+def best_plan_stages(L, D, S, N, M, PF, PB, XF, XB, orderings):
+    """-> (status, dict(best_index, T, C, S, bounds, order), T_all[N,S], C_all[N,S],
+    bounds_all[N, S(S+1)/2])"""
+    orderings = _i32(orderings)
+    res = Result()
+    tri = S * (S + 1) // 2
+    T_all = np.empty((N, S), np.int64)
+    C_all = np.empty((N, S), np.int64)
+    b_all = np.empty((N, tri), np.int32)
+    rc = lib().ppo_best_plan_stages(L, D, S, ctypes.c_int64(N), M, _p(_i64(PF)), _p(_i64(PB)),
+                                    _p(_i64(XF)), _p(_i64(XB)), _p(orderings), ctypes.byref(res),
+                                    _p(T_all), _p(C_all), _p(b_all))
+    xi = int(res.S)
+    out = dict(best_index=int(res.best_index), T=int(res.T), C=int(res.C), S=xi,
+               bounds=[int(res.bounds[i]) for i in range(xi)],
+               order=[int(res.order[i]) for i in range(xi)])
+    return rc, out, T_all, C_all, b_all
+
+
 def execution_order(S, M):
     """-> array [sweeps, 4S-3]: microbatch handled by each block per sweep (0 = none)."""
     J = 4 * S - 3
