@@ -188,6 +188,48 @@ int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM,
                        int32_t *status, void *stream);
 
 /*
+ * Stage-count search: the outer loop of the SPP listing (Alg. 3), which varies
+ * the number of stages xi and keeps the plan with the smallest per-iteration
+ * time.  Every candidate row holds S devices; with xi stages (1 <= xi <= S)
+ * the pipeline runs on the first xi of them (with one replica per stage the
+ * recursion for W(l, xi, r, i) places stage n on the n-th device of the
+ * ordering).  Row xi-1 of the table W of pp_partition_dp depends only on those
+ * xi devices, so one dynamic program per candidate yields all S plans:
+ * C(c, xi) = W[xi-1][L], bounds read back from (xi-1, L).
+ *
+ * pp_partition_dp_stages: the S plans of every candidate.
+ *   C_out       [N*S]          C(c, xi) at c*S + xi-1
+ *   bounds_out  [N*S(S+1)/2]   the xi bounds of (c, xi) at
+ *                              c*S(S+1)/2 + xi(xi-1)/2
+ *   workspace   as for pp_partition_dp (pp_workspace_bytes)
+ *   Faults: ORDERING (checked on the whole row of S devices).
+ *
+ * pp_best_plan_stages: those plans, the makespan (Alg. 1) of each for every
+ * microbatch count, and per microbatch count the keep-the-minimum of Alg. 3
+ * with strict '<', candidates scanned in index order and, per candidate,
+ * xi = 1, 2, ..., S: smallest T, then lowest candidate, then fewest stages.
+ *   out     [nM] pp_result; out[q].S is the winning stage count and bounds /
+ *           order hold that many entries (the rest are 0)
+ *   T_all   [nM*N*S] (T of (c, xi) for M_list[q] at (q*N + c)*S + xi-1) or NULL
+ *   C_all   [N*S] or NULL
+ *   workspace   pp_workspace_bytes_stages(L, D, S, N, nM) bytes (host function;
+ *               0 if a size is out of range)
+ *   Faults: ORDERING, OVERFLOW.
+ */
+size_t pp_workspace_bytes_stages(int L, int D, int S, int64_t N, int nM);
+int pp_partition_dp_stages(int L, int D, int S, int64_t N, const int64_t *PF,
+                           const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                           const int32_t *orderings, int64_t *C_out,
+                           int32_t *bounds_out, void *workspace,
+                           size_t workspace_bytes, int32_t *status, void *stream);
+int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM,
+                        const int32_t *M_list, const int64_t *PF,
+                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                        const int32_t *orderings, pp_result *out, int64_t *T_all,
+                        int64_t *C_all, void *workspace, size_t workspace_bytes,
+                        int32_t *status, void *stream);
+
+/*
  * Recursive device ordering (Alg. 2, Sec. IV-B): one heuristic ordering of the
  * D devices, meant as an extra candidate row (or the only one when D! is out
  * of reach).  HOST function, host pointers, no GPU work: the device graph is

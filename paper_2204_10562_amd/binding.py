@@ -24,7 +24,8 @@ PP_FAULT_OVERFLOW = 16
 PP_MAX_STAGES = 64
 
 EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
-           "pp_best_plan", "pp_best_plan_multi", "pp_rdo_order", "pp_strerror")
+           "pp_best_plan", "pp_best_plan_multi", "pp_workspace_bytes_stages", "pp_partition_dp_stages",
+           "pp_best_plan_stages", "pp_rdo_order", "pp_strerror")
 
 
 class PPResult(ctypes.Structure):
@@ -69,6 +70,12 @@ def lib():
         L.pp_best_plan.restype = i32
         L.pp_best_plan_multi.argtypes = [i32, i32, i32, i64, i32] + [vp] * 9 + [vp, sz, vp, vp]
         L.pp_best_plan_multi.restype = i32
+        L.pp_workspace_bytes_stages.argtypes = [i32, i32, i32, i64, i32]
+        L.pp_workspace_bytes_stages.restype = sz
+        L.pp_partition_dp_stages.argtypes = L.pp_partition_dp.argtypes
+        L.pp_partition_dp_stages.restype = i32
+        L.pp_best_plan_stages.argtypes = L.pp_best_plan_multi.argtypes
+        L.pp_best_plan_stages.restype = i32
         L.pp_rdo_order.argtypes = [i32, vp, vp]
         L.pp_rdo_order.restype = i32
         L.pp_strerror.argtypes = [i32]
@@ -164,6 +171,40 @@ def pp_best_plan_multi(L, D, S, N, M_list, PF, PB, XF, XB, orderings, out, T_all
         _ptr(status, i32, 1, "status"), _stream()))
 
 
+def pp_workspace_bytes_stages(L, D, S, N, nM):
+    return int(lib().pp_workspace_bytes_stages(L, D, S, N, nM))
+
+
+def pp_partition_dp_stages(L, D, S, N, PF, PB, XF, XB, orderings, C_out, bounds_out, workspace,
+                           status):
+    i64, i32 = torch.int64, torch.int32
+    _check(lib().pp_partition_dp_stages(
+        L, D, S, N, _ptr(PF, i64, L + 1, "PF"), _ptr(PB, i64, L + 1, "PB"),
+        _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(C_out, i64, N * S, "C_out"),
+        _ptr(bounds_out, i32, N * (S * (S + 1) // 2), "bounds_out"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+def pp_best_plan_stages(L, D, S, N, M_list, PF, PB, XF, XB, orderings, out, T_all, C_all,
+                        workspace, status):
+    """M_list is a host sequence of ints; out holds len(M_list) pp_result records."""
+    i64, i32 = torch.int64, torch.int32
+    nM = len(M_list)
+    Ms = (ctypes.c_int32 * nM)(*[int(m) for m in M_list])
+    _check(lib().pp_best_plan_stages(
+        L, D, S, N, nM, ctypes.cast(Ms, ctypes.c_void_p), _ptr(PF, i64, L + 1, "PF"),
+        _ptr(PB, i64, L + 1, "PB"), _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(out, torch.uint8, RESULT_BYTES * nM, "out"),
+        _ptr(T_all, i64, N * S * nM, "T_all", optional=True),
+        _ptr(C_all, i64, N * S, "C_all", optional=True),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
 def pp_rdo_order(D, bw_bytes_per_us):
     """Host function: bw is a host sequence/array of D*D ints; returns the devices by rank."""
     bw = (ctypes.c_int64 * (D * D))(*[int(x) for x in bw_bytes_per_us])
@@ -184,10 +225,13 @@ def read_workspace_stats(workspace):
                 rows_executed=int(head[PP_WS_ROWS_EXECUTED // 8:PP_WS_ROWS_EXECUTED // 8 + 64].sum()))
 
 
-def read_result(out, S, index=0):
-    """Copy a device pp_result (uint8 tensor, record number `index`) to the host and unpack it."""
+def read_result(out, S=None, index=0):
+    """Copy a device pp_result (uint8 tensor, record number `index`) to the host and unpack it
+    (S entries of bounds and order; S = None: as many as the record's own stage count)."""
     raw = bytes(out.cpu().numpy().tobytes()[index * RESULT_BYTES:(index + 1) * RESULT_BYTES])
     r = PPResult.from_buffer_copy(raw)
+    if S is None:
+        S = int(r.S)
     return dict(best_index=int(r.best_index), T=int(r.T), C=int(r.C), S=int(r.S),
                 bounds=[int(r.bounds[i]) for i in range(S)],
                 order=[int(r.order[i]) for i in range(S)])

@@ -43,8 +43,63 @@ extern "C" int pp_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, C_out,
+    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 0, C_out,
                         bounds_out, workspace, lay, status, st);
+}
+
+extern "C" size_t pp_workspace_bytes_stages(int L, int D, int S, int64_t N, int nM) {
+    if (nM < 1 || nM > PP_MAX_M_LIST || !pp_workspace_bytes(L, D, S, N)) return 0;
+    return pp_layout_stages(pp_layout(L, D, S, N), S, N, nM).total;
+}
+
+extern "C" int pp_partition_dp_stages(int L, int D, int S, int64_t N, const int64_t *PF,
+                                      const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                                      const int32_t *orderings, int64_t *C_out,
+                                      int32_t *bounds_out, void *workspace,
+                                      size_t workspace_bytes, int32_t *status, void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (!PF || !PB || !XF || !XB || !C_out || !bounds_out) return PP_ERR_INVALID_ARG;
+    pp_ws_layout lay = pp_layout(L, D, S, N);
+    rc = check_ws(workspace, workspace_bytes, lay);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t *ord = NULL;
+    rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
+    if (rc) return rc;
+    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, C_out,
+                        bounds_out, workspace, lay, status, st);
+}
+
+extern "C" int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM, const int32_t *M_list,
+                                   const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                                   const int64_t *XB, const int32_t *orderings, pp_result *out,
+                                   int64_t *T_all, int64_t *C_all, void *workspace,
+                                   size_t workspace_bytes, int32_t *status, void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (nM < 1 || nM > PP_MAX_M_LIST || !M_list || !PF || !PB || !XF || !XB || !out)
+        return PP_ERR_INVALID_ARG;
+    for (int q = 0; q < nM; ++q)
+        if (M_list[q] < 1) return PP_ERR_INVALID_ARG;
+    pp_ws_layout lay = pp_layout(L, D, S, N);
+    pp_stage_layout sl = pp_layout_stages(lay, S, N, nM);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sl.total)
+        return PP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    int64_t *C = C_all ? C_all : (int64_t *)(base + sl.C);
+    int64_t *T = T_all ? T_all : (int64_t *)(base + sl.T);
+    int32_t *bounds = (int32_t *)(base + sl.bounds);
+    const int32_t *ord = NULL;
+    rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
+    if (rc) return rc;
+    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, C, bounds,
+                      workspace, lay, status, st);
+    if (rc) return rc;
+    pp_ws_header *hdr = (pp_ws_header *)(base + lay.hdr);
+    return pp_launch_makespan_stages(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, C, T,
+                                     status, base + sl.part, hdr->ticket, out, st);
 }
 
 extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
@@ -79,7 +134,7 @@ extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const 
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, C, bounds,
+    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 0, C, bounds,
                       workspace, lay, status, st);
     if (rc) return rc;
     pp_ws_header *hdr = (pp_ws_header *)(base + lay.hdr);

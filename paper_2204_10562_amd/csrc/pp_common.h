@@ -70,6 +70,22 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     return w;
 }
 
+// Extra workspace of the stage-count search, carved after the common part.
+struct pp_stage_layout {
+    size_t bounds, C, T, part, total;
+};
+
+static inline pp_stage_layout pp_layout_stages(const pp_ws_layout &base, int S, int64_t N, int nM) {
+    pp_stage_layout w;
+    size_t off = base.total;
+    w.bounds = off; off += pp_align256((size_t)N * (S * (S + 1) / 2) * 4);
+    w.C = off;      off += pp_align256((size_t)N * S * 8);
+    w.T = off;      off += pp_align256((size_t)nM * N * S * 8);
+    w.part = off;   off += pp_align256((size_t)1024 * 16 * PP_MAX_M_LIST);
+    w.total = off;
+    return w;
+}
+
 // Host-side checks shared by the entry points; returns PP_OK or PP_ERR_INVALID_ARG.
 int pp_check_sizes(int L, int D, int S, int64_t N, const int32_t *orderings);
 
@@ -81,10 +97,13 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
                    const pp_ws_layout &lay, const int32_t **ord, hipStream_t st);
 // Exactly one of lex_ord (the library's own list of all D! orderings, known to be valid and
 // lexicographic) and user_ord (the caller's list, to be validated) is non-NULL.
+// stages == 0: C_out [N], bounds_out [N][S].  stages == 1: the plans for every stage count
+// xi = 1..S on the first xi devices: C_out [N][S], bounds_out [N][S(S+1)/2], the xi bounds of
+// stage count xi at offset xi(xi-1)/2.
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
-                 const int32_t *user_ord, int64_t *C_out, int32_t *bounds_out, void *ws,
-                 const pp_ws_layout &lay, int32_t *status, hipStream_t st);
+                 const int32_t *user_ord, int stages, int64_t *C_out, int32_t *bounds_out,
+                 void *ws, const pp_ws_layout &lay, int32_t *status, hipStream_t st);
 // Makespan of every candidate's plan for each of the nM microbatch counts in Ms (host array).
 // With part/ticket/C/out non-NULL the launch also finds, per microbatch count, the candidate
 // with the smallest T (lowest index on ties) and fills out[q]; *ticket must be 0 when the
@@ -95,6 +114,15 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
                        unsigned *ticket, pp_result *out, hipStream_t st);
+// Stage-count search: makespan of the plan with xi stages of every candidate for xi = 1..S
+// (bounds [N][S(S+1)/2] and C [N][S] as pp_launch_dp leaves them with stages == 1), written to
+// T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest
+// candidate and then lowest xi on ties, into out[q].  part must hold 1024 * nM pairs of int64.
+int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int *Ms,
+                              const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                              const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
+                              const int64_t *C, int64_t *T_st, int32_t *status, void *part,
+                              unsigned *ticket, pp_result *out, hipStream_t st);
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
                      unsigned *ticket, pp_result *out, hipStream_t st);

@@ -222,10 +222,11 @@ static long long choose_chunk(int64_t N, int D, bool lex, long long simds, int w
 
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
-                 const int32_t *user_ord, int64_t *C_out, int32_t *bounds_out, void *ws,
-                 const pp_ws_layout &lay, int32_t *status, hipStream_t st) {
+                 const int32_t *user_ord, int stages, int64_t *C_out, int32_t *bounds_out,
+                 void *ws, const pp_ws_layout &lay, int32_t *status, hipStream_t st) {
     char *base = (char *)ws;
     dp_args a;
+    a.stages = stages;
     a.L = L; a.D = D; a.S = S; a.K = pp_index_bits(L); a.N = N;
     a.fit_limit = (1ull << (31 - a.K)) - 1;
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;
@@ -250,8 +251,9 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         t.xkt = (const int *)(base + lay.xkt);
         int cus = 256;
         int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess)
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            cus = 256;
         const size_t lds_wave = pp_dp_tile_lds_per_wave(S, lay.nt);
         int wpb = 4;  // waves per workgroup, limited by 64 KiB of LDS
         while (wpb > 1 && lds_wave * wpb > 64 * 1024) wpb >>= 1;
@@ -281,8 +283,9 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     if (!(e && atoi(e) == 1)) {
         int cus = 256;
         int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess)
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            cus = 256;
         long long waves = lay.slots < N ? lay.slots : N;
         return pp_launch_dp_big(a, (int)waves, cus, st);
     }

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     if (wave >= b.waves) return;
     unsigned short *arg = a.arg + (size_t)wave * b.arg_stride;
     unsigned long long pairs = 0, nrows = 0;
+    const int tri = S * (S + 1) / 2;
 
     for (long long c = wave; c < a.N; c += b.waves) {
         // ordering: lane n holds device o[n]
@@ -140,8 +141,14 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
             }
         }
         if (__ballot(bad)) {
-            if (lane == 0) { pp_raise(a.status, PP_FAULT_ORDERING); a.C_out[c] = PP_INF64; }
-            if (lane < S) a.bounds_out[c * S + lane] = 0;
+            if (lane == 0) pp_raise(a.status, PP_FAULT_ORDERING);
+            if (a.stages) {
+                if (lane < S) a.C_out[c * S + lane] = PP_INF64;
+                for (int n = lane; n < tri; n += 64) a.bounds_out[c * tri + n] = 0;
+            } else {
+                if (lane == 0) a.C_out[c] = PP_INF64;
+                if (lane < S) a.bounds_out[c * S + lane] = 0;
+            }
             continue;
         }
         const int v_link = __shfl_up(v_o, 1) * D + v_o;
@@ -151,6 +158,7 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
         for (int l = lane; l <= Lp; l += 64) cur[l] = l ? sPk[l] + l : PP_INF32;
         big_lds_sync();
         int top = cur[L];  // S == 1: C = P[L]
+        int v_tops = top;  // lane n keeps W[n][L] (with its split index) for the stage-count search
 
         for (int n = 1; n < S; ++n) {
             const int *xrow = a.x32 + (size_t)__builtin_amdgcn_readlane(v_link, n) * L;
@@ -172,6 +180,8 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
                 if (lane == 0) nxt[0] = PP_INF32;
                 big_lds_sync();
                 int *t = cur; cur = nxt; nxt = t;
+                const int top_n = cur[L];
+                if (lane == n) v_tops = top_n;
                 pairs += (unsigned long long)(L - n) * (L - n + 1) / 2;
             } else {
                 // only W[S-1][L] is needed of the last row
@@ -180,6 +190,7 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
                 for (int k = lane; k < L; k += 64) v = bmin(v, bmax(cur[k], PL - sPk[k]));
                 for (int off = 32; off; off >>= 1) v = bmin(v, __shfl_xor(v, off));
                 top = v;
+                if (lane == n) v_tops = v;
                 pairs += (unsigned long long)(L - n);
             }
             ++nrows;
@@ -189,6 +200,28 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
         // bound n.  The table was written by other lanes of this wave: wait for the stores,
         // then read past the L1 cache (which may hold lines of an earlier candidate).
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        if (a.stages) {
+            // lane xi-1 follows its own chain from (xi-1, L): the plan with xi stages
+            if (lane < S) {
+                a.C_out[c * S + lane] = (long long)(v_tops >> K);
+                int *bo = a.bounds_out + c * tri + lane * (lane + 1) / 2;
+                int e = L;
+                for (int m = lane; m >= 1; --m) {
+                    bo[m] = e;
+                    if (m == lane) {
+                        e = v_tops & kmask;
+                        e = e < Lp ? e : Lp - 1;  // stays inside the table whatever the data
+                    } else {
+                        const size_t at = (size_t)m * Lp + e;
+                        const unsigned *word = (const unsigned *)(arg + (at & ~(size_t)1));
+                        unsigned w2 = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        e = (int)((at & 1) ? (w2 >> 16) : (w2 & 0xffffu));
+                    }
+                }
+                bo[0] = e;
+            }
+            continue;
+        }
         int e = L, mine = 0;
         for (int m = S - 1; m >= 1; --m) {
             if (lane == m) mine = e;

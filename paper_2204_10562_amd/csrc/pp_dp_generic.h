@@ -21,6 +21,11 @@ struct dp_args {
     const int *p32, *x32;
     unsigned short *arg;  // [nblocks][S][L+1] backtrack tables, one per working workgroup
     int nblocks;          // workgroups that take part (the rest of the grid returns)
+    // stages == 0: C_out [N], bounds_out [N][S]: the plan with S stages.
+    // stages == 1: the plan for every stage count xi = 1..S on the first xi devices (row xi-1
+    // of the same table, read at cell L): C_out [N][S], bounds_out [N][S(S+1)/2] with the xi
+    // bounds of stage count xi at offset xi(xi-1)/2.
+    int stages;
     long long *C_out;
     int *bounds_out;
     int32_t *status;
@@ -59,6 +64,8 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
     const V INF = WIDE ? (V)PP_INF64 : (V)PP_INF32;
     __shared__ int s_o[PP_MAX_STAGES];
     __shared__ int s_ok;
+    __shared__ long long s_top[PP_MAX_STAGES];  // W[n][L] of every row (stage-count search)
+    const int tri = a.S * (a.S + 1) / 2;
     const int L = a.L, S = a.S, K = a.K, tid = threadIdx.x, B = blockDim.x;
     const int kmask = (1 << K) - 1;
     V *sP = (V *)smem;      // WIDE: P[l];  keys: (P[l] << K) - l
@@ -75,12 +82,21 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
     for (long long c = blockIdx.x; c < a.N; c += a.nblocks) {
         __syncthreads();
         if (!load_ordering(a, c, s_o, &s_ok)) {
-            if (tid == 0) { pp_raise(a.status, PP_FAULT_ORDERING); a.C_out[c] = PP_INF64; }
-            for (int n = tid; n < S; n += B) a.bounds_out[c * S + n] = 0;
+            if (tid == 0) pp_raise(a.status, PP_FAULT_ORDERING);
+            if (a.stages) {
+                for (int n = tid; n < S; n += B) a.C_out[c * S + n] = PP_INF64;
+                for (int n = tid; n < tri; n += B) a.bounds_out[c * tri + n] = 0;
+            } else {
+                if (tid == 0) a.C_out[c] = PP_INF64;
+                for (int n = tid; n < S; n += B) a.bounds_out[c * S + n] = 0;
+            }
             continue;
         }
         // one stage holding the first l layers
-        for (int l = tid; l <= L; l += B) sW[l] = l ? (WIDE ? sP[l] : sP[l] + l) : INF;
+        for (int l = tid; l <= L; l += B) {
+            sW[l] = l ? (WIDE ? sP[l] : sP[l] + l) : INF;
+            if (l == L) s_top[0] = (long long)sW[l];
+        }
 
         for (int n = 1; n < S; ++n) {
             __syncthreads();
@@ -110,6 +126,7 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
                     }
                     sW[l] = best;
                     arg[n * (L + 1) + l] = (unsigned short)bk;
+                    if (l == L) s_top[n] = (long long)best;
                 } else {
                     const int Pl = (int)sP[l] + l;
                     int best = PP_INF32;
@@ -120,14 +137,27 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
                     }
                     sW[l] = (V)best;
                     arg[n * (L + 1) + l] = (unsigned short)(best & kmask);
+                    if (l == L) s_top[n] = (long long)best;
                 }
             }
         }
-        // the backtrack table was written by the whole workgroup and is read by thread 0: a
-        // workgroup-scope fence is enough (and much cheaper than a device-scope one)
+        // the backtrack table was written by the whole workgroup and is read by a few of its
+        // threads: a workgroup-scope fence is enough (and much cheaper than a device-scope one)
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
         __syncthreads();
-        if (tid == 0) {
+        if (a.stages) {
+            // thread xi-1 reads back the plan with xi stages from (xi-1, L)
+            for (int t = tid; t < S; t += B) {
+                a.C_out[c * S + t] = WIDE ? s_top[t] : (long long)((int)s_top[t] >> K);
+                int *bo = a.bounds_out + c * tri + t * (t + 1) / 2;
+                int e = L;
+                for (int n = t; n >= 1; --n) {
+                    bo[n] = e;
+                    e = arg[n * (L + 1) + e];
+                }
+                bo[0] = e;
+            }
+        } else if (tid == 0) {
             a.C_out[c] = WIDE ? (long long)sW[L] : (long long)((int)sW[L] >> K);
             int e = L;
             for (int n = S - 1; n >= 1; --n) {
@@ -135,6 +165,8 @@ __device__ void dp_generic_body(const dp_args &a, unsigned char *smem) {
                 e = arg[n * (L + 1) + e];
             }
             a.bounds_out[c * S] = e;
+        }
+        if (tid == 0) {
             for (int n = 1; n < S - 1; ++n) pairs += (unsigned long long)(L - n) * (L - n + 1) / 2;
             if (S > 1) pairs += (unsigned long long)(L - S + 1);
             nrows += S - 1;

@@ -17,12 +17,14 @@ struct dp_tile_args {
     dp_args g;        // tables, outputs and the generic fallback's arguments
 };
 
-// LDS bytes one wave needs: S key rows, the backtrack arena, the pending candidates' row slots.
+// LDS bytes one wave needs: S key rows, the backtrack arena, the pending candidates' row slots
+// and (used by the stage-count search only) the key of cell L of each of their rows.
 __host__ __device__ static inline size_t pp_dp_tile_lds_per_wave(int S, int nt) {
     size_t rows = (size_t)S * (8 * nt + 4) * 4;
     size_t arena = (size_t)DPT_ARENA_ROWS * (8 * nt + 4);
     size_t slots = (size_t)DPT_PENDING * S;
-    return (rows + arena + slots + 15) & ~(size_t)15;
+    size_t tops = (size_t)DPT_PENDING * S * 4;
+    return (rows + arena + slots + tops + 15) & ~(size_t)15;
 }
 
 // grid workgroups of wpb waves; wave w walks candidates [w*chunk, (w+1)*chunk)

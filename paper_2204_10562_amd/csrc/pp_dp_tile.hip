@@ -72,6 +72,9 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     int *rows = (int *)mine;
     unsigned char *arena = mine + (size_t)S * RS * 4;
     unsigned char *slots = arena + (size_t)DPT_ARENA_ROWS * RB;  // [pending][S] arena row of row n
+    int *tops = (int *)(slots + (size_t)DPT_PENDING * S);        // [pending][S] key of cell (n, L)
+    const bool stages = a.g.stages != 0;
+    const int tri = S * (S + 1) / 2;
     long long *C_out = a.g.C_out;
     int *bounds_out = a.g.bounds_out;
     const int *ord = a.g.ord;
@@ -129,6 +132,8 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     int arena_used = 0;
     bool fresh = true;  // the arena was emptied: the next candidate must recompute every row
     int v_cur = 0;  // lane n: arena row holding the split indices of row n of the current path
+    // lane n: key of cell (n, L) of the current path, i.e. the result for n+1 stages
+    int v_tops = __builtin_amdgcn_readlane(Pl[NT - 1], top_lane);
 
     // Writes out C and the plans of all pending candidates, one per lane.
     auto flush = [&]() {
@@ -137,15 +142,22 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         const long long cq = pend0 + lane;
         const bool bad = live && v_top < 0;
         if (__ballot(bad) && lane == 0) pp_raise(a.g.status, PP_FAULT_ORDERING);
-        if (live) C_out[cq] = bad ? PP_INF64 : (long long)(v_top >> K);
-        int e = L;
-        for (int n = S - 1; n >= 0; --n) {
-            if (live) bounds_out[cq * S + n] = bad ? 0 : e;
-            if (n == 0) break;
-            // split index stored with cell (n, e): the key itself for the last row
-            int nxt = v_top & kmask;
-            if (n < S - 1 && live && !bad) nxt = arena[(int)slots[lane * S + n] * RB + e] & kmask;
-            e = (live && !bad) ? nxt : 0;
+        // xi = number of stages of the plan read back: S only, or every count 1..S
+        for (int xi = stages ? 1 : S; xi <= S; ++xi) {
+            int top = v_top;
+            if (xi < S && live && !bad) top = tops[lane * S + xi - 1];
+            const long long cat = stages ? cq * S + xi - 1 : cq;
+            if (live) C_out[cat] = bad ? PP_INF64 : (long long)(top >> K);
+            int *bo = bounds_out + (stages ? cq * tri + xi * (xi - 1) / 2 : cq * S);
+            int e = L;
+            for (int n = xi - 1; n >= 0; --n) {
+                if (live) bo[n] = bad ? 0 : e;
+                if (n == 0) break;
+                // split index stored with cell (n, e): the key itself for the plan's last row
+                int nxt = top & kmask;
+                if (n < xi - 1 && live && !bad) nxt = arena[(int)slots[lane * S + n] * RB + e] & kmask;
+                e = (live && !bad) ? nxt : 0;
+            }
         }
         pend0 += pending;
         pending = 0;
@@ -288,7 +300,8 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                 pairs += (unsigned long long)((L - n) * (L - n + 1) / 2);
                 ++nrows;
                 const int slot = arena_used++;
-                if (lane == n) v_cur = slot;
+                const int top_n = __builtin_amdgcn_readlane(acc[NT - 1], top_lane);
+                if (lane == n) { v_cur = slot; v_tops = top_n; }
                 if (lb == 0) {
                     unsigned char *arow = arena + slot * RB;
 #pragma unroll
@@ -312,6 +325,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                 // candidate finished: remember its key and the arena rows of its path
                 if (lane == pending) v_top = top;
                 if (lane < S) slots[pending * S + lane] = (unsigned char)v_cur;
+                if (stages && lane < S) tops[pending * S + lane] = v_tops;
                 ++pending;
             }
         };

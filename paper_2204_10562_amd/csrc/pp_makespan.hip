@@ -34,6 +34,16 @@ struct mk_args {
     const int *orderings;  // NULL = all D! orderings, candidate index = lexicographic rank
     const int *bounds;
     long long *T_out;      // [nM][N]; may be NULL when only the winners are wanted
+    // Where candidate c's data lie: devices at orderings[c*ord_stride + n], bounds at
+    // bounds[c*bnd_stride + bnd_off + n], T of microbatch count q at
+    // T_out[(q*N + c)*t_stride + t_off].  (ord_stride, bnd_stride, bnd_off, t_stride, t_off)
+    // = (S, S, 0, 1, 0) for plain lists; the stage-count search evaluates the plans with S = xi
+    // stages out of rows that hold search = S_max devices and all S_max plans.
+    int ord_stride, bnd_off, t_off;
+    long long bnd_stride, t_stride;
+    // search > 0 (arg-min only): the N entries are (candidate, stage count) pairs, entry
+    // i = c*search + xi-1; the record of the winner is decoded accordingly
+    int search;
     int32_t *status;
     // arg-min (all NULL when not wanted)
     tc_pair *part;         // [nM][waves]
@@ -68,15 +78,15 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
     if (live) {
         if (a.orderings) {
             for (int n = 0; n < S; ++n) {
-                int d = a.orderings[c * S + n];
+                int d = a.orderings[c * a.ord_stride + n];
                 bool bad = d < 0 || d >= D;
-                for (int q = 0; q < n; ++q) bad |= (a.orderings[c * S + q] == d);
+                for (int q = 0; q < n; ++q) bad |= (a.orderings[c * a.ord_stride + q] == d);
                 if (bad) fault |= PP_FAULT_ORDERING;
             }
         }
         int prev = 0;
         for (int n = 0; n < S; ++n) {
-            int e = a.bounds[c * S + n];
+            int e = a.bounds[c * a.bnd_stride + a.bnd_off + n];
             if (e <= prev || e > L) fault |= PP_FAULT_BOUNDS;
             prev = e;
         }
@@ -90,8 +100,8 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
     for (int n = 0; n < S; ++n) {
         long long F = 0, Bk = 0, cf = 0, cb = 0;
         if (live && !fault) {
-            int o_n = a.orderings ? a.orderings[c * S + n] : pp_unrank_next(D, n, rem, used);
-            int e = a.bounds[c * S + n];
+            int o_n = a.orderings ? a.orderings[c * a.ord_stride + n] : pp_unrank_next(D, n, rem, used);
+            int e = a.bounds[c * a.bnd_stride + a.bnd_off + n];
             F = a.PF[e] - a.PF[e_prev];
             Bk = a.PB[e] - a.PB[e_prev];
             if (n) {
@@ -129,7 +139,7 @@ __device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool 
                                      long long T, long long wave_id, long long n_waves) {
     if (live) {
         if (fault) { T = PP_INF64; pp_raise(a.status, fault); }
-        if (a.T_out) a.T_out[(long long)q * a.N + c] = T;
+        if (a.T_out) a.T_out[((long long)q * a.N + c) * a.t_stride + a.t_off] = T;
     }
     if (!a.part) return;
     tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
@@ -178,21 +188,29 @@ __device__ __forceinline__ void conclude(const mk_args &a, long long n_waves, lo
         }
         w = wave_tc_min(w);
         const bool none = w.T == PP_INF64;
+        // the winner: candidate c with xi stages, its C at C[at_c], its bounds from bounds[at_b]
+        long long c = w.c, at_c = w.c, at_b = w.c * a.bnd_stride + a.bnd_off;
+        int xi = S;
+        if (a.search && !none) {
+            c = w.c / a.search;
+            xi = (int)(w.c - c * a.search) + 1;
+            at_b = c * ((long long)a.search * (a.search + 1) / 2) + xi * (xi - 1) / 2;
+        }
         pp_result *out = a.out + q;
         if (lane == 0) {
-            out->best_index = none ? -1 : w.c;
+            out->best_index = none ? -1 : c;
             out->T = w.T;
-            out->C = none ? PP_INF64 : a.C[w.c];
-            out->S = S;
+            out->C = none ? PP_INF64 : a.C[at_c];
+            out->S = xi;
         }
-        // lane n writes bound n and device n (lanes S.. write zeros)
+        // lane n writes bound n and device n (lanes xi.. write zeros)
         int b = 0, o = 0;
-        if (lane < S && !none) {
-            b = a.bounds[w.c * S + lane];
+        if (lane < xi && !none) {
+            b = a.bounds[at_b + lane];
             if (a.orderings) {
-                o = a.orderings[w.c * S + lane];
+                o = a.orderings[c * a.ord_stride + lane];
             } else {
-                unsigned long long rem = (unsigned long long)w.c;
+                unsigned long long rem = (unsigned long long)c;
                 unsigned used = 0;
                 for (int n = 0; n <= lane; ++n) o = pp_unrank_next(a.D, n, rem, used);
             }
@@ -367,6 +385,34 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
+static void plain_layout(mk_args &a, int S) {
+    a.ord_stride = S; a.bnd_stride = S; a.bnd_off = 0; a.t_stride = 1; a.t_off = 0; a.search = 0;
+}
+
+// Lanes per workgroup of the LDS kernel: as many as keep 2J rows of int64 within 64 KiB.
+static int lds_lanes(int S) {
+    const int J = 4 * S - 3;
+    int W = 64;
+    while ((size_t)2 * J * W * 8 > 64 * 1024) W >>= 1;
+    return W;
+}
+
+// Register kernel for a.S <= 16, LDS kernel beyond.  With a.part set the LDS kernel must run
+// full waves (lds_lanes(a.S) == 64).
+static int launch_makespan(const mk_args &a, hipStream_t st) {
+    switch (a.S) {
+#define CASE(n) case n: return launch_regs<n>(a, st);
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+        CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
+#undef CASE
+    }
+    const int W = lds_lanes(a.S);
+    const size_t lds = (size_t)2 * (4 * a.S - 3) * W * 8;
+    unsigned grid = (unsigned)((a.N + W - 1) / W);
+    hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
 int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
@@ -379,20 +425,10 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;
     a.XF = (const long long *)XF; a.XB = (const long long *)XB;
     a.orderings = orderings; a.bounds = bounds;
+    plain_layout(a, S);
     a.T_out = (long long *)T_out; a.status = status;
     a.part = (tc_pair *)part; a.ticket = ticket; a.C = (const long long *)C; a.out = out;
-    switch (S) {
-#define CASE(n) case n: return launch_regs<n>(a, st);
-        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
-        CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
-#undef CASE
-    }
-    const int J = 4 * S - 3;
-    int W = 64;  // lanes per workgroup: as many as keep 2J rows of int64 within 64 KiB of LDS
-    while ((size_t)2 * J * W * 8 > 64 * 1024) W >>= 1;
-    size_t lds = (size_t)2 * J * W * 8;
-    unsigned grid = (unsigned)((N + W - 1) / W);
-    if (W != 64 && part) {
+    if (S > 16 && lds_lanes(S) != 64 && part) {
         // narrow workgroups: per microbatch count, T goes to memory and a separate pass finds
         // the minimum
         for (int q = 0; q < nM; ++q) {
@@ -401,34 +437,35 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
             b.part = NULL; b.ticket = NULL; b.C = NULL; b.out = NULL;
             b.T_out = T_out ? (long long *)T_out + (long long)q * N : (long long *)T_scratch;
             if (!b.T_out) return PP_ERR_INVALID_ARG;
-            hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, b);
-            if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
-            int rc = pp_launch_argmin(D, S, N, (const int64_t *)b.T_out, C, bounds, orderings, part,
-                                      ticket, out + q, st);
+            int rc = launch_makespan(b, st);
+            if (rc) return rc;
+            rc = pp_launch_argmin(D, S, N, (const int64_t *)b.T_out, C, bounds, orderings, part,
+                                  ticket, out + q, st);
             if (rc) return rc;
         }
         return PP_OK;
     }
-    hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, a);
-    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+    return launch_makespan(a, st);
 }
 
 // ---------------------------------------------------------------- stand-alone arg-min
 
-// Each wave reduces a strided share of T and then joins the same last-wave reduction.
+// Each wave reduces a strided share of T (blockIdx.y selects the microbatch count) and then
+// joins the same last-wave reduction.
 __global__ __launch_bounds__(64) void k_argmin(mk_args a) {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x, q = blockIdx.y;
+    const long long *T = a.T_out + (long long)q * a.N;
     tc_pair v = {PP_INF64, INT64_MAX};
     for (long long c = (long long)blockIdx.x * 64 + lane; c < a.N; c += (long long)gridDim.x * 64) {
-        tc_pair o = {a.T_out[c], c};
+        tc_pair o = {T[c], c};
         v = tc_min(v, o);
     }
     // emit() reduces over the wave: hand it this lane's minimum as if it were the lane's own
     // candidate; T_out must not be rewritten
     mk_args b = a;
     b.T_out = NULL;
-    emit(b, 0, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
-    conclude(b, gridDim.x, gridDim.x);
+    emit(b, q, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
+    conclude(b, gridDim.x, (long long)gridDim.x * gridDim.y);
 }
 
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
@@ -440,10 +477,45 @@ int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = 1;
     a.PF = a.PB = a.XF = a.XB = NULL;
     a.orderings = orderings; a.bounds = bounds;
+    plain_layout(a, S);
     a.T_out = (long long *)T; a.status = NULL;
     a.part = (tc_pair *)part; a.ticket = ticket; a.C = (const long long *)C; a.out = out;
     long long waves = (N + 63) / 64;
     if (waves > 1024) waves = 1024;
     hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves), dim3(64), 0, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+// ---------------------------------------------------------------- stage-count search
+
+int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int *Ms,
+                              const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                              const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
+                              const int64_t *C, int64_t *T_st, int32_t *status, void *part,
+                              unsigned *ticket, pp_result *out, hipStream_t st) {
+    mk_args a;
+    a.L = L; a.D = D; a.N = N; a.nM = nM;
+    for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
+    a.PF = (const long long *)PF; a.PB = (const long long *)PB;
+    a.XF = (const long long *)XF; a.XB = (const long long *)XB;
+    a.orderings = orderings; a.bounds = bounds;
+    a.T_out = (long long *)T_st; a.status = status;
+    a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL;
+    a.ord_stride = S; a.bnd_stride = (long long)S * (S + 1) / 2; a.t_stride = S; a.search = 0;
+    // one launch per stage count: the schedules of xi stages on the first xi devices
+    for (int xi = 1; xi <= S; ++xi) {
+        a.S = xi;
+        a.bnd_off = xi * (xi - 1) / 2;
+        a.t_off = xi - 1;
+        int rc = launch_makespan(a, st);
+        if (rc) return rc;
+    }
+    // smallest T over all (candidate, stage count) pairs, lowest c*S + xi-1 on ties
+    mk_args m = a;
+    m.S = S; m.N = N * S; m.search = S;
+    m.part = (tc_pair *)part; m.ticket = ticket; m.C = (const long long *)C; m.out = out;
+    long long waves = (m.N + 63) / 64;
+    if (waves > 1024) waves = 1024;
+    hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves, nM), dim3(64), 0, st, m);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }

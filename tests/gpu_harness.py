@@ -92,3 +92,32 @@ class GpuProblem:
         res = [pp.read_result(out, S, q) for q in range(nM)]
         return (self.take_status(), res, None if T is None else T.cpu().numpy().reshape(nM, N),
                 None if C is None else C.cpu().numpy())
+
+    def dp_stages(self, orderings="default", N=None, S=None):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        tri = S * (S + 1) // 2
+        o = self.orderings if isinstance(orderings, str) else orderings
+        C = torch.empty(N * S, dtype=torch.int64, device=self.dev)
+        bounds = torch.empty(N * tri, dtype=torch.int32, device=self.dev)
+        pp.pp_partition_dp_stages(w.L, w.D, S, N, self.PF, self.PB, self.XF, self.XB, o, C, bounds,
+                                  self.workspace(N, S), self.status)
+        return self.take_status(), C.cpu().numpy().reshape(N, S), bounds.cpu().numpy().reshape(N, tri)
+
+    def best_stages(self, Ms, orderings="default", N=None, S=None, want_all=True):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        nM = len(Ms)
+        need = pp.pp_workspace_bytes_stages(w.L, w.D, S, N, nM)
+        assert need > 0
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        out = torch.zeros(pp.RESULT_BYTES * nM, dtype=torch.uint8, device=self.dev)
+        T = torch.empty(N * S * nM, dtype=torch.int64, device=self.dev) if want_all else None
+        C = torch.empty(N * S, dtype=torch.int64, device=self.dev) if want_all else None
+        pp.pp_best_plan_stages(w.L, w.D, S, N, list(Ms), self.PF, self.PB, self.XF, self.XB, o, out,
+                               T, C, self.ws, self.status)
+        res = [pp.read_result(out, None, q) for q in range(nM)]
+        return (self.take_status(), res, None if T is None else T.cpu().numpy().reshape(nM, N, S),
+                None if C is None else C.cpu().numpy().reshape(N, S))
