@@ -113,6 +113,26 @@ def main():
     t_mk = {M: timed(lambda M=M: pp.pp_schedule_makespan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, bounds, T, g.status), reps) for M in Ms}
     t_multi = timed(lambda: pp.pp_best_plan_multi(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status), reps)
     t_best = {M: timed(lambda M=M: pp.pp_best_plan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status), reps) for M in Ms}
+    # the stage-count search (Alg. 3's outer loop) over the same candidates: not part of the step
+    ws_st = torch.empty(pp.pp_workspace_bytes_stages(L, D, S, N, len(Ms)), dtype=torch.uint8, device=dev)
+    C_st = torch.empty(N * S, dtype=torch.int64, device=dev)
+    b_st = torch.empty(N * (S * (S + 1) // 2), dtype=torch.int32, device=dev)
+    out_st = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
+    t_dp_st = timed(lambda: pp.pp_partition_dp_stages(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C_st, b_st, ws_st, g.status), reps)
+    t_stages = timed(lambda: pp.pp_best_plan_stages(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out_st, None, None, ws_st, g.status), reps)
+    stage_winner = pp.read_result(out_st, None, len(Ms) - 1)
+    del ws_st, C_st, b_st
+    # the recursive device ordering (Alg. 2) as one more candidate: where does it rank?
+    rdo = pp.pp_rdo_order(D, w.bw.reshape(-1).tolist())
+    T_all = torch.empty(N * len(Ms), dtype=torch.int64, device=dev)
+    pp.pp_best_plan_multi(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out, T_all, None, ws, g.status)
+    T_all = T_all.reshape(len(Ms), N)
+    o_rdo = torch.tensor(rdo[:S], dtype=torch.int32, device=dev)
+    out1 = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
+    T_rdo = torch.empty(len(Ms), dtype=torch.int64, device=dev)
+    pp.pp_best_plan_multi(L, D, S, 1, Ms, g.PF, g.PB, g.XF, g.XB, o_rdo, out1, T_rdo, None, ws, g.status)
+    rdo_rank = [(int(T_rdo[q].item()), int((T_all[q] < T_rdo[q]).sum().item()), int(T_all[q].min().item())) for q in range(len(Ms))]
+    del T_all
     assert int(g.status.item()) == 0
     # what the DP really evaluated (rows shared by consecutive candidates are computed once)
     pp.pp_partition_dp(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C, bounds, ws, g.status)
@@ -133,6 +153,12 @@ def main():
     log("  pp_best_plan_multi     %9.1f us   %.3e plans/s" % (t_multi * 1e6, N * len(Ms) / t_multi))
     log("  whole step             %9.1f us   %.3e plans/s" % (ms_per_step * 1e3, plans_per_s))
     log("  winner:", winner)
+    log("  stage-count search (not in the step): pp_partition_dp_stages %.1f us, pp_best_plan_stages %.1f us = %.3e (candidate, stage count, M) plans/s"
+        % (t_dp_st * 1e6, t_stages * 1e6, N * S * len(Ms) / t_stages))
+    log("     winner over stage counts 1..%d for M=%d:" % (S, Ms[-1]), stage_winner)
+    for M, (t, better, tmin) in zip(Ms, rdo_rank):
+        log("  recursive device ordering %s, M=%d: T=%d, %d of %d candidates are faster (best T=%d, +%.2f%%)"
+            % (rdo[:S], M, t, better, N, tmin, 100.0 * (t - tmin) / tmin))
 
     cpu = None
     if not args.no_cpu_baseline:
