@@ -260,6 +260,8 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         if (lds_wave * wpb > 64 * 1024) return PP_ERR_INVALID_ARG;  // cannot happen for S <= 64
         t.hoist = 1;
         if (const char *e = getenv("PP_DP_HOIST")) t.hoist = atoi(e) != 0;
+        t.prio = 1;
+        if (const char *e = getenv("PP_DP_PRIO")) t.prio = atoi(e) != 0;
         int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
         if (!t.hoist) waves_per_simd = 4;
         if (const char *e = getenv("PP_DP_WPS")) { int v = atoi(e); if (v >= 1 && v <= 8) waves_per_simd = v; }

@@ -13,6 +13,7 @@ struct dp_tile_args {
     long long chunk;  // consecutive candidates walked by one wave
     int validate;     // orderings came from the caller: check them
     int hoist;        // keep the candidate-independent difference keys in registers
+    int prio;         // waves raise their issue priority with the share of their chunk still to do
     const int *xkt;   // [link][b][j] keys ((XF+XB) << K) | k for k = 8j+b, infinite if k == 0 or k >= L
     dp_args g;        // tables, outputs and the generic fallback's arguments
 };

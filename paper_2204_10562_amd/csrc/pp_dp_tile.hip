@@ -236,6 +236,15 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         // c is a valid candidate whose rows first..S-1 are to be computed; xk holds (or is
         // about to receive) the channel keys of row `first`
         fresh = false;
+        if (a.prio) {
+            // Of the waves that share a SIMD the one with the larger share of its chunk still to
+            // do issues first, so that they finish together and none runs alone at the end.
+            const int left = (int)(((c1 - c) * 4) / a.chunk);
+            if (left >= 3) __builtin_amdgcn_s_setprio(3);
+            else if (left == 2) __builtin_amdgcn_s_setprio(2);
+            else if (left == 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         const bool more = c + 1 < c1;
         int v_on = (more && lane < S) ? ord[(c + 1) * S + lane] : 0;
         int first_n = -2, v_link_n = 0;  // next candidate: -2 none, -1 bad ordering
