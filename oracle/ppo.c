@@ -696,3 +696,249 @@ int ppo_rdo_order(int D, const int64_t *bw, int32_t *order_out) {
     free(verts);
     return rc;
 }
+
+/* ------------------------------------------------------------------ */
+/* Partition, replication and mapping (PRM, Alg. 4) and the complete    */
+/* planner (SPP, Alg. 3) with replicated stages                         */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    int L, D, M;
+    const int64_t *PF, *PB, *PA;     /* prefix sums of p^f, p^b, alpha (length L+1) */
+    const int64_t *actf, *actb, *bw; /* d^f, d^b per boundary; bandwidth matrix      */
+    const int32_t *o;                /* device of rank 0..D-1                        */
+    int64_t *memo;                   /* W(l, xi, r, n) or -1                         */
+    int32_t *arg_l, *arg_r;          /* minimising (l', r')                          */
+} prm_ctx;
+
+static size_t prm_at(const prm_ctx *x, int l, int n, int xi, int r) {
+    const size_t d1 = (size_t)x->D + 1;
+    return (((size_t)l * d1 + n) * d1 + xi) * d1 + r;
+}
+
+/* min of b_{u,v} over u in ranks [a0,a1), v in ranks [b0,b1), u != v */
+static int64_t min_bw(const prm_ctx *x, int a0, int a1, int b0, int b1) {
+    int64_t m = INF;
+    for (int u = a0; u < a1; ++u)
+        for (int v = b0; v < b1; ++v)
+            if (u != v) {
+                int64_t b = x->bw[(size_t)x->o[u] * x->D + x->o[v]];
+                if (b < m) m = b;
+            }
+    return m;
+}
+
+/* Eq. 1: ring AllReduce of layers [l0, l1) replicated over ranks [n-r, n) */
+static int64_t allreduce_time(const prm_ctx *x, int l0, int l1, int r, int n) {
+    if (r == 1) return 0;
+    int64_t b = min_bw(x, n - r, n, n - r, n);
+    return ceil_div(2 * (int64_t)(r - 1) * (x->PA[l1] - x->PA[l0]), (int64_t)r * b);
+}
+
+/* per-microbatch forward / backward time of layers [l0, l1) on r replicas: p / k */
+static int64_t rep_fwd(const prm_ctx *x, int l0, int l1, int r) { return ceil_div(x->PF[l1] - x->PF[l0], r); }
+static int64_t rep_bwd(const prm_ctx *x, int l0, int l1, int r) { return ceil_div(x->PB[l1] - x->PB[l0], r); }
+
+/* c^f, c^b (Sec. III-B) across the boundary after layer lp-1: stage on ranks
+ * [n-r-rp, n-r) with rp replicas feeds the stage on ranks [n-r, n) with r replicas */
+static int64_t rep_cf(const prm_ctx *x, int lp, int rp, int r, int n) {
+    int64_t b = min_bw(x, n - r - rp, n - r, n - r, n);
+    return ceil_div(x->actf[lp - 1], (int64_t)rp * r * b);
+}
+static int64_t rep_cb(const prm_ctx *x, int lp, int rp, int r, int n) {
+    int64_t b = min_bw(x, n - r, n, n - r - rp, n - r);
+    return ceil_div(x->actb[lp - 1], (int64_t)rp * r * b);
+}
+
+/* W(l, xi, r, n): first l layers in xi stages on ranks 0..n-1, last stage on r replicas */
+static int64_t prm(prm_ctx *x, int l, int n, int xi, int r) {
+    if (l < xi || n < xi) return INF;
+    size_t at = prm_at(x, l, n, xi, r);
+    if (x->memo[at] >= 0) return x->memo[at];
+    int64_t best = INF;
+    int bl = 0, br = 0;
+    if (xi == 1 && r == n) {
+        best = x->M * (rep_fwd(x, 0, l, n) + rep_bwd(x, 0, l, n)) + allreduce_time(x, 0, l, n, n);
+    } else if (xi == 1 || r == n) {
+        best = INF;
+    } else {
+        for (int lp = 1; lp <= l - 1; ++lp)
+            for (int rp = 1; rp <= n - r; ++rp) {
+                int64_t w = prm(x, lp, n - r, xi - 1, rp);
+                if (w == INF) continue; /* max{INF, ...} never improves */
+                int64_t comm = x->M * (rep_cf(x, lp, rp, r, n) + rep_cb(x, lp, rp, r, n));
+                int64_t last = x->M * (rep_fwd(x, lp, l, r) + rep_bwd(x, lp, l, r)) +
+                               allreduce_time(x, lp, l, r, n);
+                int64_t t = max2(w, max2(comm, last));
+                if (best > t) {
+                    best = t;
+                    bl = lp;
+                    br = rp;
+                }
+            }
+    }
+    x->memo[at] = best;
+    x->arg_l[at] = bl;
+    x->arg_r[at] = br;
+    return best;
+}
+
+/* T of a plan with replicated stages: Alg. 1 on the stages' per-replica times, then Eq. 2:
+ * an AllReduce starts when the stage's last backward pass has finished. */
+static int64_t rep_makespan(const prm_ctx *x, int S, const int32_t *bounds, const int32_t *reps) {
+    int64_t F[PPO_MAX_STAGES], B[PPO_MAX_STAGES], cf[PPO_MAX_STAGES], cb[PPO_MAX_STAGES];
+    int64_t A[PPO_MAX_STAGES];
+    int M = x->M, n = 0, l0 = 0;
+    for (int s = 0; s < S; ++s) {
+        int r = reps[s], l1 = bounds[s];
+        n += r;
+        F[s] = rep_fwd(x, l0, l1, r);
+        B[s] = rep_bwd(x, l0, l1, r);
+        A[s] = allreduce_time(x, l0, l1, r, n);
+        cf[s] = cb[s] = 0;
+        if (s) {
+            cf[s] = rep_cf(x, l0, reps[s - 1], r, n);
+            cb[s] = rep_cb(x, l0, reps[s - 1], r, n);
+        }
+        l0 = l1;
+    }
+    const int R = 2 * S - 1, J = 2 * R - 1;
+    int64_t *fin = (int64_t *)malloc((size_t)J * M * sizeof(int64_t));
+    if (!fin) return -1;
+    int64_t T = ppo_pe_makespan(S, M, F, B, cf, cb, NULL, fin);
+    for (int s = 0; s < S && T >= 0; ++s) {
+        if (reps[s] == 1) continue;
+        /* last backward block of stage s: block 2R - (2s+1), or the merged block R */
+        int j = s == S - 1 ? R : 2 * R - (2 * s + 1);
+        int64_t done = 0;
+        for (int m = 0; m < M; ++m) done = max2(done, fin[(size_t)(j - 1) * M + m]);
+        T = max2(T, done + A[s]);
+    }
+    free(fin);
+    return T;
+}
+
+int ppo_spp_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
+                       const int64_t *bwd_us, const int64_t *act_fwd_bytes,
+                       const int64_t *act_bwd_bytes, const int64_t *alpha_bytes,
+                       const int64_t *bw, const int32_t *orderings, ppo_rep_result *out,
+                       int64_t *T_all, int64_t *W_all, int32_t *bounds_all, int32_t *reps_all) {
+    if (L < 1 || D < 1 || D > PPO_MAX_STAGES || N < 1 || M < 1 || !fwd_us || !bwd_us ||
+        !act_fwd_bytes || !alpha_bytes || !bw || !out)
+        return PPO_ERR_INVALID_ARG;
+    if (!act_bwd_bytes) act_bwd_bytes = act_fwd_bytes;
+    if (!orderings && factorial_or_neg(D) != N) return PPO_ERR_INVALID_ARG;
+    int fault = 0;
+    for (int l = 0; l < L; ++l) {
+        if (fwd_us[l] < 0 || bwd_us[l] < 0 || alpha_bytes[l] < 0) fault |= PPO_FAULT_NEGATIVE;
+        if (l + 1 < L && (act_fwd_bytes[l] < 0 || act_bwd_bytes[l] < 0)) fault |= PPO_FAULT_NEGATIVE;
+    }
+    for (int u = 0; u < D; ++u)
+        for (int v = 0; v < D; ++v)
+            if (u != v && bw[(size_t)u * D + v] <= 0) fault |= PPO_FAULT_BANDWIDTH;
+    int32_t *own = NULL;
+    if (!orderings) {
+        own = all_orderings(D, N);
+        if (!own) return PPO_ERR_NOMEM;
+        orderings = own;
+    }
+    for (int64_t c = 0; c < N && !fault; ++c)
+        if (!ordering_ok(orderings + c * D, D, D)) fault |= PPO_FAULT_ORDERING;
+    int64_t *PF = (int64_t *)calloc((size_t)L + 1, sizeof(int64_t));
+    int64_t *PB = (int64_t *)calloc((size_t)L + 1, sizeof(int64_t));
+    int64_t *PA = (int64_t *)calloc((size_t)L + 1, sizeof(int64_t));
+    const int tri = D * (D + 1) / 2;
+    int64_t *T = (int64_t *)malloc((size_t)N * D * sizeof(int64_t));
+    int64_t *W = (int64_t *)malloc((size_t)N * D * sizeof(int64_t));
+    int32_t *bd = (int32_t *)calloc((size_t)N * tri, sizeof(int32_t));
+    int32_t *rp = (int32_t *)calloc((size_t)N * tri, sizeof(int32_t));
+    if (!PF || !PB || !PA || !T || !W || !bd || !rp) fault = PPO_ERR_NOMEM;
+    if (fault == 0) {
+        for (int l = 0; l < L; ++l) {
+            PF[l + 1] = PF[l] + fwd_us[l];
+            PB[l + 1] = PB[l] + bwd_us[l];
+            PA[l + 1] = PA[l] + alpha_bytes[l];
+            /* M * (time) and 2 (r-1) * (parameter bytes) must stay far from 2^63 */
+            if (PF[l + 1] + PB[l + 1] >= CAP / ((int64_t)M + 4 * D) || PA[l + 1] >= CAP / (2 * D))
+                fault |= PPO_FAULT_OVERFLOW;
+        }
+    }
+    int nomem = 0;
+    if (fault == 0) {
+        const size_t states = ((size_t)L + 1) * (D + 1) * (D + 1) * (D + 1);
+#pragma omp parallel for schedule(dynamic, 1) num_threads(ppo_get_num_threads())
+        for (int64_t c = 0; c < N; ++c) {
+            prm_ctx x = {L, D, M, PF, PB, PA, act_fwd_bytes, act_bwd_bytes, bw, orderings + c * D,
+                         NULL, NULL, NULL};
+            x.memo = (int64_t *)malloc(states * sizeof(int64_t));
+            x.arg_l = (int32_t *)malloc(states * sizeof(int32_t));
+            x.arg_r = (int32_t *)malloc(states * sizeof(int32_t));
+            if (!x.memo || !x.arg_l || !x.arg_r) {
+                nomem = 1;
+            } else {
+                for (size_t i = 0; i < states; ++i) x.memo[i] = -1;
+                /* Alg. 3: for every stage count, the replication of the last stage with the
+                 * smallest W (first such r), its plan, and the plan's schedule */
+                for (int xi = 1; xi <= D; ++xi) {
+                    int64_t wbest = INF;
+                    int rbest = 0;
+                    for (int r = 1; r <= D; ++r) {
+                        int64_t w = prm(&x, L, D, xi, r);
+                        if (w < wbest) {
+                            wbest = w;
+                            rbest = r;
+                        }
+                    }
+                    W[c * D + xi - 1] = wbest;
+                    T[c * D + xi - 1] = INF;
+                    if (wbest == INF) continue;
+                    int32_t *b = bd + c * tri + xi * (xi - 1) / 2;
+                    int32_t *k = rp + c * tri + xi * (xi - 1) / 2;
+                    int l = L, n = D, r = rbest;
+                    for (int s = xi - 1; s >= 0; --s) {
+                        b[s] = l;
+                        k[s] = r;
+                        size_t at = prm_at(&x, l, n, s + 1, r);
+                        int lp = x.arg_l[at], rq = x.arg_r[at];
+                        n -= r;
+                        l = lp;
+                        r = rq;
+                    }
+                    int64_t t = rep_makespan(&x, xi, b, k);
+                    if (t < 0) nomem = 1;
+                    else T[c * D + xi - 1] = t;
+                }
+            }
+            free(x.memo); free(x.arg_l); free(x.arg_r);
+        }
+        if (nomem) fault = PPO_ERR_NOMEM;
+    }
+    if (fault == 0) {
+        /* keep-the-minimum with strict '<': candidates in index order, stage counts 1, 2, ... */
+        int64_t T_best = INF, best = -1;
+        int xi_best = 0;
+        for (int64_t c = 0; c < N; ++c)
+            for (int xi = 1; xi <= D; ++xi)
+                if (T[c * D + xi - 1] < T_best) {
+                    T_best = T[c * D + xi - 1];
+                    best = c;
+                    xi_best = xi;
+                }
+        memset(out, 0, sizeof(*out));
+        out->best_index = best;
+        out->T = T_best;
+        out->S = xi_best;
+        out->W = best >= 0 ? W[best * D + xi_best - 1] : INF;
+        for (int n = 0; n < D && best >= 0; ++n) out->order[n] = orderings[best * D + n];
+        for (int s = 0; s < xi_best && best >= 0; ++s) {
+            out->bounds[s] = bd[best * tri + xi_best * (xi_best - 1) / 2 + s];
+            out->reps[s] = rp[best * tri + xi_best * (xi_best - 1) / 2 + s];
+        }
+        if (T_all) memcpy(T_all, T, (size_t)N * D * sizeof(int64_t));
+        if (W_all) memcpy(W_all, W, (size_t)N * D * sizeof(int64_t));
+        if (bounds_all) memcpy(bounds_all, bd, (size_t)N * tri * sizeof(int32_t));
+        if (reps_all) memcpy(reps_all, rp, (size_t)N * tri * sizeof(int32_t));
+    }
+    free(PF); free(PB); free(PA); free(T); free(W); free(bd); free(rp); free(own);
+    return fault;
+}

@@ -106,6 +106,42 @@ int ppo_best_plan_stages(int L, int D, int S, int64_t N, int M, const int64_t *P
                          const int32_t *orderings, ppo_result *out, int64_t *T_all,
                          int64_t *C_all, int32_t *bounds_all);
 
+/* The complete planner with replicated stages, for every candidate ordering of
+ * all D devices (Alg. 3 with Alg. 4 and Alg. 1; the ordering is given instead
+ * of computed by Alg. 2).
+ *   PRM (Alg. 4, recursion for W(l, xi, r, i) in Sec. IV-B): memoised recursion
+ *   written as the listing: base case one stage replicated over all i GPUs,
+ *   otherwise min over l' = 1..l-1 and r' = 1..i-r (in this order, replaced only
+ *   on strict improvement) of the max of the sub-problem, the channel and the
+ *   last stage.  Integer readings: a stage of r replicas takes
+ *   ceil(sum p^f / r) forward and ceil(sum p^b / r) backward per microbatch;
+ *   c^f = ceil(d^f / (r' r min b_{v',v})), c^b = ceil(d^b / (r' r min b_{v,v'}))
+ *   (v' in the earlier stage); A = ceil(2 (r-1) sum alpha / (r min b)) over
+ *   the ordered pairs of the replica set (Eq. 1), 0 for r = 1; the stage term
+ *   is M (F + B) + A and the channel term M (c^f + c^b).
+ *   SPP (Alg. 3): for xi = 1..D: r = first minimiser of W(L, xi, r, D); plan;
+ *   T = max(T_PE, max over replicated stages of (end of its last backward pass
+ *   + A)) (Eq. 2, Alg. 1 on the per-replica times); keep the smallest T,
+ *   strict '<', candidates in index order and xi ascending.
+ *   alpha_bytes [L]; orderings [N*D] or NULL = all D! in lexicographic order.
+ *   T_all, W_all [N*D] at c*D + xi-1 (INT64_MAX = no plan with xi stages);
+ *   bounds_all, reps_all [N*D(D+1)/2], the xi entries of (c, xi) at
+ *   c*D(D+1)/2 + xi(xi-1)/2.  All optional. */
+typedef struct {
+    int64_t best_index, T, W;
+    int32_t S;
+    int32_t bounds[PPO_MAX_STAGES]; /* S entries */
+    int32_t reps[PPO_MAX_STAGES];   /* S entries, sum = D */
+    int32_t order[PPO_MAX_STAGES];  /* D entries: device of every rank */
+} ppo_rep_result;
+
+int ppo_spp_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
+                       const int64_t *bwd_us, const int64_t *act_fwd_bytes,
+                       const int64_t *act_bwd_bytes, const int64_t *alpha_bytes,
+                       const int64_t *bw_bytes_per_us, const int32_t *orderings,
+                       ppo_rep_result *out, int64_t *T_all, int64_t *W_all,
+                       int32_t *bounds_all, int32_t *reps_all);
+
 /* Execution-ordering phase of Alg. 1 alone, for a pipeline of S stages and
  * M microbatches.  rounds_out[t*(4S-3) + (j-1)] = microbatch (1-based) that
  * block j handles in sweep t, or 0.  Returns the number of sweeps, or a

@@ -71,6 +71,18 @@ def _i32(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
 
 
+class RepResult(ctypes.Structure):
+    _fields_ = [
+        ("best_index", ctypes.c_int64),
+        ("T", ctypes.c_int64),
+        ("W", ctypes.c_int64),
+        ("S", ctypes.c_int32),
+        ("bounds", ctypes.c_int32 * MAX_STAGES),
+        ("reps", ctypes.c_int32 * MAX_STAGES),
+        ("order", ctypes.c_int32 * MAX_STAGES),
+    ]
+
+
 def set_num_threads(n):
     lib().ppo_set_num_threads(ctypes.c_int(int(n)))
 
@@ -146,6 +158,29 @@ def best_plan_stages(L, D, S, N, M, PF, PB, XF, XB, orderings):
                bounds=[int(res.bounds[i]) for i in range(xi)],
                order=[int(res.order[i]) for i in range(xi)])
     return rc, out, T_all, C_all, b_all
+
+
+def spp_replicated(L, D, N, M, fwd, bwd, actf, actb, alpha, bw, orderings):
+    """-> (status, dict(best_index, T, W, S, bounds, reps, order), T_all[N,D], W_all[N,D],
+    bounds_all[N, D(D+1)/2], reps_all[N, D(D+1)/2])"""
+    orderings = _i32(orderings)
+    res = RepResult()
+    tri = D * (D + 1) // 2
+    T_all = np.empty((N, D), np.int64)
+    W_all = np.empty((N, D), np.int64)
+    b_all = np.empty((N, tri), np.int32)
+    r_all = np.empty((N, tri), np.int32)
+    actb = None if actb is None else _i64(actb)
+    rc = lib().ppo_spp_replicated(L, D, ctypes.c_int64(N), M, _p(_i64(fwd)), _p(_i64(bwd)),
+                                  _p(_i64(actf)), _p(actb), _p(_i64(alpha)), _p(_i64(bw)),
+                                  _p(orderings), ctypes.byref(res), _p(T_all), _p(W_all),
+                                  _p(b_all), _p(r_all))
+    xi = int(res.S)
+    out = dict(best_index=int(res.best_index), T=int(res.T), W=int(res.W), S=xi,
+               bounds=[int(res.bounds[i]) for i in range(xi)],
+               reps=[int(res.reps[i]) for i in range(xi)],
+               order=[int(res.order[i]) for i in range(D)])
+    return rc, out, T_all, W_all, b_all, r_all
 
 
 def execution_order(S, M):
