@@ -230,6 +230,60 @@ int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM,
                         int32_t *status, void *stream);
 
 /*
+ * The complete planner with replicated stages (Alg. 3 with Alg. 4 and Alg. 1)
+ * for a batch of orderings of ALL D devices.  A stage may run on k GPUs of
+ * consecutive ranks (Sec. III-B): a replica then takes ceil(sum p / k) per
+ * microbatch and pass, a transfer between stages of k' and k replicas
+ * ceil(d / (k' k min b)) per direction (minimum over the links from the
+ * sending to the receiving GPU set), and a replicated stage ends with a ring
+ * AllReduce of A = ceil(2 (k-1) sum alpha / (k min b)) (Eq. 1; minimum over the
+ * ordered pairs of its GPUs; 0 for k = 1).
+ *   PRM (Alg. 4; recursion for W(l, xi, r, i) of Sec. IV-B):
+ *     W(l, 1, i, i)  = M (F + B) + A,   layers [0, l) on ranks 0..i-1
+ *     W(l, xi, r, i) = min over l' = xi-1..l-1 and r' = 1..i-r of
+ *                      max{ W(l', xi-1, r', i-r), M (c^f + c^b), M (F + B) + A }
+ *     the first minimiser in (l', r') order is kept (strict-improvement update).
+ *   SPP (Alg. 3), per candidate: for xi = 1..D the first r with the smallest
+ *     W(L, xi, r, D), its plan, and the plan's T = max(end of the last backward
+ *     block on stage 0 under Alg. 1, end of the last AllReduce) (Eq. 2, an
+ *     AllReduce starts when its stage's last backward pass has finished); then
+ *     keep-the-minimum with strict '<': smallest T, then lowest candidate, then
+ *     fewest stages.
+ *   fwd_us, bwd_us, act_fwd_bytes, act_bwd_bytes (NULL = forward's), alpha_bytes
+ *   [L]; bw_bytes_per_us [D*D]; orderings [N*D] or NULL = all D! orderings in
+ *   lexicographic order (N = D!).
+ *   out      one pp_rep_result
+ *   T_all, W_all  [N*D]: value of (c, xi) at c*D + xi-1, INT64_MAX where no plan
+ *                 with xi stages exists (xi > L); either may be NULL
+ *   bounds_all, reps_all  [N*D(D+1)/2]: the xi entries of (c, xi) at
+ *                 c*D(D+1)/2 + xi(xi-1)/2; either may be NULL
+ *   workspace     pp_workspace_bytes_replicated(L, D, N) bytes, 256-byte aligned
+ * Limits: D <= 16 and (36 + 8 D)(L + 1) + 64 <= 65536 (the tables of one state
+ * live in LDS): L <= 653 at D = 8, L <= 398 at D = 16; otherwise
+ * PP_ERR_INVALID_ARG (pp_workspace_bytes_replicated returns 0);
+ * sums of times * (M + 4D) and of parameter sizes * 2D below 2^62.
+ * Faults: NEGATIVE, BANDWIDTH, ORDERING, OVERFLOW.
+ */
+typedef struct {
+    int64_t best_index; /* lowest candidate index with the minimum T; -1 if none */
+    int64_t T;          /* its per-iteration time (us)                           */
+    int64_t W;          /* its W(|S|) (us)                                        */
+    int32_t S;          /* its number of stages                                  */
+    int32_t bounds[PP_MAX_STAGES]; /* entries 0..S-1                             */
+    int32_t reps[PP_MAX_STAGES];   /* GPUs per stage, entries 0..S-1, sum = D    */
+    int32_t order[PP_MAX_STAGES];  /* device of every rank, entries 0..D-1      */
+} pp_rep_result;
+
+size_t pp_workspace_bytes_replicated(int L, int D, int64_t N);
+int pp_plan_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
+                       const int64_t *bwd_us, const int64_t *act_fwd_bytes,
+                       const int64_t *act_bwd_bytes, const int64_t *alpha_bytes,
+                       const int64_t *bw_bytes_per_us, const int32_t *orderings,
+                       pp_rep_result *out, int64_t *T_all, int64_t *W_all,
+                       int32_t *bounds_all, int32_t *reps_all, void *workspace,
+                       size_t workspace_bytes, int32_t *status, void *stream);
+
+/*
  * Recursive device ordering (Alg. 2, Sec. IV-B): one heuristic ordering of the
  * D devices, meant as an extra candidate row (or the only one when D! is out
  * of reach).  HOST function, host pointers, no GPU work: the device graph is

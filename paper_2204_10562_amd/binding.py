@@ -25,7 +25,8 @@ PP_MAX_STAGES = 64
 
 EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
            "pp_best_plan", "pp_best_plan_multi", "pp_workspace_bytes_stages", "pp_partition_dp_stages",
-           "pp_best_plan_stages", "pp_rdo_order", "pp_strerror")
+           "pp_best_plan_stages", "pp_workspace_bytes_replicated", "pp_plan_replicated", "pp_rdo_order",
+           "pp_strerror")
 
 
 class PPResult(ctypes.Structure):
@@ -39,7 +40,20 @@ class PPResult(ctypes.Structure):
     ]
 
 
+class PPRepResult(ctypes.Structure):
+    _fields_ = [
+        ("best_index", ctypes.c_int64),
+        ("T", ctypes.c_int64),
+        ("W", ctypes.c_int64),
+        ("S", ctypes.c_int32),
+        ("bounds", ctypes.c_int32 * PP_MAX_STAGES),
+        ("reps", ctypes.c_int32 * PP_MAX_STAGES),
+        ("order", ctypes.c_int32 * PP_MAX_STAGES),
+    ]
+
+
 RESULT_BYTES = ctypes.sizeof(PPResult)
+REP_RESULT_BYTES = ctypes.sizeof(PPRepResult)
 _lib = None
 
 
@@ -76,6 +90,10 @@ def lib():
         L.pp_partition_dp_stages.restype = i32
         L.pp_best_plan_stages.argtypes = L.pp_best_plan_multi.argtypes
         L.pp_best_plan_stages.restype = i32
+        L.pp_workspace_bytes_replicated.argtypes = [i32, i32, i64]
+        L.pp_workspace_bytes_replicated.restype = sz
+        L.pp_plan_replicated.argtypes = [i32, i32, i64, i32] + [vp] * 12 + [vp, sz, vp, vp]
+        L.pp_plan_replicated.restype = i32
         L.pp_rdo_order.argtypes = [i32, vp, vp]
         L.pp_rdo_order.restype = i32
         L.pp_strerror.argtypes = [i32]
@@ -203,6 +221,38 @@ def pp_best_plan_stages(L, D, S, N, M_list, PF, PB, XF, XB, orderings, out, T_al
         _ptr(C_all, i64, N * S, "C_all", optional=True),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
         _ptr(status, i32, 1, "status"), _stream()))
+
+
+def pp_workspace_bytes_replicated(L, D, N):
+    return int(lib().pp_workspace_bytes_replicated(L, D, N))
+
+
+def pp_plan_replicated(L, D, N, M, fwd_us, bwd_us, act_fwd_bytes, act_bwd_bytes, alpha_bytes,
+                       bw_bytes_per_us, orderings, out, T_all, W_all, bounds_all, reps_all, workspace,
+                       status):
+    i64, i32 = torch.int64, torch.int32
+    tri = D * (D + 1) // 2
+    _check(lib().pp_plan_replicated(
+        L, D, N, M, _ptr(fwd_us, i64, L, "fwd_us"), _ptr(bwd_us, i64, L, "bwd_us"),
+        _ptr(act_fwd_bytes, i64, L, "act_fwd_bytes"),
+        _ptr(act_bwd_bytes, i64, L, "act_bwd_bytes", optional=True),
+        _ptr(alpha_bytes, i64, L, "alpha_bytes"), _ptr(bw_bytes_per_us, i64, D * D, "bw_bytes_per_us"),
+        _ptr(orderings, i32, N * D, "orderings", optional=True),
+        _ptr(out, torch.uint8, REP_RESULT_BYTES, "out"),
+        _ptr(T_all, i64, N * D, "T_all", optional=True), _ptr(W_all, i64, N * D, "W_all", optional=True),
+        _ptr(bounds_all, i32, N * tri, "bounds_all", optional=True),
+        _ptr(reps_all, i32, N * tri, "reps_all", optional=True),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+def read_rep_result(out, D):
+    """Copy a device pp_rep_result (uint8 tensor) to the host and unpack it."""
+    r = PPRepResult.from_buffer_copy(bytes(out.cpu().numpy().tobytes()[:REP_RESULT_BYTES]))
+    S = int(r.S)
+    return dict(best_index=int(r.best_index), T=int(r.T), W=int(r.W), S=S,
+                bounds=[int(r.bounds[i]) for i in range(S)], reps=[int(r.reps[i]) for i in range(S)],
+                order=[int(r.order[i]) for i in range(D)])
 
 
 def pp_rdo_order(D, bw_bytes_per_us):

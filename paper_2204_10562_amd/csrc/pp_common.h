@@ -10,7 +10,7 @@
 #define PP_INF32 0x7fffffff
 #define PP_CAP62 ((long long)1 << 62)
 
-static inline size_t pp_align256(size_t x) { return (x + 255) & ~(size_t)255; }
+__host__ __device__ static inline size_t pp_align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Number of key bits that hold a split index 0..L-1.
 static inline int pp_index_bits(int L) {
@@ -123,6 +123,14 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
                               unsigned *ticket, pp_result *out, hipStream_t st);
+// Makespan (Eq. 2) of the plans with replicated stages of every (candidate, stage count) and
+// the keep-the-minimum over them; arrays laid out as pp_plan_replicated documents.  *ticket
+// (65 counters) must be 0 when the last kernel starts.
+int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, const int64_t *PB,
+                           const int64_t *PA, const int64_t *actf, const int64_t *actb,
+                           const int64_t *bw, const int32_t *orderings, const int32_t *bounds,
+                           const int32_t *reps, const int64_t *W, int64_t *T_out, int32_t *status,
+                           void *part, unsigned *ticket, pp_rep_result *out, hipStream_t st);
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
                      unsigned *ticket, pp_result *out, hipStream_t st);

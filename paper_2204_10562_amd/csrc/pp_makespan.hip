@@ -45,6 +45,12 @@ struct mk_args {
     // i = c*search + xi-1; the record of the winner is decoded accordingly
     int search;
     int32_t *status;
+    // replicated stages (k_rep_makespan and the record of its arg-min; NULL otherwise): replica
+    // counts laid out like bounds, prefix sums of the parameter sizes, activation sizes, the
+    // bandwidth matrix, and W per (candidate, stage count) (PP_INF64 = no such plan)
+    const int *reps;
+    const long long *PA, *actf, *actb, *bw, *W;
+    pp_rep_result *rout;   // [nM] winner records with replica counts (instead of out)
     // arg-min (all NULL when not wanted)
     tc_pair *part;         // [nM][waves]
     unsigned *ticket;      // 1 + 64 counters, all 0 when the kernel starts and again when it ends
@@ -196,6 +202,21 @@ __device__ __forceinline__ void conclude(const mk_args &a, long long n_waves, lo
             xi = (int)(w.c - c * a.search) + 1;
             at_b = c * ((long long)a.search * (a.search + 1) / 2) + xi * (xi - 1) / 2;
         }
+        if (a.rout) {
+            // plan with replicated stages: xi bounds and replica counts, all D devices by rank
+            pp_rep_result *out = a.rout + q;
+            if (lane == 0) {
+                out->best_index = none ? -1 : c;
+                out->T = w.T;
+                out->W = none ? PP_INF64 : a.C[at_c];
+                out->S = none ? 0 : xi;
+            }
+            const bool in = lane < xi && !none;
+            out->bounds[lane] = in ? a.bounds[at_b + lane] : 0;
+            out->reps[lane] = in ? a.reps[at_b + lane] : 0;
+            out->order[lane] = (lane < a.D && !none) ? a.orderings[c * a.ord_stride + lane] : 0;
+            continue;
+        }
         pp_result *out = a.out + q;
         if (lane == 0) {
             out->best_index = none ? -1 : c;
@@ -270,8 +291,9 @@ __device__ __forceinline__ void ramp_down(V (&fin)[4 * S - 3 + 1], const V (&dur
 // pipeline fills completely (M >= J-1) the sweeps split into a ramp-up (blocks 1..t), a
 // steady phase (all blocks) and a ramp-down (blocks t-M+1..J) whose block ranges are known at
 // compile time; otherwise every block update is selected by a per-lane compare.
-template <int S, typename V>
-__device__ __forceinline__ V sweep_regs(const long long (&dur64)[4 * S - 3 + 1], int M) {
+// `result(fin)` turns the final finish times into the value returned.
+template <int S, typename V, typename Result>
+__device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S - 3 + 1], int M, Result result) {
     constexpr int R = 2 * S - 1, J = 2 * R - 1;
     V dur[J + 1], fin[J + 1];
 #pragma unroll
@@ -282,7 +304,7 @@ __device__ __forceinline__ V sweep_regs(const long long (&dur64)[4 * S - 3 + 1],
             ramp_up<S, V, 1>(fin, dur);
             for (int t = J; t <= M; ++t) sweep_blocks<S, V, 1, J>(fin, dur);
             ramp_down<S, V, 1>(fin, dur);
-            return fin[J];
+            return result(fin);
         }
     }
     const int sweeps = M + 2 * R - 2;
@@ -308,7 +330,7 @@ __device__ __forceinline__ V sweep_regs(const long long (&dur64)[4 * S - 3 + 1],
             fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
         }
     }
-    return fin[J];
+    return result(fin);
 }
 
 template <int S>
@@ -326,11 +348,130 @@ __global__ __launch_bounds__(64) void k_makespan_regs(mk_args a) {
     const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
     // 32-bit arithmetic if no finish time of any lane can reach 2^31
     const bool narrow = fq || !live || worst <= (long long)0x7fffffff / ((long long)M + 4 * S - 4);
+    // T is the finish of the last backward block on stage 0
     long long T;
-    if (__all(narrow)) T = (long long)sweep_regs<S, int>(dur, M);
-    else T = sweep_regs<S, long long>(dur, M);
+    if (__all(narrow)) T = sweep_regs<S, int>(dur, M, [](const int (&fin)[J + 1]) { return (long long)fin[J]; });
+    else T = sweep_regs<S, long long>(dur, M, [](const long long (&fin)[J + 1]) { return fin[J]; });
     emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x);
     conclude(a, gridDim.x, (long long)gridDim.x * gridDim.y);
+}
+
+// ---------------------------------------------------------------- replicated stages, S <= 16
+
+__device__ __forceinline__ long long ceil_div64(long long x, long long y) { return x / y + (x % y != 0); }
+
+// Plans with replicated stages (Sec. III-B): stage s runs on reps[s] GPUs of consecutive ranks,
+// a replica takes ceil(p / k) per microbatch, a transfer between stages of k' and k replicas
+// ceil(d / (k' k min b)) with the minimum over the links between the two GPU sets, and a
+// replicated stage ends with a ring AllReduce of ceil(2 (k-1) sum alpha / (k min b)) (Eq. 1)
+// that starts when its last backward pass has finished.  T is the later of the last backward
+// block on stage 0 and the end of the last AllReduce (Eq. 2).  One lane per candidate; the
+// plan with S stages of candidate c is read from the triangular arrays.
+template <int S>
+__global__ __launch_bounds__(64) void k_rep_makespan(mk_args a) {
+    constexpr int R = 2 * S - 1, J = 4 * S - 3;
+    const int lane = threadIdx.x, L = a.L, D = a.D;
+    const long long c = (long long)blockIdx.x * 64 + lane;
+    const bool live = c < a.N;
+    const int M = a.Ms[0];
+    long long dur[J + 1], A[S];
+    long long worst = 0, amax = 0;
+    int fault = 0;
+    const bool none = live && a.W[c * a.t_stride + a.t_off] == PP_INF64;  // no plan with S stages
+    const bool work = live && !none;
+    const int *bd = a.bounds + c * a.bnd_stride + a.bnd_off;
+    const int *rp = a.reps + c * a.bnd_stride + a.bnd_off;
+    const int *o = a.orderings + c * a.ord_stride;
+    if (work) {
+        int prev = 0, used = 0;
+        for (int s = 0; s < S; ++s) {
+            int e = bd[s], k = rp[s];
+            if (e <= prev || e > L || k < 1 || k > D) fault |= PP_FAULT_BOUNDS;
+            prev = e;
+            used += k;
+        }
+        if (prev != L || used != D) fault |= PP_FAULT_BOUNDS;
+        for (int n = 0; n < D; ++n) {
+            int d = o[n];
+            bool bad = d < 0 || d >= D;
+            for (int q = 0; q < n; ++q) bad |= (o[q] == d);
+            if (bad) fault |= PP_FAULT_ORDERING;
+        }
+    }
+    const bool ok = work && !fault;
+    int e0 = 0, n = 0, kprev = 0;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        long long F = 0, Bk = 0, cf = 0, cb = 0, As = 0;
+        if (ok) {
+            const int e = bd[s], k = rp[s];
+            F = ceil_div64(a.PF[e] - a.PF[e0], k);
+            Bk = ceil_div64(a.PB[e] - a.PB[e0], k);
+            if (k > 1) {
+                long long m = PP_INF64;
+                for (int u = n; u < n + k; ++u)
+                    for (int v = n; v < n + k; ++v)
+                        if (u != v) {
+                            long long x = a.bw[(size_t)o[u] * D + o[v]];
+                            m = x < m ? x : m;
+                        }
+                As = ceil_div64(2 * (long long)(k - 1) * (a.PA[e] - a.PA[e0]), (long long)k * m);
+            }
+            if (s) {
+                long long mf = PP_INF64, mb = PP_INF64;
+                for (int u = n - kprev; u < n; ++u)
+                    for (int v = n; v < n + k; ++v) {
+                        long long x = a.bw[(size_t)o[u] * D + o[v]], y = a.bw[(size_t)o[v] * D + o[u]];
+                        mf = x < mf ? x : mf;
+                        mb = y < mb ? y : mb;
+                    }
+                cf = ceil_div64(a.actf[e0 - 1], (long long)kprev * k * mf);
+                cb = ceil_div64(a.actb[e0 - 1], (long long)kprev * k * mb);
+            }
+            e0 = e;
+            n += k;
+            kprev = k;
+        }
+        A[s] = As;
+        amax = As > amax ? As : amax;
+        long long w = F + Bk > cf + cb ? F + Bk : cf + cb;
+        worst = w > worst ? w : worst;
+        const int r = 2 * s + 1;
+        if (s == S - 1) {
+            dur[R] = F + Bk;
+        } else {
+            dur[r] = F;
+            dur[2 * R - r] = Bk;
+        }
+        if (s) {
+            dur[r - 1] = cf;
+            dur[2 * R - (r - 1)] = cb;
+        }
+    }
+    dur[0] = 0;
+    if (ok) {
+        fault |= overflow_fault(worst, M, S);
+        if (amax >= PP_CAP62 / 2) fault |= PP_FAULT_OVERFLOW;
+    }
+    // the later of the last backward block on stage 0 and the end of every AllReduce
+    auto finish = [&](auto &fin) {
+        long long T = (long long)fin[J];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const int jb = s == S - 1 ? R : 2 * R - (2 * s + 1);
+            const long long t = (long long)fin[jb] + A[s];
+            T = (A[s] > 0 && t > T) ? t : T;
+        }
+        return T;
+    };
+    const bool narrow = !ok || fault || worst <= (long long)0x7fffffff / ((long long)M + 4 * S - 4);
+    long long T;
+    if (__all(narrow)) T = sweep_regs<S, int>(dur, M, finish);
+    else T = sweep_regs<S, long long>(dur, M, finish);
+    if (live) {
+        if (fault) pp_raise(a.status, fault);
+        a.T_out[c * a.t_stride + a.t_off] = (none || fault) ? PP_INF64 : T;
+    }
 }
 
 // ---------------------------------------------------------------- LDS columns, any S
@@ -387,6 +528,7 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
 
 static void plain_layout(mk_args &a, int S) {
     a.ord_stride = S; a.bnd_stride = S; a.bnd_off = 0; a.t_stride = 1; a.t_off = 0; a.search = 0;
+    a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
 }
 
 // Lanes per workgroup of the LDS kernel: as many as keep 2J rows of int64 within 64 KiB.
@@ -502,6 +644,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
     a.T_out = (long long *)T_st; a.status = status;
     a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL;
     a.ord_stride = S; a.bnd_stride = (long long)S * (S + 1) / 2; a.t_stride = S; a.search = 0;
+    a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
     // one launch per stage count: the schedules of xi stages on the first xi devices
     for (int xi = 1; xi <= S; ++xi) {
         a.S = xi;
@@ -517,5 +660,54 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
     long long waves = (m.N + 63) / 64;
     if (waves > 1024) waves = 1024;
     hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves, nM), dim3(64), 0, st, m);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+// ---------------------------------------------------------------- replicated stages: launch
+
+template <int S>
+static int launch_rep(const mk_args &a, hipStream_t st) {
+    unsigned grid = (unsigned)((a.N + 63) / 64);
+    hipLaunchKernelGGL(k_rep_makespan<S>, dim3(grid), dim3(64), 0, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, const int64_t *PB,
+                           const int64_t *PA, const int64_t *actf, const int64_t *actb,
+                           const int64_t *bw, const int32_t *orderings, const int32_t *bounds,
+                           const int32_t *reps, const int64_t *W, int64_t *T_out, int32_t *status,
+                           void *part, unsigned *ticket, pp_rep_result *out, hipStream_t st) {
+    if (D > 16) return PP_ERR_INVALID_ARG;
+    mk_args a;
+    a.L = L; a.D = D; a.N = N; a.nM = 1;
+    for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = M;
+    a.PF = (const long long *)PF; a.PB = (const long long *)PB;
+    a.XF = a.XB = NULL;
+    a.PA = (const long long *)PA; a.actf = (const long long *)actf; a.actb = (const long long *)actb;
+    a.bw = (const long long *)bw; a.W = (const long long *)W;
+    a.orderings = orderings; a.bounds = bounds; a.reps = reps;
+    a.T_out = (long long *)T_out; a.status = status;
+    a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL; a.rout = NULL;
+    a.ord_stride = D; a.bnd_stride = (long long)D * (D + 1) / 2; a.t_stride = D; a.search = 0;
+    for (int xi = 1; xi <= D; ++xi) {
+        a.S = xi;
+        a.bnd_off = xi * (xi - 1) / 2;
+        a.t_off = xi - 1;
+        int rc = PP_ERR_INVALID_ARG;
+        switch (xi) {
+#define CASE(n) case n: rc = launch_rep<n>(a, st); break;
+            CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+            CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
+#undef CASE
+        }
+        if (rc) return rc;
+    }
+    // smallest T over all (candidate, stage count) pairs, lowest c*D + xi-1 on ties
+    mk_args m = a;
+    m.S = D; m.N = N * D; m.search = D;
+    m.part = (tc_pair *)part; m.ticket = ticket; m.C = (const long long *)W; m.rout = out;
+    long long waves = (m.N + 63) / 64;
+    if (waves > 1024) waves = 1024;
+    hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves, 1), dim3(64), 0, st, m);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }

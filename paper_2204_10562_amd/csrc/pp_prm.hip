@@ -1,0 +1,439 @@
+// Partition, replication and mapping (PRM, Alg. 4; recursion for W(l, xi, r, i) in Sec. IV-B)
+// for a batch of device orderings: the dynamic program over (layers, stages, replicas of the
+// last stage, GPUs used) with the AllReduce term of Eq. 1, for every stage count at once.
+//
+//   W(l, xi, r, i) = min over l' in [xi-1, l-1], r' in [1, i-r] of
+//                    max{ W(l', xi-1, r', i-r),  M (c^f + c^b),  M (F + B) + A }
+//   W(l, 1, i, i)  = M (F + B) + A of layers [0, l) on all i GPUs
+// where, for the last stage = layers [l', l) on the r GPUs of ranks [i-r, i):
+//   F = ceil(sum p^f / r), B = ceil(sum p^b / r)            (per-replica times, Sec. III-B)
+//   A = ceil(2 (r-1) sum alpha / (r min b)), 0 for r = 1    (Eq. 1; min over the replica set)
+//   c^f = ceil(d^f / (r' r min b_{v',v})), c^b = ceil(d^b / (r' r min b_{v,v'}))
+//         (v' in the r' GPUs of ranks [i-r-r', i-r), v in the last stage's).
+// The listing scans l' ascending, then r' ascending, and replaces its best only on strict
+// improvement: the minimiser kept is the first in (l', r') order.
+//
+// One workgroup per candidate (persistent over candidates), one thread per cell l.  State
+// (xi, r, i) depends only on states with fewer GPUs, so states are visited by ascending i.
+// All states with the same (r, i) share the last stage's terms, which are made division-free:
+// with Q[l] = floor(P[l] / r), R[l] = P[l] mod r,  ceil((P[l] - P[l']) / r) =
+// Q[l] - Q[l'] + (R[l] > R[l']); so the stage term is U[l] - U[l'] + (remainder compares) with
+// U = M (QF + QB) + QA.  The sub-problem and channel terms do not depend on l: they are
+// merged once per state into G[r'][l'] in LDS.  States that use all D GPUs are needed at
+// l = L only and are reduced by the whole workgroup instead.
+#include "pp_common.h"
+
+#define PRM_THREADS 128
+
+struct prm_args {
+    int L, D, M;
+    long long N;
+    const long long *fwd, *bwd, *actf, *actb, *alpha, *bw;
+    const int *ord;  // [N][D], or NULL = all D! orderings in lexicographic order
+    char *scratch;   // slots * slot_bytes
+    size_t slot_bytes;
+    long long *W_out;  // [N][D]: W of the best plan with xi stages at xi-1 (PP_INF64: none)
+    int *bounds_out;   // [N][D(D+1)/2]
+    int *reps_out;     // [N][D(D+1)/2]
+    long long *pre_out;  // [3][L+1]: prefix sums of fwd, bwd, alpha for the kernels that follow
+    unsigned *ticket;    // 65 arrival counters of the arg-min that follows, cleared here
+    int32_t *status;
+};
+
+__host__ __device__ static inline int prm_states(int D) { return D * (D + 1) * (D + 2) / 6; }
+
+// Index of state (i GPUs, xi stages, r replicas of the last stage), 1 <= xi <= i,
+// 1 <= r <= i - xi + 1.
+__host__ __device__ static inline int prm_sid(int i, int xi, int r) {
+    return (i - 1) * i * (i + 1) / 6 + (xi - 1) * (i + 1) - xi * (xi - 1) / 2 + (r - 1);
+}
+
+// Bytes of per-workgroup scratch: W and the minimising (l', r') of every state and cell, and
+// the minima of the bandwidth matrix over rank sets.
+static inline size_t prm_slot_bytes(int L, int D) {
+    size_t cells = (size_t)prm_states(D) * (L + 1);
+    size_t minima = (size_t)(D + 1) * (D + 1) * (D + 1) * 2 + (size_t)(D + 1) * (D + 1);
+    return pp_align256(cells * 8) + pp_align256(cells * 4) + pp_align256(minima * 8);
+}
+
+static inline size_t prm_lds_bytes(int L, int D) {
+    // PF, PB, PA, U, RA (int64), RFB (int32), G (int64, D-1 rows)
+    return (size_t)(L + 1) * (5 * 8 + 4) + (size_t)(D > 1 ? D - 1 : 1) * (L + 1) * 8 + 64;
+}
+
+struct prm_key {
+    long long v;
+    int lp, rp;
+};
+
+__device__ __forceinline__ bool prm_less(const prm_key &a, const prm_key &b) {
+    if (a.v != b.v) return a.v < b.v;
+    if (a.lp != b.lp) return a.lp < b.lp;
+    return a.rp < b.rp;
+}
+
+__device__ __forceinline__ long long cdiv64(long long a, long long b) { return a / b + (a % b != 0); }
+
+__global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int s_o[PP_MAX_STAGES];
+    __shared__ int s_fault;
+    __shared__ prm_key s_red[PRM_THREADS / 64];
+    const int L = a.L, D = a.D, tid = threadIdx.x, B = blockDim.x;
+    const long long M = a.M;
+    const int L1 = L + 1, D1 = D + 1;
+    long long *PF = (long long *)smem, *PB = PF + L1, *PA = PB + L1, *U = PA + L1, *RA = U + L1;
+    long long *G = RA + L1;                            // [D-1][L1]
+    int *RFB = (int *)(G + (size_t)(D > 1 ? D - 1 : 1) * L1);  // RF | RB << 8 (both < r <= 64)
+    const int NS = prm_states(D), tri = D * (D + 1) / 2;
+    char *slot = a.scratch + (size_t)blockIdx.x * a.slot_bytes;
+    long long *Wt = (long long *)slot;                                 // [NS][L1]
+    unsigned *At = (unsigned *)(slot + pp_align256((size_t)NS * L1 * 8));  // l' | r' << 16
+    long long *bfwd = (long long *)((char *)At + pp_align256((size_t)NS * L1 * 4));  // [p][rp][r]
+    long long *bbwd = bfwd + (size_t)D1 * D1 * D1;
+    long long *bin = bbwd + (size_t)D1 * D1 * D1;                       // [n][r]
+
+    // prefix sums (every workgroup makes its own copy: L is small next to the DP) and input checks
+    if (tid == 0) s_fault = 0;
+    __syncthreads();
+    {
+        int fault = 0;
+        for (int l = tid; l < L; l += B) {
+            long long x = a.fwd[l], y = a.bwd[l], z = a.alpha[l];
+            if (x < 0 || y < 0 || z < 0) fault |= PP_FAULT_NEGATIVE;
+            if (l + 1 < L && (a.actf[l] < 0 || a.actb[l] < 0)) fault |= PP_FAULT_NEGATIVE;
+            if (x >= PP_CAP62 || y >= PP_CAP62 || z >= PP_CAP62) fault |= PP_FAULT_OVERFLOW;
+            PF[l + 1] = x; PB[l + 1] = y; PA[l + 1] = z;
+        }
+        for (int t = tid; t < D * D; t += B)
+            if (t / D != t % D && a.bw[t] <= 0) fault |= PP_FAULT_BANDWIDTH;
+        if (fault) atomicOr(&s_fault, fault);
+    }
+    __syncthreads();
+    if (tid == 0 && !s_fault) {
+        long long f = 0, b = 0, al = 0;
+        PF[0] = PB[0] = PA[0] = 0;
+        for (int l = 1; l <= L; ++l) {
+            f += PF[l]; b += PB[l]; al += PA[l];
+            // M * (time) and 2 (r-1) * (parameter bytes) must stay far from 2^63
+            if (f + b >= PP_CAP62 / (M + 4 * D) || al >= PP_CAP62 / (2 * D)) { s_fault = PP_FAULT_OVERFLOW; break; }
+            PF[l] = f; PB[l] = b; PA[l] = al;
+        }
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        for (int t = tid; t < 65; t += B) a.ticket[t] = 0;
+        if (!s_fault)
+            for (int l = tid; l <= L; l += B) {
+                a.pre_out[l] = PF[l];
+                a.pre_out[L1 + l] = PB[l];
+                a.pre_out[2 * L1 + l] = PA[l];
+            }
+    }
+    if (s_fault) {
+        // nothing can be planned: every (candidate, stage count) is marked as having no plan
+        if (tid == 0 && blockIdx.x == 0) pp_raise(a.status, s_fault);
+        for (long long t = (long long)blockIdx.x * B + tid; t < a.N * D; t += (long long)gridDim.x * B)
+            a.W_out[t] = PP_INF64;
+        return;
+    }
+
+    for (long long c = blockIdx.x; c < a.N; c += gridDim.x) {
+        __syncthreads();
+        // ---- ordering
+        if (tid == 0) {
+            int bad = 0;
+            if (a.ord) {
+                for (int n = 0; n < D; ++n) {
+                    int d = a.ord[c * D + n];
+                    if (d < 0 || d >= D) bad = 1;
+                    for (int q = 0; q < n; ++q) bad |= (s_o[q] == d);
+                    s_o[n] = d;
+                }
+            } else {
+                unsigned long long rem = (unsigned long long)c;
+                unsigned used = 0;
+                for (int n = 0; n < D; ++n) s_o[n] = pp_unrank_next(D, n, rem, used);
+            }
+            s_fault = bad;
+        }
+        __syncthreads();
+        if (s_fault) {
+            if (tid == 0) pp_raise(a.status, PP_FAULT_ORDERING);
+            for (int n = tid; n < D; n += B) a.W_out[c * D + n] = PP_INF64;
+            for (int n = tid; n < tri; n += B) { a.bounds_out[c * tri + n] = 0; a.reps_out[c * tri + n] = 0; }
+            continue;
+        }
+        // ---- minima of the bandwidth matrix over rank sets
+        // bfwd[p][rp][r]: links from ranks [p-rp, p) to ranks [p, p+r); bbwd: the other direction
+        for (int t = tid; t < D1 * D1 * D1; t += B) {
+            const int p = t / (D1 * D1), rp = (t / D1) % D1, r = t % D1;
+            if (p < 1 || rp < 1 || r < 1 || rp > p || p + r > D) continue;
+            long long mf = PP_INF64, mb = PP_INF64;
+            for (int u = p - rp; u < p; ++u)
+                for (int v = p; v < p + r; ++v) {
+                    long long x = a.bw[(size_t)s_o[u] * D + s_o[v]], y = a.bw[(size_t)s_o[v] * D + s_o[u]];
+                    mf = x < mf ? x : mf;
+                    mb = y < mb ? y : mb;
+                }
+            bfwd[t] = mf;
+            bbwd[t] = mb;
+        }
+        // bin[n][r]: ordered pairs inside ranks [n-r, n)
+        for (int t = tid; t < D1 * D1; t += B) {
+            const int n = t / D1, r = t % D1;
+            if (n < 1 || r < 2 || r > n) continue;
+            long long m = PP_INF64;
+            for (int u = n - r; u < n; ++u)
+                for (int v = n - r; v < n; ++v)
+                    if (u != v) {
+                        long long x = a.bw[(size_t)s_o[u] * D + s_o[v]];
+                        m = x < m ? x : m;
+                    }
+            bin[t] = m;
+        }
+        __syncthreads();
+
+        // ---- states by ascending number of GPUs; all D GPUs are handled below
+        for (int i = 1; i < D; ++i)
+            for (int r = 1; r <= i; ++r) {
+                // last stage on r replicas, ranks [i-r, i): division-free form of its terms
+                const long long den = r > 1 ? (long long)r * bin[i * D1 + r] : 1;
+                for (int l = tid; l <= L; l += B) {
+                    long long qf = PF[l] / r, qb = PB[l] / r;
+                    long long num = 2 * (long long)(r - 1) * PA[l];
+                    long long qa = num / den;
+                    U[l] = M * (qf + qb) + qa;
+                    RA[l] = num - qa * den;
+                    RFB[l] = (int)(PF[l] - qf * r) | ((int)(PB[l] - qb * r) << 8);
+                }
+                __syncthreads();
+                for (int xi = 1; xi <= i - r + 1; ++xi) {
+                    long long *Ws = Wt + (size_t)prm_sid(i, xi, r) * L1;
+                    unsigned *As = At + (size_t)prm_sid(i, xi, r) * L1;
+                    if (xi == 1) {
+                        // a single stage must take all i GPUs
+                        for (int l = tid; l <= L; l += B) {
+                            long long w = PP_INF64;
+                            if (r == i && l >= 1)
+                                w = U[l] + M * (((RFB[l] & 255) > 0) + ((RFB[l] >> 8) > 0)) + (RA[l] > 0);
+                            Ws[l] = w;
+                            As[l] = 0;
+                        }
+                        continue;  // nothing below reads LDS that the next state rewrites
+                    }
+                    const int n0 = i - r;         // GPUs of the sub-problem
+                    const int nrp = n0 - (xi - 2);  // r' = 1..nrp leave >= 1 GPU per earlier stage
+                    // G[r'][l'] = max(W(l', xi-1, r', n0), M (c^f + c^b))
+                    for (int t = tid; t < nrp * L1; t += B) {
+                        const int rp = 1 + t / L1, lp = t % L1;
+                        long long g = PP_INF64;
+                        if (lp >= xi - 1 && lp <= L - 1) {
+                            long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
+                            if (w != PP_INF64) {
+                                const size_t at = ((size_t)n0 * D1 + rp) * D1 + r;
+                                long long cf = cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]);
+                                long long cb = cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at]);
+                                long long x = M * (cf + cb);
+                                g = w > x ? w : x;
+                            }
+                        }
+                        G[(size_t)(rp - 1) * L1 + lp] = g;
+                    }
+                    __syncthreads();
+                    for (int l = tid; l <= L; l += B) {
+                        prm_key best = {PP_INF64, 0, 0};
+                        if (l >= xi) {
+                            const long long Ul = U[l], RAl = RA[l];
+                            const int rf = RFB[l] & 255, rb = RFB[l] >> 8;
+                            for (int lp = xi - 1; lp < l; ++lp) {
+                                const int q = RFB[lp];
+                                const long long last = Ul - U[lp] + M * ((rf > (q & 255)) + (rb > (q >> 8))) +
+                                                       (RAl > RA[lp]);
+                                for (int rp = 1; rp <= nrp; ++rp) {
+                                    const long long g = G[(size_t)(rp - 1) * L1 + lp];
+                                    const long long t = g > last ? g : last;
+                                    if (t < best.v) { best.v = t; best.lp = lp; best.rp = rp; }
+                                }
+                            }
+                        }
+                        Ws[l] = best.v;
+                        As[l] = (unsigned)best.lp | ((unsigned)best.rp << 16);
+                    }
+                    __syncthreads();  // G is rewritten by the next state
+                }
+                __syncthreads();  // U, RA, RFB are rewritten by the next (r, i)
+            }
+
+        // ---- all D GPUs: only W(L, xi, r, D) is needed; the workgroup shares the scan of (l', r')
+        __threadfence_block();
+        __syncthreads();
+        for (int xi = 1; xi <= D; ++xi)
+            for (int r = 1; r <= D - xi + 1; ++r) {
+                const int sid = prm_sid(D, xi, r);
+                prm_key best = {PP_INF64, 0, 0};
+                const long long den = r > 1 ? (long long)r * bin[D * D1 + r] : 1;
+                if (xi == 1) {
+                    if (r == D && tid == 0)
+                        best.v = M * (cdiv64(PF[L], r) + cdiv64(PB[L], r)) + cdiv64(2 * (long long)(r - 1) * PA[L], den);
+                } else {
+                    const int n0 = D - r, nrp = n0 - (xi - 2);
+                    for (int t = tid; t < nrp * L; t += B) {
+                        // l' ascending first, then r': any order works, the key decides
+                        const int lp = t / nrp, rp = 1 + t % nrp;
+                        if (lp < xi - 1) continue;
+                        long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
+                        if (w == PP_INF64) continue;
+                        const size_t at = ((size_t)n0 * D1 + rp) * D1 + r;
+                        long long cf = cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]);
+                        long long cb = cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at]);
+                        long long last = M * (cdiv64(PF[L] - PF[lp], r) + cdiv64(PB[L] - PB[lp], r)) +
+                                         cdiv64(2 * (long long)(r - 1) * (PA[L] - PA[lp]), den);
+                        long long x = M * (cf + cb);
+                        prm_key k = {w > x ? w : x, lp, rp};
+                        k.v = k.v > last ? k.v : last;
+                        if (prm_less(k, best)) best = k;
+                    }
+                }
+                // minimum over the workgroup: lowest value, then lowest l', then lowest r'
+                for (int off = 32; off; off >>= 1) {
+                    prm_key o;
+                    o.v = __shfl_xor(best.v, off);
+                    o.lp = __shfl_xor(best.lp, off);
+                    o.rp = __shfl_xor(best.rp, off);
+                    if (prm_less(o, best)) best = o;
+                }
+                if ((tid & 63) == 0) s_red[tid >> 6] = best;
+                __syncthreads();
+                if (tid == 0) {
+                    for (int w = 1; w < B / 64; ++w)
+                        if (prm_less(s_red[w], best)) best = s_red[w];
+                    Wt[(size_t)sid * L1 + L] = best.v;
+                    At[(size_t)sid * L1 + L] = (unsigned)best.lp | ((unsigned)best.rp << 16);
+                }
+                __syncthreads();
+            }
+
+        // ---- per stage count: the first r with the smallest W (Alg. 3), and its plan
+        __threadfence_block();
+        __syncthreads();
+        for (int xi = 1 + tid; xi <= D; xi += B) {
+            long long wbest = PP_INF64;
+            int rbest = 0;
+            for (int r = 1; r <= D - xi + 1; ++r) {
+                long long w = Wt[(size_t)prm_sid(D, xi, r) * L1 + L];
+                if (w < wbest) { wbest = w; rbest = r; }
+            }
+            a.W_out[c * D + xi - 1] = wbest;
+            int *bo = a.bounds_out + c * tri + xi * (xi - 1) / 2;
+            int *ro = a.reps_out + c * tri + xi * (xi - 1) / 2;
+            int l = L, n = D, r = rbest;
+            for (int s = xi - 1; s >= 0; --s) {
+                if (wbest == PP_INF64) { bo[s] = 0; ro[s] = 0; continue; }
+                bo[s] = l;
+                ro[s] = r;
+                unsigned arg = At[(size_t)prm_sid(n, s + 1, r) * L1 + l];
+                n -= r;
+                l = (int)(arg & 0xffffu);
+                r = (int)(arg >> 16);
+            }
+        }
+    }
+}
+
+// Row c = the ordering of lexicographic rank c among all D! (D <= 20).
+__global__ __launch_bounds__(256) void k_all_orderings(int D, long long N, int *ord) {
+    const long long c = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (c >= N) return;
+    unsigned long long rem = (unsigned long long)c;
+    unsigned used = 0;
+    for (int n = 0; n < D; ++n) ord[c * D + n] = pp_unrank_next(D, n, rem, used);
+}
+
+// Workspace of pp_plan_replicated.
+struct rep_layout {
+    size_t slots_at, ord, pre, W, T, bounds, reps, part, ticket, total;
+    int slots;
+};
+
+static rep_layout rep_layout_of(int L, int D, int64_t N) {
+    rep_layout w;
+    size_t off = 0;
+    const size_t tri = (size_t)D * (D + 1) / 2;
+    w.slots = (int)(N < 2560 ? N : 2560);  // 10 workgroups of 128 threads per compute unit
+    w.slots_at = off; off += pp_align256((size_t)w.slots * prm_slot_bytes(L, D));
+    w.ord = off;      off += pp_align256((size_t)N * D * 4);
+    w.pre = off;      off += pp_align256((size_t)3 * (L + 1) * 8);
+    w.W = off;        off += pp_align256((size_t)N * D * 8);
+    w.T = off;        off += pp_align256((size_t)N * D * 8);
+    w.bounds = off;   off += pp_align256((size_t)N * tri * 4);
+    w.reps = off;     off += pp_align256((size_t)N * tri * 4);
+    w.part = off;     off += pp_align256((size_t)1024 * 16);
+    w.ticket = off;   off += pp_align256(65 * 4);
+    w.total = off;
+    return w;
+}
+
+static bool rep_sizes_ok(int L, int D, int64_t N, const int32_t *orderings) {
+    if (L < 1 || L > PP_MAX_LAYERS || D < 1 || D > 16 || N < 1) return false;
+    if (prm_lds_bytes(L, D) > 64 * 1024) return false;
+    if (!orderings) {
+        int64_t f = 1;
+        for (int i = 2; i <= D; ++i) f *= i;  // D <= 16: no overflow
+        if (f != N) return false;
+    }
+    return true;
+}
+
+extern "C" size_t pp_workspace_bytes_replicated(int L, int D, int64_t N) {
+    if (L < 1 || L > PP_MAX_LAYERS || D < 1 || D > 16 || N < 1) return 0;
+    if (prm_lds_bytes(L, D) > 64 * 1024) return 0;
+    return rep_layout_of(L, D, N).total;
+}
+
+extern "C" int pp_plan_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
+                                  const int64_t *bwd_us, const int64_t *act_fwd_bytes,
+                                  const int64_t *act_bwd_bytes, const int64_t *alpha_bytes,
+                                  const int64_t *bw, const int32_t *orderings, pp_rep_result *out,
+                                  int64_t *T_all, int64_t *W_all, int32_t *bounds_all,
+                                  int32_t *reps_all, void *workspace, size_t workspace_bytes,
+                                  int32_t *status, void *stream) {
+    if (!rep_sizes_ok(L, D, N, orderings) || M < 1) return PP_ERR_INVALID_ARG;
+    if (!fwd_us || !bwd_us || !act_fwd_bytes || !alpha_bytes || !bw || !out) return PP_ERR_INVALID_ARG;
+    const rep_layout lay = rep_layout_of(L, D, N);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < lay.total) return PP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    const int32_t *ord = orderings;
+    if (!ord) {
+        int *list = (int *)(base + lay.ord);
+        hipLaunchKernelGGL(k_all_orderings, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, D,
+                           (long long)N, list);
+        if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+        ord = list;
+    }
+    const int64_t *actb = act_bwd_bytes ? act_bwd_bytes : act_fwd_bytes;
+    int64_t *W = W_all ? W_all : (int64_t *)(base + lay.W);
+    int64_t *T = T_all ? T_all : (int64_t *)(base + lay.T);
+    int32_t *bounds = bounds_all ? bounds_all : (int32_t *)(base + lay.bounds);
+    int32_t *reps = reps_all ? reps_all : (int32_t *)(base + lay.reps);
+    int64_t *pre = (int64_t *)(base + lay.pre);
+
+    prm_args a;
+    a.L = L; a.D = D; a.M = M; a.N = N;
+    a.fwd = (const long long *)fwd_us; a.bwd = (const long long *)bwd_us;
+    a.actf = (const long long *)act_fwd_bytes; a.actb = (const long long *)actb;
+    a.alpha = (const long long *)alpha_bytes; a.bw = (const long long *)bw;
+    a.ord = ord;
+    a.scratch = base + lay.slots_at;
+    a.slot_bytes = prm_slot_bytes(L, D);
+    a.W_out = (long long *)W; a.bounds_out = bounds; a.reps_out = reps;
+    a.pre_out = (long long *)pre;
+    a.ticket = (unsigned *)(base + lay.ticket);
+    a.status = status;
+    hipLaunchKernelGGL(k_prm, dim3(lay.slots), dim3(PRM_THREADS), prm_lds_bytes(L, D), st, a);
+    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+    return pp_launch_rep_makespan(L, D, N, M, pre, pre + (L + 1), pre + 2 * (L + 1), act_fwd_bytes,
+                                  actb, bw, ord, bounds, reps, W, T, status, base + lay.part,
+                                  (unsigned *)(base + lay.ticket), out, st);
+}

@@ -178,3 +178,13 @@ def pair_evals_per_candidate(L: int, S: int) -> int:
     """Number of (cell, split) pairs the partition DP inspects for one candidate:
     sum over xi = 2..S of (L - xi + 1)(L - xi + 2) / 2."""
     return sum((L - xi + 1) * (L - xi + 2) // 2 for xi in range(2, S + 1))
+
+
+def parameter_sizes(w: Workload, seed_offset: int = 0) -> np.ndarray:
+    """Per-layer parameter (= gradient) sizes alpha_l in bytes for the AllReduce term of the
+    planner with replicated stages: log-uniform in [1 MiB, 64 MiB], from a generator of its
+    own (seeded by the workload's name and length), so that the draws of the workload itself
+    do not change."""
+    tag = sum(ord(ch) for ch in w.name) * 1000 + w.L
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 7919 + tag + seed_offset))
+    return _rint(np.exp(rng.uniform(math.log(1 * MIB), math.log(64 * MIB), size=w.L)))

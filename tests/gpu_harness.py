@@ -121,3 +121,26 @@ class GpuProblem:
         res = [pp.read_result(out, None, q) for q in range(nM)]
         return (self.take_status(), res, None if T is None else T.cpu().numpy().reshape(nM, N, S),
                 None if C is None else C.cpu().numpy().reshape(N, S))
+
+    def plan_replicated(self, M, alpha, orderings="default", N=None, want_all=True):
+        w = self.w
+        N = N or w.N
+        L, D = w.L, w.D
+        tri = D * (D + 1) // 2
+        o = self.orderings if isinstance(orderings, str) else orderings
+        need = pp.pp_workspace_bytes_replicated(L, D, N)
+        assert need > 0
+        ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        al = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.int64)).to(self.dev)
+        out = torch.zeros(pp.REP_RESULT_BYTES, dtype=torch.uint8, device=self.dev)
+        T = torch.empty(N * D, dtype=torch.int64, device=self.dev) if want_all else None
+        W = torch.empty(N * D, dtype=torch.int64, device=self.dev) if want_all else None
+        b = torch.empty(N * tri, dtype=torch.int32, device=self.dev) if want_all else None
+        r = torch.empty(N * tri, dtype=torch.int32, device=self.dev) if want_all else None
+        pp.pp_plan_replicated(L, D, N, M, self.fwd, self.bwd, self.actf, self.actb, al, self.bw, o, out,
+                              T, W, b, r, ws, self.status)
+        res = pp.read_rep_result(out, D)
+        if not want_all:
+            return self.take_status(), res
+        return (self.take_status(), res, T.cpu().numpy().reshape(N, D), W.cpu().numpy().reshape(N, D),
+                b.cpu().numpy().reshape(N, tri), r.cpu().numpy().reshape(N, tri))
