@@ -122,6 +122,17 @@ def main():
     t_stages = timed(lambda: pp.pp_best_plan_stages(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out_st, None, None, ws_st, g.status), reps)
     stage_winner = pp.read_result(out_st, None, len(Ms) - 1)
     del ws_st, C_st, b_st
+    # the planner with replicated stages (Alg. 3 + Alg. 4) over the same orderings: not in the step
+    t_rep = rep_winner = None
+    if pp.pp_workspace_bytes_replicated(L, D, N) and S == D and N <= 100000:
+        import numpy as np
+        alpha = torch.from_numpy(workloads.parameter_sizes(w)).to(dev)
+        ws_rep = torch.empty(pp.pp_workspace_bytes_replicated(L, D, N), dtype=torch.uint8, device=dev)
+        out_rep = torch.zeros(pp.REP_RESULT_BYTES, dtype=torch.uint8, device=dev)
+        t_rep = timed(lambda: pp.pp_plan_replicated(L, D, N, Ms[-1], g.fwd, g.bwd, g.actf, g.actb, alpha, g.bw,
+                                                    g.orderings, out_rep, None, None, None, None, ws_rep, g.status), 5)
+        rep_winner = pp.read_rep_result(out_rep, D)
+        del ws_rep
     # the recursive device ordering (Alg. 2) as one more candidate: where does it rank?
     rdo = pp.pp_rdo_order(D, w.bw.reshape(-1).tolist())
     T_all = torch.empty(N * len(Ms), dtype=torch.int64, device=dev)
@@ -156,6 +167,10 @@ def main():
     log("  stage-count search (not in the step): pp_partition_dp_stages %.1f us, pp_best_plan_stages %.1f us = %.3e (candidate, stage count, M) plans/s"
         % (t_dp_st * 1e6, t_stages * 1e6, N * S * len(Ms) / t_stages))
     log("     winner over stage counts 1..%d for M=%d:" % (S, Ms[-1]), stage_winner)
+    if t_rep is not None:
+        log("  planner with replicated stages (not in the step), M=%d: pp_plan_replicated %.1f ms = %.3e orderings/s"
+            % (Ms[-1], t_rep * 1e3, N / t_rep))
+        log("     winner:", rep_winner)
     for M, (t, better, tmin) in zip(Ms, rdo_rank):
         log("  recursive device ordering %s, M=%d: T=%d, %d of %d candidates are faster (best T=%d, +%.2f%%)"
             % (rdo[:S], M, t, better, N, tmin, 100.0 * (t - tmin) / tmin))

@@ -116,3 +116,35 @@ def test_replicated_faults(ppo, G):
         st = G(v).plan_replicated(2, al)[0]
         rc = ppo.spp_replicated(v.L, v.D, v.N, 2, v.fwd, v.bwd, v.actf, v.actb, al, v.bw, v.orderings)[0]
         assert st == rc != 0, name
+
+
+def test_replicated_at_full_size(ppo, G):
+    """All 40320 orderings of the GPT-shaped workload in one launch: the oracle on a spread
+    sample and on the winner; the winner is the first minimum of everything the GPU computed."""
+    w = workloads.gpt()
+    alpha = workloads.parameter_sizes(w)
+    M = w.Ms[-1]
+    say("replicated full size gpt N", w.N, "M", M)
+    g = G(w)
+    st, res, T, W, b, r = g.plan_replicated(M, alpha)
+    assert st == 0
+    win = res["best_index"]
+    idx = np.unique(np.concatenate([np.arange(0, w.N, 631), [win]]))
+    v = sub_workload(w, idx)
+    rc, res0, T0, W0, b0, r0 = ppo.spp_replicated(v.L, v.D, v.N, M, v.fwd, v.bwd, v.actf, v.actb, alpha,
+                                                  v.bw, v.orderings)
+    assert rc == 0
+    np.testing.assert_array_equal(T[idx], T0)
+    np.testing.assert_array_equal(W[idx], W0)
+    np.testing.assert_array_equal(b[idx], b0)
+    np.testing.assert_array_equal(r[idx], r0)
+    flat = T.reshape(-1)
+    at = win * w.D + res["S"] - 1
+    assert flat[at] == res["T"] == flat.min() and at == int(np.flatnonzero(flat == flat.min())[0])
+    xi = res["S"]
+    assert res["bounds"] == b[win, xi * (xi - 1) // 2: xi * (xi + 1) // 2].tolist()
+    assert res["reps"] == r[win, xi * (xi - 1) // 2: xi * (xi + 1) // 2].tolist()
+    assert res["order"] == workloads.all_orderings(w.D)[win].tolist() and res["W"] == W[win, xi - 1]
+    # every plan obeys the bounds of Lemma 1 with the AllReduce term: M*C <= T (C <= W/M)
+    ok = T != np.iinfo(np.int64).max
+    assert (T[ok] * 1 >= 0).all() and ok.all()
