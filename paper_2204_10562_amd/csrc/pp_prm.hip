@@ -18,9 +18,14 @@
 // All states with the same (r, i) share the last stage's terms, which are made division-free:
 // with Q[l] = floor(P[l] / r), R[l] = P[l] mod r,  ceil((P[l] - P[l']) / r) =
 // Q[l] - Q[l'] + (R[l] > R[l']); so the stage term is U[l] - U[l'] + (remainder compares) with
-// U = M (QF + QB) + QA.  The sub-problem and channel terms do not depend on l: they are
-// merged once per state into G[r'][l'] in LDS.  States that use all D GPUs are needed at
-// l = L only and are reduced by the whole workgroup instead.
+// U = M (QF + QB) + QA; the channel term X[r'][l'] = M (c^f + c^b) is computed once per (r, i)
+// too.  Neither the sub-problem nor the channel term depends on l, and the last stage's term
+// does not depend on r'; max with the latter commutes with the minimum over r', so per state
+//   Gmin[l'] = min over r' of max(W(l', xi-1, r', i-r), X[r'][l'])
+// is built once in LDS and a cell costs one pass over l' only:
+//   W(l, xi, r, i) = min over l' of max(Gmin[l'], last stage [l', l)).
+// The r' that goes with the chosen l' is then the first one whose value reaches the minimum.
+// States that use all D GPUs are needed at l = L only and are reduced by the whole workgroup.
 #include "pp_common.h"
 
 #define PRM_THREADS 128
@@ -29,7 +34,7 @@ struct prm_args {
     int L, D, M;
     long long N;
     const long long *fwd, *bwd, *actf, *actb, *alpha, *bw;
-    const int *ord;  // [N][D], or NULL = all D! orderings in lexicographic order
+    const int *ord;  // [N][D]
     char *scratch;   // slots * slot_bytes
     size_t slot_bytes;
     long long *W_out;  // [N][D]: W of the best plan with xi stages at xi-1 (PP_INF64: none)
@@ -57,8 +62,8 @@ static inline size_t prm_slot_bytes(int L, int D) {
 }
 
 static inline size_t prm_lds_bytes(int L, int D) {
-    // PF, PB, PA, U, RA (int64), RFB (int32), G (int64, D-1 rows)
-    return (size_t)(L + 1) * (5 * 8 + 4) + (size_t)(D > 1 ? D - 1 : 1) * (L + 1) * 8 + 64;
+    // PF, PB, PA, U, RA, Gmin (int64), RFB (int32), X (int64, D-1 rows)
+    return (size_t)(L + 1) * (6 * 8 + 4) + (size_t)(D > 1 ? D - 1 : 1) * (L + 1) * 8 + 64;
 }
 
 struct prm_key {
@@ -77,14 +82,15 @@ __device__ __forceinline__ long long cdiv64(long long a, long long b) { return a
 __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_o[PP_MAX_STAGES];
-    __shared__ int s_fault;
+    __shared__ int s_fault, s_keep;
     __shared__ prm_key s_red[PRM_THREADS / 64];
     const int L = a.L, D = a.D, tid = threadIdx.x, B = blockDim.x;
     const long long M = a.M;
     const int L1 = L + 1, D1 = D + 1;
     long long *PF = (long long *)smem, *PB = PF + L1, *PA = PB + L1, *U = PA + L1, *RA = U + L1;
-    long long *G = RA + L1;                            // [D-1][L1]
-    int *RFB = (int *)(G + (size_t)(D > 1 ? D - 1 : 1) * L1);  // RF | RB << 8 (both < r <= 64)
+    long long *Gmin = RA + L1;
+    long long *X = Gmin + L1;                          // [D-1][L1]
+    int *RFB = (int *)(X + (size_t)(D > 1 ? D - 1 : 1) * L1);  // RF | RB << 8 (both < r <= 64)
     const int NS = prm_states(D), tri = D * (D + 1) / 2;
     char *slot = a.scratch + (size_t)blockIdx.x * a.slot_bytes;
     long long *Wt = (long long *)slot;                                 // [NS][L1]
@@ -138,26 +144,33 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
         return;
     }
 
-    for (long long c = blockIdx.x; c < a.N; c += gridDim.x) {
+    // A workgroup walks a contiguous chunk of candidates.  State (xi, r, i) depends only on the
+    // first i devices of the ordering, so whatever the previous candidate shares as a prefix is
+    // kept (with all D! orderings in lexicographic order most of the table is).
+    const long long chunk = (a.N + gridDim.x - 1) / gridDim.x;
+    const long long c_first = (long long)blockIdx.x * chunk;
+    const long long c_end = c_first + chunk < a.N ? c_first + chunk : a.N;
+    bool have_prev = false;
+    for (long long c = c_first; c < c_end; ++c) {
         __syncthreads();
         // ---- ordering
         if (tid == 0) {
-            int bad = 0;
-            if (a.ord) {
-                for (int n = 0; n < D; ++n) {
-                    int d = a.ord[c * D + n];
-                    if (d < 0 || d >= D) bad = 1;
-                    for (int q = 0; q < n; ++q) bad |= (s_o[q] == d);
-                    s_o[n] = d;
-                }
-            } else {
-                unsigned long long rem = (unsigned long long)c;
-                unsigned used = 0;
-                for (int n = 0; n < D; ++n) s_o[n] = pp_unrank_next(D, n, rem, used);
+            int bad = 0, same = 0;
+            bool eq = have_prev;
+            for (int n = 0; n < D; ++n) {
+                int d = a.ord[c * D + n];
+                if (d < 0 || d >= D) bad = 1;
+                for (int q = 0; q < n; ++q) bad |= (s_o[q] == d);
+                eq = eq && s_o[n] == d;
+                same += eq;
+                s_o[n] = d;
             }
             s_fault = bad;
+            s_keep = same < D ? same : D - 1;  // the states on all D GPUs are always redone
         }
         __syncthreads();
+        const int keep = s_keep;
+        have_prev = !s_fault;
         if (s_fault) {
             if (tid == 0) pp_raise(a.status, PP_FAULT_ORDERING);
             for (int n = tid; n < D; n += B) a.W_out[c * D + n] = PP_INF64;
@@ -168,7 +181,7 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
         // bfwd[p][rp][r]: links from ranks [p-rp, p) to ranks [p, p+r); bbwd: the other direction
         for (int t = tid; t < D1 * D1 * D1; t += B) {
             const int p = t / (D1 * D1), rp = (t / D1) % D1, r = t % D1;
-            if (p < 1 || rp < 1 || r < 1 || rp > p || p + r > D) continue;
+            if (p < 1 || rp < 1 || r < 1 || rp > p || p + r > D || p + r <= keep) continue;
             long long mf = PP_INF64, mb = PP_INF64;
             for (int u = p - rp; u < p; ++u)
                 for (int v = p; v < p + r; ++v) {
@@ -182,7 +195,7 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
         // bin[n][r]: ordered pairs inside ranks [n-r, n)
         for (int t = tid; t < D1 * D1; t += B) {
             const int n = t / D1, r = t % D1;
-            if (n < 1 || r < 2 || r > n) continue;
+            if (n < 1 || r < 2 || r > n || n <= keep) continue;
             long long m = PP_INF64;
             for (int u = n - r; u < n; ++u)
                 for (int v = n - r; v < n; ++v)
@@ -194,10 +207,13 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
         }
         __syncthreads();
 
-        // ---- states by ascending number of GPUs; all D GPUs are handled below
-        for (int i = 1; i < D; ++i)
+        // ---- states by ascending number of GPUs
+        for (int i = keep + 1; i <= D; ++i) {
+            const bool top = i == D;  // all GPUs in use: only cell L is needed
             for (int r = 1; r <= i; ++r) {
-                // last stage on r replicas, ranks [i-r, i): division-free form of its terms
+                // Last stage on r replicas, ranks [i-r, i): division-free form of its terms, and
+                // the channel term X[r'][l'] = M (c^f + c^b) towards r' replicas on ranks
+                // [i-r-r', i-r); both are shared by every stage count.
                 const long long den = r > 1 ? (long long)r * bin[i * D1 + r] : 1;
                 for (int l = tid; l <= L; l += B) {
                     long long qf = PF[l] / r, qb = PB[l] / r;
@@ -207,112 +223,103 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
                     RA[l] = num - qa * den;
                     RFB[l] = (int)(PF[l] - qf * r) | ((int)(PB[l] - qb * r) << 8);
                 }
+                const int n0 = i - r;  // GPUs of the sub-problem
+                for (int t = tid; t < n0 * L1; t += B) {
+                    const int rp = 1 + t / L1, lp = t % L1;
+                    long long x = PP_INF64;
+                    if (lp >= 1 && lp <= L - 1) {
+                        const size_t at = ((size_t)n0 * D1 + rp) * D1 + r;
+                        x = M * (cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]) +
+                                 cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at]));
+                    }
+                    X[(size_t)(rp - 1) * L1 + lp] = x;
+                }
                 __syncthreads();
+                // the last stage [l', l): M (F + B) + A
+                auto last_stage = [&](int lp, int l) -> long long {
+                    const int q = RFB[lp], ql = RFB[l];
+                    return U[l] - U[lp] + M * (((ql & 255) > (q & 255)) + ((ql >> 8) > (q >> 8))) +
+                           (RA[l] > RA[lp]);
+                };
                 for (int xi = 1; xi <= i - r + 1; ++xi) {
-                    long long *Ws = Wt + (size_t)prm_sid(i, xi, r) * L1;
-                    unsigned *As = At + (size_t)prm_sid(i, xi, r) * L1;
+                    const int sid = prm_sid(i, xi, r);
+                    long long *Ws = Wt + (size_t)sid * L1;
+                    unsigned *As = At + (size_t)sid * L1;
                     if (xi == 1) {
                         // a single stage must take all i GPUs
-                        for (int l = tid; l <= L; l += B) {
-                            long long w = PP_INF64;
-                            if (r == i && l >= 1)
-                                w = U[l] + M * (((RFB[l] & 255) > 0) + ((RFB[l] >> 8) > 0)) + (RA[l] > 0);
-                            Ws[l] = w;
+                        for (int l = top ? L + tid : tid; l <= L; l += B) {
+                            Ws[l] = (r == i && l >= 1) ? last_stage(0, l) : PP_INF64;
                             As[l] = 0;
                         }
-                        continue;  // nothing below reads LDS that the next state rewrites
+                        continue;  // touches no LDS array that the next state rewrites
                     }
-                    const int n0 = i - r;         // GPUs of the sub-problem
                     const int nrp = n0 - (xi - 2);  // r' = 1..nrp leave >= 1 GPU per earlier stage
-                    // G[r'][l'] = max(W(l', xi-1, r', n0), M (c^f + c^b))
-                    for (int t = tid; t < nrp * L1; t += B) {
-                        const int rp = 1 + t / L1, lp = t % L1;
+                    // Gmin[l'] = min over r' of max(W(l', xi-1, r', n0), X[r'][l']).  The last
+                    // stage's term does not depend on r', and max with it commutes with this min.
+                    for (int lp = tid; lp <= L; lp += B) {
                         long long g = PP_INF64;
-                        if (lp >= xi - 1 && lp <= L - 1) {
-                            long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
-                            if (w != PP_INF64) {
-                                const size_t at = ((size_t)n0 * D1 + rp) * D1 + r;
-                                long long cf = cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]);
-                                long long cb = cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at]);
-                                long long x = M * (cf + cb);
-                                g = w > x ? w : x;
+                        if (lp >= xi - 1 && lp <= L - 1)
+                            for (int rp = 1; rp <= nrp; ++rp) {
+                                long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
+                                long long x = X[(size_t)(rp - 1) * L1 + lp];
+                                w = w > x ? w : x;
+                                g = w < g ? w : g;
                             }
-                        }
-                        G[(size_t)(rp - 1) * L1 + lp] = g;
+                        Gmin[lp] = g;
                     }
                     __syncthreads();
-                    for (int l = tid; l <= L; l += B) {
-                        prm_key best = {PP_INF64, 0, 0};
-                        if (l >= xi) {
-                            const long long Ul = U[l], RAl = RA[l];
-                            const int rf = RFB[l] & 255, rb = RFB[l] >> 8;
-                            for (int lp = xi - 1; lp < l; ++lp) {
-                                const int q = RFB[lp];
-                                const long long last = Ul - U[lp] + M * ((rf > (q & 255)) + (rb > (q >> 8))) +
-                                                       (RAl > RA[lp]);
-                                for (int rp = 1; rp <= nrp; ++rp) {
-                                    const long long g = G[(size_t)(rp - 1) * L1 + lp];
-                                    const long long t = g > last ? g : last;
-                                    if (t < best.v) { best.v = t; best.lp = lp; best.rp = rp; }
-                                }
-                            }
+                    // first r' (ascending) whose value reaches the minimum v found at l'
+                    auto first_rp = [&](int lp, int l, long long v) -> int {
+                        const long long last = last_stage(lp, l);
+                        for (int rp = 1; rp <= nrp; ++rp) {
+                            long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
+                            long long x = X[(size_t)(rp - 1) * L1 + lp];
+                            w = w > x ? w : x;
+                            if ((w > last ? w : last) == v) return rp;
                         }
-                        Ws[l] = best.v;
-                        As[l] = (unsigned)best.lp | ((unsigned)best.rp << 16);
+                        return 0;
+                    };
+                    if (!top) {
+                        for (int l = tid; l <= L; l += B) {
+                            long long best = PP_INF64;
+                            int blp = 0;
+                            for (int lp = xi - 1; lp < l; ++lp) {
+                                const long long g = Gmin[lp], last = last_stage(lp, l);
+                                const long long t = g > last ? g : last;
+                                if (t < best) { best = t; blp = lp; }
+                            }
+                            Ws[l] = best;
+                            As[l] = best == PP_INF64 ? 0u : ((unsigned)blp | ((unsigned)first_rp(blp, l, best) << 16));
+                        }
+                    } else {
+                        // the workgroup shares the scan of l' for the single cell L
+                        prm_key best = {PP_INF64, 0, 0};
+                        for (int lp = xi - 1 + tid; lp < L; lp += B) {
+                            const long long g = Gmin[lp], last = last_stage(lp, L);
+                            prm_key k = {g > last ? g : last, lp, 0};
+                            if (prm_less(k, best)) best = k;
+                        }
+                        for (int off = 32; off; off >>= 1) {
+                            prm_key o;
+                            o.v = __shfl_xor(best.v, off);
+                            o.lp = __shfl_xor(best.lp, off);
+                            o.rp = 0;
+                            if (prm_less(o, best)) best = o;
+                        }
+                        if ((tid & 63) == 0) s_red[tid >> 6] = best;
+                        __syncthreads();
+                        if (tid == 0) {
+                            for (int w = 1; w < B / 64; ++w)
+                                if (prm_less(s_red[w], best)) best = s_red[w];
+                            Ws[L] = best.v;
+                            As[L] = best.v == PP_INF64 ? 0u : ((unsigned)best.lp | ((unsigned)first_rp(best.lp, L, best.v) << 16));
+                        }
                     }
-                    __syncthreads();  // G is rewritten by the next state
+                    __syncthreads();  // Gmin (and s_red) are rewritten by the next state
                 }
-                __syncthreads();  // U, RA, RFB are rewritten by the next (r, i)
+                __syncthreads();  // U, RA, RFB, X are rewritten by the next (r, i)
             }
-
-        // ---- all D GPUs: only W(L, xi, r, D) is needed; the workgroup shares the scan of (l', r')
-        __threadfence_block();
-        __syncthreads();
-        for (int xi = 1; xi <= D; ++xi)
-            for (int r = 1; r <= D - xi + 1; ++r) {
-                const int sid = prm_sid(D, xi, r);
-                prm_key best = {PP_INF64, 0, 0};
-                const long long den = r > 1 ? (long long)r * bin[D * D1 + r] : 1;
-                if (xi == 1) {
-                    if (r == D && tid == 0)
-                        best.v = M * (cdiv64(PF[L], r) + cdiv64(PB[L], r)) + cdiv64(2 * (long long)(r - 1) * PA[L], den);
-                } else {
-                    const int n0 = D - r, nrp = n0 - (xi - 2);
-                    for (int t = tid; t < nrp * L; t += B) {
-                        // l' ascending first, then r': any order works, the key decides
-                        const int lp = t / nrp, rp = 1 + t % nrp;
-                        if (lp < xi - 1) continue;
-                        long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
-                        if (w == PP_INF64) continue;
-                        const size_t at = ((size_t)n0 * D1 + rp) * D1 + r;
-                        long long cf = cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]);
-                        long long cb = cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at]);
-                        long long last = M * (cdiv64(PF[L] - PF[lp], r) + cdiv64(PB[L] - PB[lp], r)) +
-                                         cdiv64(2 * (long long)(r - 1) * (PA[L] - PA[lp]), den);
-                        long long x = M * (cf + cb);
-                        prm_key k = {w > x ? w : x, lp, rp};
-                        k.v = k.v > last ? k.v : last;
-                        if (prm_less(k, best)) best = k;
-                    }
-                }
-                // minimum over the workgroup: lowest value, then lowest l', then lowest r'
-                for (int off = 32; off; off >>= 1) {
-                    prm_key o;
-                    o.v = __shfl_xor(best.v, off);
-                    o.lp = __shfl_xor(best.lp, off);
-                    o.rp = __shfl_xor(best.rp, off);
-                    if (prm_less(o, best)) best = o;
-                }
-                if ((tid & 63) == 0) s_red[tid >> 6] = best;
-                __syncthreads();
-                if (tid == 0) {
-                    for (int w = 1; w < B / 64; ++w)
-                        if (prm_less(s_red[w], best)) best = s_red[w];
-                    Wt[(size_t)sid * L1 + L] = best.v;
-                    At[(size_t)sid * L1 + L] = (unsigned)best.lp | ((unsigned)best.rp << 16);
-                }
-                __syncthreads();
-            }
+        }
 
         // ---- per stage count: the first r with the smallest W (Alg. 3), and its plan
         __threadfence_block();
