@@ -258,8 +258,8 @@ int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM,
  *   bounds_all, reps_all  [N*D(D+1)/2]: the xi entries of (c, xi) at
  *                 c*D(D+1)/2 + xi(xi-1)/2; either may be NULL
  *   workspace     pp_workspace_bytes_replicated(L, D, N) bytes, 256-byte aligned
- * Limits: D <= 16 and (44 + 8 D)(L + 1) + 64 <= 65536 (the tables of one state
- * live in LDS): L <= 605 at D = 8, L <= 379 at D = 16; otherwise
+ * Limits: D <= 16 and (48 + 8 D)(L + 1) + 88 <= 65536 (the tables of one state
+ * live in LDS): L <= 583 at D = 8, L <= 370 at D = 16; otherwise
  * PP_ERR_INVALID_ARG (pp_workspace_bytes_replicated returns 0);
  * sums of times * (M + 4D) and of parameter sizes * 2D below 2^62.
  * Faults: NEGATIVE, BANDWIDTH, ORDERING, OVERFLOW.

@@ -62,8 +62,10 @@ static inline size_t prm_slot_bytes(int L, int D) {
 }
 
 static inline size_t prm_lds_bytes(int L, int D) {
-    // PF, PB, PA, U, RA, Gmin (int64), RFB (int32), X (int64, D-1 rows)
-    return (size_t)(L + 1) * (6 * 8 + 4) + (size_t)(D > 1 ? D - 1 : 1) * (L + 1) * 8 + 64;
+    // PF, PB, PA (int64), one row record per layer position (32 bytes in the int64 form),
+    // X (int64, D-1 rows)
+    // (the three prefix arrays are padded to an even length so that the records are 16-byte aligned)
+    return (size_t)(L + 2) * (3 * 8) + (size_t)(L + 1) * 32 + (size_t)(D > 1 ? D - 1 : 1) * (L + 1) * 8 + 64;
 }
 
 struct prm_key {
@@ -79,70 +81,47 @@ __device__ __forceinline__ bool prm_less(const prm_key &a, const prm_key &b) {
 
 __device__ __forceinline__ long long cdiv64(long long a, long long b) { return a / b + (a % b != 0); }
 
-__global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ int s_o[PP_MAX_STAGES];
-    __shared__ int s_fault, s_keep;
-    __shared__ prm_key s_red[PRM_THREADS / 64];
+// Values are int64, or int32 when every finite value of the launch is known to stay below
+// 2^30 (decided on the device from bounds on the stage and channel terms).
+template <bool WIDE> struct prm_val { using V = int; };
+template <> struct prm_val<true> { using V = long long; };
+
+// What the cell loop reads per layer position l' (one LDS access in the int32 form):
+//   g  = Gmin[l'] of the current state
+//   u  = U[l'], ra = remainder of the AllReduce quotient   (current (r, i))
+//   oh = (1 << RF[l']) | (1 << (16 + RB[l'])), the remainders of the two compute quotients as
+//        one-hot bits, so that [RF[l] > RF[l']] + [RB[l] > RB[l']] is the popcount of oh
+//        masked with ((1 << RF[l]) - 1) | (((1 << RB[l]) - 1) << 16).
+template <bool WIDE> struct alignas(16) prm_row { int g, u, ra, oh; };
+template <> struct alignas(16) prm_row<true> { long long g, u, ra; int oh, pad; };
+
+struct prm_shared {
+    int o[PP_MAX_STAGES];
+    int fault, keep, wide;
+    unsigned long long amax_f, amax_b, bmin, bmax;
+    prm_key red[PRM_THREADS / 64];
+};
+
+template <bool WIDE>
+__device__ void prm_run(const prm_args &a, unsigned char *smem, prm_shared &sh) {
+    using V = typename prm_val<WIDE>::V;
+    using Row = prm_row<WIDE>;
+    const V INF = WIDE ? (V)PP_INF64 : (V)PP_INF32;
     const int L = a.L, D = a.D, tid = threadIdx.x, B = blockDim.x;
     const long long M = a.M;
+    const V Mv = (V)a.M;
     const int L1 = L + 1, D1 = D + 1;
-    long long *PF = (long long *)smem, *PB = PF + L1, *PA = PB + L1, *U = PA + L1, *RA = U + L1;
-    long long *Gmin = RA + L1;
-    long long *X = Gmin + L1;                          // [D-1][L1]
-    int *RFB = (int *)(X + (size_t)(D > 1 ? D - 1 : 1) * L1);  // RF | RB << 8 (both < r <= 64)
+    const int L1p = (L1 + 1) & ~1;  // even, so that what follows the int64 arrays is 16-byte aligned
+    long long *PF = (long long *)smem, *PB = PF + L1p, *PA = PB + L1p;
+    Row *Q = (Row *)(PA + L1p);                          // [L1]
+    V *X = (V *)((long long *)(PA + L1p) + 4 * (size_t)L1);  // [D-1][L1], after 32 bytes per record
     const int NS = prm_states(D), tri = D * (D + 1) / 2;
     char *slot = a.scratch + (size_t)blockIdx.x * a.slot_bytes;
-    long long *Wt = (long long *)slot;                                 // [NS][L1]
+    V *Wt = (V *)slot;                                                   // [NS][L1]
     unsigned *At = (unsigned *)(slot + pp_align256((size_t)NS * L1 * 8));  // l' | r' << 16
     long long *bfwd = (long long *)((char *)At + pp_align256((size_t)NS * L1 * 4));  // [p][rp][r]
     long long *bbwd = bfwd + (size_t)D1 * D1 * D1;
-    long long *bin = bbwd + (size_t)D1 * D1 * D1;                       // [n][r]
-
-    // prefix sums (every workgroup makes its own copy: L is small next to the DP) and input checks
-    if (tid == 0) s_fault = 0;
-    __syncthreads();
-    {
-        int fault = 0;
-        for (int l = tid; l < L; l += B) {
-            long long x = a.fwd[l], y = a.bwd[l], z = a.alpha[l];
-            if (x < 0 || y < 0 || z < 0) fault |= PP_FAULT_NEGATIVE;
-            if (l + 1 < L && (a.actf[l] < 0 || a.actb[l] < 0)) fault |= PP_FAULT_NEGATIVE;
-            if (x >= PP_CAP62 || y >= PP_CAP62 || z >= PP_CAP62) fault |= PP_FAULT_OVERFLOW;
-            PF[l + 1] = x; PB[l + 1] = y; PA[l + 1] = z;
-        }
-        for (int t = tid; t < D * D; t += B)
-            if (t / D != t % D && a.bw[t] <= 0) fault |= PP_FAULT_BANDWIDTH;
-        if (fault) atomicOr(&s_fault, fault);
-    }
-    __syncthreads();
-    if (tid == 0 && !s_fault) {
-        long long f = 0, b = 0, al = 0;
-        PF[0] = PB[0] = PA[0] = 0;
-        for (int l = 1; l <= L; ++l) {
-            f += PF[l]; b += PB[l]; al += PA[l];
-            // M * (time) and 2 (r-1) * (parameter bytes) must stay far from 2^63
-            if (f + b >= PP_CAP62 / (M + 4 * D) || al >= PP_CAP62 / (2 * D)) { s_fault = PP_FAULT_OVERFLOW; break; }
-            PF[l] = f; PB[l] = b; PA[l] = al;
-        }
-    }
-    __syncthreads();
-    if (blockIdx.x == 0) {
-        for (int t = tid; t < 65; t += B) a.ticket[t] = 0;
-        if (!s_fault)
-            for (int l = tid; l <= L; l += B) {
-                a.pre_out[l] = PF[l];
-                a.pre_out[L1 + l] = PB[l];
-                a.pre_out[2 * L1 + l] = PA[l];
-            }
-    }
-    if (s_fault) {
-        // nothing can be planned: every (candidate, stage count) is marked as having no plan
-        if (tid == 0 && blockIdx.x == 0) pp_raise(a.status, s_fault);
-        for (long long t = (long long)blockIdx.x * B + tid; t < a.N * D; t += (long long)gridDim.x * B)
-            a.W_out[t] = PP_INF64;
-        return;
-    }
+    long long *bin = bbwd + (size_t)D1 * D1 * D1;                        // [n][r]
 
     // A workgroup walks a contiguous chunk of candidates.  State (xi, r, i) depends only on the
     // first i devices of the ordering, so whatever the previous candidate shares as a prefix is
@@ -160,23 +139,24 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
             for (int n = 0; n < D; ++n) {
                 int d = a.ord[c * D + n];
                 if (d < 0 || d >= D) bad = 1;
-                for (int q = 0; q < n; ++q) bad |= (s_o[q] == d);
-                eq = eq && s_o[n] == d;
+                for (int q = 0; q < n; ++q) bad |= (sh.o[q] == d);
+                eq = eq && sh.o[n] == d;
                 same += eq;
-                s_o[n] = d;
+                sh.o[n] = d;
             }
-            s_fault = bad;
-            s_keep = same < D ? same : D - 1;  // the states on all D GPUs are always redone
+            sh.fault = bad;
+            sh.keep = same < D ? same : D - 1;  // the states on all D GPUs are always redone
         }
         __syncthreads();
-        const int keep = s_keep;
-        have_prev = !s_fault;
-        if (s_fault) {
+        const int keep = sh.keep;
+        have_prev = !sh.fault;
+        if (sh.fault) {
             if (tid == 0) pp_raise(a.status, PP_FAULT_ORDERING);
             for (int n = tid; n < D; n += B) a.W_out[c * D + n] = PP_INF64;
             for (int n = tid; n < tri; n += B) { a.bounds_out[c * tri + n] = 0; a.reps_out[c * tri + n] = 0; }
             continue;
         }
+        const int *o = sh.o;
         // ---- minima of the bandwidth matrix over rank sets
         // bfwd[p][rp][r]: links from ranks [p-rp, p) to ranks [p, p+r); bbwd: the other direction
         for (int t = tid; t < D1 * D1 * D1; t += B) {
@@ -185,7 +165,7 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
             long long mf = PP_INF64, mb = PP_INF64;
             for (int u = p - rp; u < p; ++u)
                 for (int v = p; v < p + r; ++v) {
-                    long long x = a.bw[(size_t)s_o[u] * D + s_o[v]], y = a.bw[(size_t)s_o[v] * D + s_o[u]];
+                    long long x = a.bw[(size_t)o[u] * D + o[v]], y = a.bw[(size_t)o[v] * D + o[u]];
                     mf = x < mf ? x : mf;
                     mb = y < mb ? y : mb;
                 }
@@ -200,7 +180,7 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
             for (int u = n - r; u < n; ++u)
                 for (int v = n - r; v < n; ++v)
                     if (u != v) {
-                        long long x = a.bw[(size_t)s_o[u] * D + s_o[v]];
+                        long long x = a.bw[(size_t)o[u] * D + o[v]];
                         m = x < m ? x : m;
                     }
             bin[t] = m;
@@ -219,36 +199,38 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
                     long long qf = PF[l] / r, qb = PB[l] / r;
                     long long num = 2 * (long long)(r - 1) * PA[l];
                     long long qa = num / den;
-                    U[l] = M * (qf + qb) + qa;
-                    RA[l] = num - qa * den;
-                    RFB[l] = (int)(PF[l] - qf * r) | ((int)(PB[l] - qb * r) << 8);
+                    Q[l].u = (V)(M * (qf + qb) + qa);
+                    Q[l].ra = (V)(num - qa * den);
+                    Q[l].oh = (1 << (int)(PF[l] - qf * r)) | (1 << (16 + (int)(PB[l] - qb * r)));
                 }
                 const int n0 = i - r;  // GPUs of the sub-problem
                 for (int t = tid; t < n0 * L1; t += B) {
                     const int rp = 1 + t / L1, lp = t % L1;
-                    long long x = PP_INF64;
+                    V x = INF;
                     if (lp >= 1 && lp <= L - 1) {
                         const size_t at = ((size_t)n0 * D1 + rp) * D1 + r;
-                        x = M * (cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]) +
-                                 cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at]));
+                        x = (V)(M * (cdiv64(a.actf[lp - 1], (long long)rp * r * bfwd[at]) +
+                                     cdiv64(a.actb[lp - 1], (long long)rp * r * bbwd[at])));
                     }
                     X[(size_t)(rp - 1) * L1 + lp] = x;
                 }
                 __syncthreads();
-                // the last stage [l', l): M (F + B) + A
-                auto last_stage = [&](int lp, int l) -> long long {
-                    const int q = RFB[lp], ql = RFB[l];
-                    return U[l] - U[lp] + M * (((ql & 255) > (q & 255)) + ((ql >> 8) > (q >> 8))) +
-                           (RA[l] > RA[lp]);
+                // the last stage [l', l): M (F + B) + A, from the records of l' and l
+                auto last_stage = [&](const Row &q, const Row &ql, int mask) -> V {
+                    return ql.u - q.u + Mv * (V)__popc((unsigned)(q.oh & mask)) + (V)(ql.ra > q.ra);
+                };
+                auto mask_of = [](int oh) -> int {
+                    // remainders (f, b) one-hot at bits f and 16 + b -> all lower bits of each half
+                    return oh - 0x10001;
                 };
                 for (int xi = 1; xi <= i - r + 1; ++xi) {
                     const int sid = prm_sid(i, xi, r);
-                    long long *Ws = Wt + (size_t)sid * L1;
+                    V *Ws = Wt + (size_t)sid * L1;
                     unsigned *As = At + (size_t)sid * L1;
                     if (xi == 1) {
                         // a single stage must take all i GPUs
                         for (int l = top ? L + tid : tid; l <= L; l += B) {
-                            Ws[l] = (r == i && l >= 1) ? last_stage(0, l) : PP_INF64;
+                            Ws[l] = (r == i && l >= 1) ? last_stage(Q[0], Q[l], mask_of(Q[l].oh)) : INF;
                             As[l] = 0;
                         }
                         continue;  // touches no LDS array that the next state rewrites
@@ -257,23 +239,23 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
                     // Gmin[l'] = min over r' of max(W(l', xi-1, r', n0), X[r'][l']).  The last
                     // stage's term does not depend on r', and max with it commutes with this min.
                     for (int lp = tid; lp <= L; lp += B) {
-                        long long g = PP_INF64;
+                        V g = INF;
                         if (lp >= xi - 1 && lp <= L - 1)
                             for (int rp = 1; rp <= nrp; ++rp) {
-                                long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
-                                long long x = X[(size_t)(rp - 1) * L1 + lp];
+                                V w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
+                                V x = X[(size_t)(rp - 1) * L1 + lp];
                                 w = w > x ? w : x;
                                 g = w < g ? w : g;
                             }
-                        Gmin[lp] = g;
+                        Q[lp].g = g;
                     }
                     __syncthreads();
                     // first r' (ascending) whose value reaches the minimum v found at l'
-                    auto first_rp = [&](int lp, int l, long long v) -> int {
-                        const long long last = last_stage(lp, l);
+                    auto first_rp = [&](int lp, int l, V v) -> int {
+                        const V last = last_stage(Q[lp], Q[l], mask_of(Q[l].oh));
                         for (int rp = 1; rp <= nrp; ++rp) {
-                            long long w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
-                            long long x = X[(size_t)(rp - 1) * L1 + lp];
+                            V w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
+                            V x = X[(size_t)(rp - 1) * L1 + lp];
                             w = w > x ? w : x;
                             if ((w > last ? w : last) == v) return rp;
                         }
@@ -281,43 +263,51 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
                     };
                     if (!top) {
                         for (int l = tid; l <= L; l += B) {
-                            long long best = PP_INF64;
+                            const Row ql = Q[l];
+                            const int mask = mask_of(ql.oh);
+                            V best = INF;
                             int blp = 0;
                             for (int lp = xi - 1; lp < l; ++lp) {
-                                const long long g = Gmin[lp], last = last_stage(lp, l);
-                                const long long t = g > last ? g : last;
+                                const Row q = Q[lp];
+                                const V last = last_stage(q, ql, mask);
+                                const V t = q.g > last ? q.g : last;
                                 if (t < best) { best = t; blp = lp; }
                             }
                             Ws[l] = best;
-                            As[l] = best == PP_INF64 ? 0u : ((unsigned)blp | ((unsigned)first_rp(blp, l, best) << 16));
+                            As[l] = best == INF ? 0u : ((unsigned)blp | ((unsigned)first_rp(blp, l, best) << 16));
                         }
                     } else {
                         // the workgroup shares the scan of l' for the single cell L
+                        const Row ql = Q[L];
+                        const int mask = mask_of(ql.oh);
                         prm_key best = {PP_INF64, 0, 0};
                         for (int lp = xi - 1 + tid; lp < L; lp += B) {
-                            const long long g = Gmin[lp], last = last_stage(lp, L);
-                            prm_key k = {g > last ? g : last, lp, 0};
+                            const Row q = Q[lp];
+                            const V last = last_stage(q, ql, mask);
+                            const V t = q.g > last ? q.g : last;
+                            prm_key k = {t == INF ? PP_INF64 : (long long)t, lp, 0};
                             if (prm_less(k, best)) best = k;
                         }
                         for (int off = 32; off; off >>= 1) {
-                            prm_key o;
-                            o.v = __shfl_xor(best.v, off);
-                            o.lp = __shfl_xor(best.lp, off);
-                            o.rp = 0;
-                            if (prm_less(o, best)) best = o;
+                            prm_key ok;
+                            ok.v = __shfl_xor(best.v, off);
+                            ok.lp = __shfl_xor(best.lp, off);
+                            ok.rp = 0;
+                            if (prm_less(ok, best)) best = ok;
                         }
-                        if ((tid & 63) == 0) s_red[tid >> 6] = best;
+                        if ((tid & 63) == 0) sh.red[tid >> 6] = best;
                         __syncthreads();
                         if (tid == 0) {
                             for (int w = 1; w < B / 64; ++w)
-                                if (prm_less(s_red[w], best)) best = s_red[w];
-                            Ws[L] = best.v;
-                            As[L] = best.v == PP_INF64 ? 0u : ((unsigned)best.lp | ((unsigned)first_rp(best.lp, L, best.v) << 16));
+                                if (prm_less(sh.red[w], best)) best = sh.red[w];
+                            const bool none = best.v == PP_INF64;
+                            Ws[L] = none ? INF : (V)best.v;
+                            As[L] = none ? 0u : ((unsigned)best.lp | ((unsigned)first_rp(best.lp, L, (V)best.v) << 16));
                         }
                     }
-                    __syncthreads();  // Gmin (and s_red) are rewritten by the next state
+                    __syncthreads();  // the g fields (and sh.red) are rewritten by the next state
                 }
-                __syncthreads();  // U, RA, RFB, X are rewritten by the next (r, i)
+                __syncthreads();  // the records and X are rewritten by the next (r, i)
             }
         }
 
@@ -325,18 +315,18 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
         __threadfence_block();
         __syncthreads();
         for (int xi = 1 + tid; xi <= D; xi += B) {
-            long long wbest = PP_INF64;
+            V wbest = INF;
             int rbest = 0;
             for (int r = 1; r <= D - xi + 1; ++r) {
-                long long w = Wt[(size_t)prm_sid(D, xi, r) * L1 + L];
+                V w = Wt[(size_t)prm_sid(D, xi, r) * L1 + L];
                 if (w < wbest) { wbest = w; rbest = r; }
             }
-            a.W_out[c * D + xi - 1] = wbest;
+            a.W_out[c * D + xi - 1] = wbest == INF ? PP_INF64 : (long long)wbest;
             int *bo = a.bounds_out + c * tri + xi * (xi - 1) / 2;
             int *ro = a.reps_out + c * tri + xi * (xi - 1) / 2;
             int l = L, n = D, r = rbest;
             for (int s = xi - 1; s >= 0; --s) {
-                if (wbest == PP_INF64) { bo[s] = 0; ro[s] = 0; continue; }
+                if (wbest == INF) { bo[s] = 0; ro[s] = 0; continue; }
                 bo[s] = l;
                 ro[s] = r;
                 unsigned arg = At[(size_t)prm_sid(n, s + 1, r) * L1 + l];
@@ -346,6 +336,94 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
             }
         }
     }
+}
+
+__global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ prm_shared sh;
+    const int L = a.L, D = a.D, tid = threadIdx.x, B = blockDim.x;
+    const long long M = a.M;
+    const int L1 = L + 1, L1p = (L1 + 1) & ~1;
+    long long *PF = (long long *)smem, *PB = PF + L1p, *PA = PB + L1p;
+
+    // prefix sums (every workgroup makes its own copy: L is small next to the DP), input checks
+    // and the bounds that decide between int32 and int64 values
+    if (tid == 0) {
+        sh.fault = 0;
+        sh.amax_f = sh.amax_b = sh.bmax = 0;
+        sh.bmin = ~0ull;
+    }
+    __syncthreads();
+    {
+        int fault = 0;
+        unsigned long long af = 0, ab = 0, lo = ~0ull, hi = 0;
+        for (int l = tid; l < L; l += B) {
+            long long x = a.fwd[l], y = a.bwd[l], z = a.alpha[l];
+            if (x < 0 || y < 0 || z < 0) fault |= PP_FAULT_NEGATIVE;
+            if (l + 1 < L) {
+                long long f = a.actf[l], b = a.actb[l];
+                if (f < 0 || b < 0) fault |= PP_FAULT_NEGATIVE;
+                af = (unsigned long long)f > af ? (unsigned long long)f : af;
+                ab = (unsigned long long)b > ab ? (unsigned long long)b : ab;
+            }
+            if (x >= PP_CAP62 || y >= PP_CAP62 || z >= PP_CAP62) fault |= PP_FAULT_OVERFLOW;
+            PF[l + 1] = x; PB[l + 1] = y; PA[l + 1] = z;
+        }
+        for (int t = tid; t < D * D; t += B)
+            if (t / D != t % D) {
+                long long b = a.bw[t];
+                if (b <= 0) fault |= PP_FAULT_BANDWIDTH;
+                lo = (unsigned long long)b < lo ? (unsigned long long)b : lo;
+                hi = (unsigned long long)b > hi ? (unsigned long long)b : hi;
+            }
+        if (fault) atomicOr(&sh.fault, fault);
+        atomicMax(&sh.amax_f, af);
+        atomicMax(&sh.amax_b, ab);
+        atomicMax(&sh.bmax, hi);
+        atomicMin(&sh.bmin, lo);
+    }
+    __syncthreads();
+    if (tid == 0 && !sh.fault) {
+        long long f = 0, b = 0, al = 0;
+        PF[0] = PB[0] = PA[0] = 0;
+        for (int l = 1; l <= L; ++l) {
+            f += PF[l]; b += PB[l]; al += PA[l];
+            // M * (time) and 2 (r-1) * (parameter bytes) must stay far from 2^63
+            if (f + b >= PP_CAP62 / (M + 4 * D) || al >= PP_CAP62 / (2 * D)) { sh.fault = PP_FAULT_OVERFLOW; break; }
+            PF[l] = f; PB[l] = b; PA[l] = al;
+        }
+        // int32 values if the largest stage term, the largest channel term and the largest
+        // AllReduce remainder all stay below 2^30
+        const long long lim = 1ll << 30;
+        bool narrow = !sh.fault && M < (1 << 20);
+        if (narrow && D > 1) {
+            const long long bmin = (long long)sh.bmin;
+            narrow = (long long)sh.bmax < lim / D &&
+                     cdiv64((long long)sh.amax_f, bmin) + cdiv64((long long)sh.amax_b, bmin) < lim / M &&
+                     2 * al / bmin + 1 < lim / 2;
+        }
+        narrow = narrow && f + b + 2 < lim / (2 * M);
+        sh.wide = !narrow;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        for (int t = tid; t < 65; t += B) a.ticket[t] = 0;
+        if (!sh.fault)
+            for (int l = tid; l <= L; l += B) {
+                a.pre_out[l] = PF[l];
+                a.pre_out[L1 + l] = PB[l];
+                a.pre_out[2 * L1 + l] = PA[l];
+            }
+    }
+    if (sh.fault) {
+        // nothing can be planned: every (candidate, stage count) is marked as having no plan
+        if (tid == 0 && blockIdx.x == 0) pp_raise(a.status, sh.fault);
+        for (long long t = (long long)blockIdx.x * B + tid; t < a.N * D; t += (long long)gridDim.x * B)
+            a.W_out[t] = PP_INF64;
+        return;
+    }
+    if (sh.wide) prm_run<true>(a, smem, sh);
+    else prm_run<false>(a, smem, sh);
 }
 
 // Row c = the ordering of lexicographic rank c among all D! (D <= 20).

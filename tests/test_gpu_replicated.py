@@ -148,3 +148,25 @@ def test_replicated_at_full_size(ppo, G):
     # every plan obeys the bounds of Lemma 1 with the AllReduce term: M*C <= T (C <= W/M)
     ok = T != np.iinfo(np.int64).max
     assert (T[ok] * 1 >= 0).all() and ok.all()
+
+
+@pytest.mark.parametrize("seed,L,D,N,what", [(541, 20, 4, 12, "times"), (542, 12, 5, 10, "acts"),
+                                              (543, 16, 4, 8, "bandwidth"), (544, 14, 4, 8, "alpha")])
+def test_replicated_wide_values(ppo, G, seed, L, D, N, what):
+    # values beyond 2^30 somewhere: the int64 form of the tables must give the same answers
+    w = workloads.random_small(seed, L, D, D, N, zero_frac=0.1, hi_time=9, hi_act=300)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    alpha = rng.integers(0, 300, size=L).astype(np.int64)
+    if what == "times":
+        w.fwd = w.fwd << 28
+        w.bwd = w.bwd << 28
+    elif what == "acts":
+        w.actf = w.actf << 30
+        w.actb = w.actb << 30
+    elif what == "bandwidth":
+        w.bw = w.bw << 29
+        w.actf = w.actf << 29
+    else:
+        alpha = alpha << 34
+    say("replicated wide", what, seed, L, D, N)
+    check(ppo, G, w, alpha, 5)
