@@ -217,7 +217,9 @@ __device__ void prm_run(const prm_args &a, unsigned char *smem, prm_shared &sh) 
                 __syncthreads();
                 // the last stage [l', l): M (F + B) + A, from the records of l' and l
                 auto last_stage = [&](const Row &q, const Row &ql, int mask) -> V {
-                    return ql.u - q.u + Mv * (V)__popc((unsigned)(q.oh & mask)) + (V)(ql.ra > q.ra);
+                    const int flags = __popc((unsigned)(q.oh & mask));  // 0, 1 or 2
+                    const V extra = WIDE ? Mv * (V)flags : (V)__mul24(flags, (int)Mv);  // M < 2^20 here
+                    return ql.u - q.u + extra + (V)(ql.ra > q.ra);
                 };
                 auto mask_of = [](int oh) -> int {
                     // remainders (f, b) one-hot at bits f and 16 + b -> all lower bits of each half
@@ -240,13 +242,24 @@ __device__ void prm_run(const prm_args &a, unsigned char *smem, prm_shared &sh) 
                     // stage's term does not depend on r', and max with it commutes with this min.
                     for (int lp = tid; lp <= L; lp += B) {
                         V g = INF;
-                        if (lp >= xi - 1 && lp <= L - 1)
-                            for (int rp = 1; rp <= nrp; ++rp) {
-                                V w = Wt[(size_t)prm_sid(n0, xi - 1, rp) * L1 + lp];
-                                V x = X[(size_t)(rp - 1) * L1 + lp];
-                                w = w > x ? w : x;
-                                g = w < g ? w : g;
+                        if (lp >= xi - 1 && lp <= L - 1) {
+                            // four loads in flight at a time; a clamped r' repeats the last one
+                            const V *Wsub = Wt + (size_t)prm_sid(n0, xi - 1, 1) * L1 + lp;  // r' = 1, 2, ...
+                            for (int rp0 = 1; rp0 <= nrp; rp0 += 4) {
+                                V w[4], x[4];
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) {
+                                    const int rp = rp0 + k <= nrp ? rp0 + k : nrp;
+                                    w[k] = Wsub[(size_t)(rp - 1) * L1];
+                                    x[k] = X[(size_t)(rp - 1) * L1 + lp];
+                                }
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) {
+                                    const V m = w[k] > x[k] ? w[k] : x[k];
+                                    g = m < g ? m : g;
+                                }
                             }
+                        }
                         Q[lp].g = g;
                     }
                     __syncthreads();
@@ -267,11 +280,30 @@ __device__ void prm_run(const prm_args &a, unsigned char *smem, prm_shared &sh) 
                             const int mask = mask_of(ql.oh);
                             V best = INF;
                             int blp = 0;
-                            for (int lp = xi - 1; lp < l; ++lp) {
+                            // Splits from l-1 downwards: the last stage's term grows as l'
+                            // falls, so once it alone exceeds the best value no lower l' can
+                            // match it.  '<=' keeps the lowest l' among equal values, which is
+                            // what the ascending scan with '<' of the listing keeps.
+                            int lp = l - 1;
+                            for (; lp - 3 >= xi - 1; lp -= 4) {
+                                Row q[4];
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) q[k] = Q[lp - k];
+                                V last = 0;
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) {
+                                    last = last_stage(q[k], ql, mask);
+                                    const V t = q[k].g > last ? q[k].g : last;
+                                    if (t <= best) { best = t; blp = lp - k; }
+                                }
+                                if (last > best) { lp = xi - 2; break; }  // nothing below can win
+                            }
+                            for (; lp >= xi - 1; --lp) {
                                 const Row q = Q[lp];
                                 const V last = last_stage(q, ql, mask);
+                                if (last > best) break;
                                 const V t = q.g > last ? q.g : last;
-                                if (t < best) { best = t; blp = lp; }
+                                if (t <= best) { best = t; blp = lp; }
                             }
                             Ws[l] = best;
                             As[l] = best == INF ? 0u : ((unsigned)blp | ((unsigned)first_rp(blp, l, best) << 16));
