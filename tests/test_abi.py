@@ -75,3 +75,46 @@ def test_host_side_argument_errors_enqueue_nothing(libpp):
     assert libpp.pp_best_plan_multi(16, 4, 4, 24, 2, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1  # M = 0
     assert libpp.pp_best_plan_multi(16, 4, 4, 24, 17, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1
     assert libpp.pp_best_plan_multi(16, 4, 4, 24, 0, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1
+
+
+def test_stage_search_and_replicated_argument_errors(libpp):
+    from paper_2204_10562_amd import binding
+    z = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)
+    Ms = (ctypes.c_int32 * 2)(4, 8)
+    mp = ctypes.cast(Ms, ctypes.c_void_p)
+    # workspace sizes: the stage search needs more than the plain path, and grows with nM
+    a = binding.pp_workspace_bytes(128, 8, 8, 40320)
+    b1 = binding.pp_workspace_bytes_stages(128, 8, 8, 40320, 1)
+    b4 = binding.pp_workspace_bytes_stages(128, 8, 8, 40320, 4)
+    assert b4 > b1 > a and b4 % 256 == 0
+    assert binding.pp_workspace_bytes_stages(128, 8, 8, 40320, 0) == 0
+    assert binding.pp_workspace_bytes_stages(128, 8, 8, 40320, 17) == 0
+    assert binding.pp_workspace_bytes_stages(128, 8, 9, 40320, 1) == 0
+    assert libpp.pp_partition_dp_stages(16, 4, 5, 24, one, one, one, one, one, one, one, one, 1 << 30, z, z) == -1
+    assert libpp.pp_partition_dp_stages(16, 4, 4, 24, one, one, one, one, z, one, one, one, 16, z, z) == -2
+    assert libpp.pp_best_plan_stages(16, 4, 4, 24, 2, mp, one, one, one, one, z, z, z, z, one, 1 << 30, z, z) == -1  # no out
+    assert libpp.pp_best_plan_stages(16, 4, 4, 24, 2, mp, one, one, one, one, z, one, z, z, one, 4096, z, z) == -2  # too small
+    # replicated planner: limits on D and on what fits in LDS, all D devices per ordering
+    r = binding.pp_workspace_bytes_replicated(128, 8, 40320)
+    assert r > 0 and r % 256 == 0
+    assert binding.pp_workspace_bytes_replicated(583, 8, 10) > 0
+    assert binding.pp_workspace_bytes_replicated(584, 8, 10) == 0
+    assert binding.pp_workspace_bytes_replicated(370, 16, 10) > 0
+    assert binding.pp_workspace_bytes_replicated(371, 16, 10) == 0
+    assert binding.pp_workspace_bytes_replicated(16, 17, 10) == 0
+    args = (one,) * 6
+    assert libpp.pp_plan_replicated(16, 17, 10, 4, *args, one, one, z, z, z, z, one, 1 << 30, z, z) == -1   # D > 16
+    assert libpp.pp_plan_replicated(16, 4, 23, 4, *args, z, one, z, z, z, z, one, 1 << 30, z, z) == -1    # N != D!
+    assert libpp.pp_plan_replicated(16, 4, 24, 0, *args, z, one, z, z, z, z, one, 1 << 30, z, z) == -1    # M = 0
+    assert libpp.pp_plan_replicated(16, 4, 24, 4, *args, z, z, z, z, z, z, one, 1 << 30, z, z) == -1      # no out
+    assert libpp.pp_plan_replicated(16, 4, 24, 4, *args, z, one, z, z, z, z, one, 256, z, z) == -2        # too small
+    assert libpp.pp_plan_replicated(16, 4, 24, 4, *args, z, one, z, z, z, z, ctypes.c_void_p(264), 1 << 30, z, z) == -2
+    # device ordering: host function
+    assert libpp.pp_rdo_order(0, one, one) == -1 and libpp.pp_rdo_order(1025, one, one) == -1
+    assert libpp.pp_rdo_order(4, z, one) == -1
+
+
+def test_rep_result_struct_size():
+    from paper_2204_10562_amd import binding
+    assert binding.REP_RESULT_BYTES == 8 * 3 + 4 + 4 * 64 * 3 + 4
