@@ -25,7 +25,7 @@ ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9
 OPS_PER_PAIR = 3  # subtract, max, min on 32-bit keys per (cell, split) pair
 # HBM bytes per k_dp_tile<16> launch on the GPT workload: scaled FETCH_SIZE + WRITE_SIZE from
 # two rocprofv3 --pmc runs (profiles/dp_tile_gpt_hbm_traffic.txt)
-DP_TRAFFIC_BYTES = {"gpt": 3.51e6}
+DP_TRAFFIC_BYTES = {"gpt": 3.53e6}
 
 
 def log(*a):
@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--workload", default="gpt", choices=["tiny", "transformer", "gpt", "hetero", "stress"])
     ap.add_argument("--candidates", type=int, default=0, help="override N for the sampled workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the diagnostics outside the step (stage-count search, replicated planner, "
+                         "rank of the min-cut ordering), e.g. for profiling the step's kernels alone")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="instead of the workload, run 10 plain device copies of this many MiB "
                          "(reference for scaling the FETCH_SIZE / WRITE_SIZE counters)")
@@ -113,37 +116,39 @@ def main():
     t_mk = {M: timed(lambda M=M: pp.pp_schedule_makespan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, bounds, T, g.status), reps) for M in Ms}
     t_multi = timed(lambda: pp.pp_best_plan_multi(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status), reps)
     t_best = {M: timed(lambda M=M: pp.pp_best_plan(L, D, S, N, M, g.PF, g.PB, g.XF, g.XB, g.orderings, out, None, None, ws, g.status), reps) for M in Ms}
-    # the stage-count search (Alg. 3's outer loop) over the same candidates: not part of the step
-    ws_st = torch.empty(pp.pp_workspace_bytes_stages(L, D, S, N, len(Ms)), dtype=torch.uint8, device=dev)
-    C_st = torch.empty(N * S, dtype=torch.int64, device=dev)
-    b_st = torch.empty(N * (S * (S + 1) // 2), dtype=torch.int32, device=dev)
-    out_st = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
-    t_dp_st = timed(lambda: pp.pp_partition_dp_stages(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C_st, b_st, ws_st, g.status), reps)
-    t_stages = timed(lambda: pp.pp_best_plan_stages(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out_st, None, None, ws_st, g.status), reps)
-    stage_winner = pp.read_result(out_st, None, len(Ms) - 1)
-    del ws_st, C_st, b_st
-    # the planner with replicated stages (Alg. 3 + Alg. 4) over the same orderings: not in the step
-    t_rep = rep_winner = None
-    if pp.pp_workspace_bytes_replicated(L, D, N) and S == D and N <= 100000:
-        import numpy as np
-        alpha = torch.from_numpy(workloads.parameter_sizes(w)).to(dev)
-        ws_rep = torch.empty(pp.pp_workspace_bytes_replicated(L, D, N), dtype=torch.uint8, device=dev)
-        out_rep = torch.zeros(pp.REP_RESULT_BYTES, dtype=torch.uint8, device=dev)
-        t_rep = timed(lambda: pp.pp_plan_replicated(L, D, N, Ms[-1], g.fwd, g.bwd, g.actf, g.actb, alpha, g.bw,
-                                                    g.orderings, out_rep, None, None, None, None, ws_rep, g.status), 5)
-        rep_winner = pp.read_rep_result(out_rep, D)
-        del ws_rep
-    # the recursive device ordering (Alg. 2) as one more candidate: where does it rank?
-    rdo = pp.pp_rdo_order(D, w.bw.reshape(-1).tolist())
-    T_all = torch.empty(N * len(Ms), dtype=torch.int64, device=dev)
-    pp.pp_best_plan_multi(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out, T_all, None, ws, g.status)
-    T_all = T_all.reshape(len(Ms), N)
-    o_rdo = torch.tensor(rdo[:S], dtype=torch.int32, device=dev)
-    out1 = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
-    T_rdo = torch.empty(len(Ms), dtype=torch.int64, device=dev)
-    pp.pp_best_plan_multi(L, D, S, 1, Ms, g.PF, g.PB, g.XF, g.XB, o_rdo, out1, T_rdo, None, ws, g.status)
-    rdo_rank = [(int(T_rdo[q].item()), int((T_all[q] < T_rdo[q]).sum().item()), int(T_all[q].min().item())) for q in range(len(Ms))]
-    del T_all
+    t_rep = rep_winner = t_stages = None
+    rdo_rank = []
+    if not args.no_extras:
+        # the stage-count search (Alg. 3's outer loop) over the same candidates: not part of the step
+        ws_st = torch.empty(pp.pp_workspace_bytes_stages(L, D, S, N, len(Ms)), dtype=torch.uint8, device=dev)
+        C_st = torch.empty(N * S, dtype=torch.int64, device=dev)
+        b_st = torch.empty(N * (S * (S + 1) // 2), dtype=torch.int32, device=dev)
+        out_st = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
+        t_dp_st = timed(lambda: pp.pp_partition_dp_stages(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C_st, b_st, ws_st, g.status), reps)
+        t_stages = timed(lambda: pp.pp_best_plan_stages(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out_st, None, None, ws_st, g.status), reps)
+        stage_winner = pp.read_result(out_st, None, len(Ms) - 1)
+        del ws_st, C_st, b_st
+        # the planner with replicated stages (Alg. 3 + Alg. 4) over the same orderings: not in the step
+        if pp.pp_workspace_bytes_replicated(L, D, N) and S == D and N <= 100000:
+            import numpy as np
+            alpha = torch.from_numpy(workloads.parameter_sizes(w)).to(dev)
+            ws_rep = torch.empty(pp.pp_workspace_bytes_replicated(L, D, N), dtype=torch.uint8, device=dev)
+            out_rep = torch.zeros(pp.REP_RESULT_BYTES, dtype=torch.uint8, device=dev)
+            t_rep = timed(lambda: pp.pp_plan_replicated(L, D, N, Ms[-1], g.fwd, g.bwd, g.actf, g.actb, alpha, g.bw,
+                                                        g.orderings, out_rep, None, None, None, None, ws_rep, g.status), 5)
+            rep_winner = pp.read_rep_result(out_rep, D)
+            del ws_rep
+        # the recursive device ordering (Alg. 2) as one more candidate: where does it rank?
+        rdo = pp.pp_rdo_order(D, w.bw.reshape(-1).tolist())
+        T_all = torch.empty(N * len(Ms), dtype=torch.int64, device=dev)
+        pp.pp_best_plan_multi(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out, T_all, None, ws, g.status)
+        T_all = T_all.reshape(len(Ms), N)
+        o_rdo = torch.tensor(rdo[:S], dtype=torch.int32, device=dev)
+        out1 = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
+        T_rdo = torch.empty(len(Ms), dtype=torch.int64, device=dev)
+        pp.pp_best_plan_multi(L, D, S, 1, Ms, g.PF, g.PB, g.XF, g.XB, o_rdo, out1, T_rdo, None, ws, g.status)
+        rdo_rank = [(int(T_rdo[q].item()), int((T_all[q] < T_rdo[q]).sum().item()), int(T_all[q].min().item())) for q in range(len(Ms))]
+        del T_all
     assert int(g.status.item()) == 0
     # what the DP really evaluated (rows shared by consecutive candidates are computed once)
     pp.pp_partition_dp(L, D, S, N, g.PF, g.PB, g.XF, g.XB, g.orderings, C, bounds, ws, g.status)
@@ -164,9 +169,10 @@ def main():
     log("  pp_best_plan_multi     %9.1f us   %.3e plans/s" % (t_multi * 1e6, N * len(Ms) / t_multi))
     log("  whole step             %9.1f us   %.3e plans/s" % (ms_per_step * 1e3, plans_per_s))
     log("  winner:", winner)
-    log("  stage-count search (not in the step): pp_partition_dp_stages %.1f us, pp_best_plan_stages %.1f us = %.3e (candidate, stage count, M) plans/s"
-        % (t_dp_st * 1e6, t_stages * 1e6, N * S * len(Ms) / t_stages))
-    log("     winner over stage counts 1..%d for M=%d:" % (S, Ms[-1]), stage_winner)
+    if t_stages is not None:
+        log("  stage-count search (not in the step): pp_partition_dp_stages %.1f us, pp_best_plan_stages %.1f us = %.3e (candidate, stage count, M) plans/s"
+            % (t_dp_st * 1e6, t_stages * 1e6, N * S * len(Ms) / t_stages))
+        log("     winner over stage counts 1..%d for M=%d:" % (S, Ms[-1]), stage_winner)
     if t_rep is not None:
         log("  planner with replicated stages (not in the step), M=%d: pp_plan_replicated %.1f ms = %.3e orderings/s"
             % (Ms[-1], t_rep * 1e3, N / t_rep))
