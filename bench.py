@@ -218,6 +218,18 @@ def main():
                      "pair_evals_nominal_per_launch": pairs, "ops_per_pair": OPS_PER_PAIR},
         "cpu_baseline": cpu,
     }
+    if t_stages is not None:
+        # measured outside the timed step: the rows built on top of the hot path
+        line["extras"] = {
+            "stage_search": {"entry_point": "pp_best_plan_stages", "us_per_call": t_stages * 1e6,
+                             "scheduled_plans_per_s": N * S * len(Ms) / t_stages,
+                             "dp_with_all_stage_counts_us": t_dp_st * 1e6},
+            "replicated_planner": None if t_rep is None else {
+                "entry_point": "pp_plan_replicated", "M": Ms[-1], "ms_per_call": t_rep * 1e3,
+                "orderings_per_s": N / t_rep},
+            "min_cut_ordering": [{"M": M, "T": t, "candidates_faster": better, "best_T": tmin}
+                                 for M, (t, better, tmin) in zip(Ms, rdo_rank)],
+        }
     print(json.dumps(line), flush=True)
 
 
