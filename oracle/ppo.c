@@ -942,3 +942,155 @@ int ppo_spp_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
     free(PF); free(PB); free(PA); free(T); free(W); free(bd); free(rp); free(own);
     return fault;
 }
+
+/* ------------------------------------------------------------------ */
+/* Schedule variants (for comparison with the PE scheduler)             */
+/* ------------------------------------------------------------------ */
+
+/*
+ * A schedule variant is a block list per microbatch, a resource per block and a service
+ * order per resource; the timing rule is the scheduling phase of Alg. 1 in every case (an
+ * item starts when its microbatch has left the preceding block and the resource is idle).
+ *   PPO_SCHED_PE      the PE scheduler itself (same result as ppo_pe_makespan)
+ *   PPO_SCHED_DUPLEX  PE's blocks and ordering phase, but the forward and the backward
+ *                     transfers of a stage pair run on separate channels
+ *   PPO_SCHED_GPIPE   every stage and channel serves all its forward items (microbatch
+ *                     order) before any backward item: "all FP before any BP" (Sec. II).
+ *                     The last stage's forward and backward are separate blocks here.
+ */
+int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F, const int64_t *B,
+                             const int64_t *cf, const int64_t *cb) {
+    if (S < 1 || S > PPO_MAX_STAGES || M < 1 || !F || !B || (S > 1 && (!cf || !cb))) return -1;
+    if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE) return -1;
+    const int merged = variant != PPO_SCHED_GPIPE;       /* last stage: one block or two */
+    const int J = merged ? 4 * S - 3 : 4 * S - 2;          /* blocks per microbatch */
+    const int nres = 3 * S;                                 /* stages, fwd channels, bwd channels */
+    int *res = (int *)malloc((size_t)(J + 1) * sizeof(int));
+    int *is_fwd = (int *)malloc((size_t)(J + 1) * sizeof(int));
+    int64_t *dur = (int64_t *)malloc((size_t)(J + 1) * sizeof(int64_t));
+    int64_t *done = (int64_t *)malloc((size_t)(J + 1) * (M + 1) * sizeof(int64_t));
+    int64_t *idle_at = (int64_t *)calloc((size_t)nres, sizeof(int64_t));
+    int *next = (int *)calloc((size_t)nres, sizeof(int));
+    int *Ulen = (int *)calloc((size_t)nres, sizeof(int));
+    pe_item *Uall = (pe_item *)malloc((size_t)nres * 2 * M * sizeof(pe_item));
+    int32_t *Q = (int32_t *)malloc((size_t)(J + 2) * M * sizeof(int32_t));
+    int *head = (int *)calloc((size_t)J + 2, sizeof(int));
+    int *tail = (int *)calloc((size_t)J + 2, sizeof(int));
+    char *nonempty = (char *)malloc((size_t)J + 2);
+    int64_t T = -1;
+    if (!res || !is_fwd || !dur || !done || !idle_at || !next || !Ulen || !Uall || !Q || !head || !tail || !nonempty)
+        goto out;
+
+    /* the blocks a microbatch passes, in order: forward through the stages and channels,
+     * then backward; resources: stage n = n, forward channel n = S + n, backward channel
+     * n = 2S + n (or S + n as well when both directions share the channel) */
+    {
+        int j = 0;
+        for (int n = 0; n < S; ++n) {
+            if (n) { ++j; res[j] = S + n; dur[j] = cf[n]; is_fwd[j] = 1; }
+            ++j; res[j] = n; is_fwd[j] = 1;
+            dur[j] = (n == S - 1 && merged) ? F[n] + B[n] : F[n];
+        }
+        for (int n = S - 1; n >= 0; --n) {
+            if (!(n == S - 1 && merged)) { ++j; res[j] = n; dur[j] = B[n]; is_fwd[j] = 0; }
+            if (n) {
+                ++j; dur[j] = cb[n]; is_fwd[j] = 0;
+                res[j] = variant == PPO_SCHED_DUPLEX ? 2 * S + n : S + n;
+            }
+        }
+        if (j != J) goto out;
+    }
+#define ULIST(r) (Uall + (size_t)(r) * 2 * M)
+    if (variant == PPO_SCHED_GPIPE) {
+        /* all forward items of a resource in microbatch order, then all backward items */
+        for (int pass = 1; pass >= 0; --pass)
+            for (int j = 1; j <= J; ++j)
+                if (is_fwd[j] == pass)
+                    for (int m = 1; m <= M; ++m) {
+                        pe_item it = {m, j};
+                        ULIST(res[j])[Ulen[res[j]]++] = it;
+                    }
+    } else {
+        /* ordering phase of Alg. 1: sweeps over the block list, one microbatch per non-empty
+         * queue (looked up at the start of the sweep) moves on by one block */
+        for (int m = 1; m <= M; ++m) Q[1 * M + tail[1]++] = m;
+        for (;;) {
+            int any = 0;
+            for (int j = 1; j <= J; ++j) { nonempty[j] = head[j] < tail[j]; any |= nonempty[j]; }
+            if (!any) break;
+            for (int j = 1; j <= J; ++j)
+                if (nonempty[j]) {
+                    int32_t m = Q[j * M + head[j]++];
+                    if (j < J) Q[(j + 1) * M + tail[j + 1]++] = m;
+                    pe_item it = {m, j};
+                    ULIST(res[j])[Ulen[res[j]]++] = it;
+                }
+        }
+    }
+    /* scheduling phase */
+    for (size_t i = 0; i < (size_t)(J + 1) * (M + 1); ++i) done[i] = -1;
+    for (;;) {
+        int progress = 0, remaining = 0;
+        for (int r = 0; r < nres; ++r) {
+            while (next[r] < Ulen[r]) {
+                pe_item it = ULIST(r)[next[r]];
+                int64_t ready = 0;
+                if (it.j > 1) {
+                    ready = done[(size_t)(it.j - 1) * (M + 1) + it.m];
+                    if (ready < 0) break;
+                }
+                int64_t fin = max2(idle_at[r], ready) + dur[it.j];
+                done[(size_t)it.j * (M + 1) + it.m] = fin;
+                idle_at[r] = fin;
+                next[r]++;
+                progress = 1;
+            }
+            remaining |= next[r] < Ulen[r];
+        }
+        if (!remaining) break;
+        if (!progress) goto out;
+    }
+#undef ULIST
+    T = 0;
+    for (int m = 1; m <= M; ++m) T = max2(T, done[(size_t)J * (M + 1) + m]);
+out:
+    free(res); free(is_fwd); free(dur); free(done); free(idle_at); free(next); free(Ulen); free(Uall);
+    free(Q); free(head); free(tail); free(nonempty);
+    return T;
+}
+
+int ppo_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
+                                  const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                                  const int64_t *XB, const int32_t *orderings,
+                                  const int32_t *bounds, int64_t *T_out) {
+    int rc = check_common(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PPO_ERR_INVALID_ARG;
+    if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE)
+        return PPO_ERR_INVALID_ARG;
+    int32_t *own = NULL;
+    if (!orderings) {
+        own = all_orderings(D, N);
+        if (!own) return PPO_ERR_NOMEM;
+        orderings = own;
+    }
+    int fault = 0, nomem = 0;
+    int nt = ppo_get_num_threads();
+    (void)nt;
+#pragma omp parallel for schedule(static) num_threads(nt) reduction(| : fault, nomem)
+    for (int64_t c = 0; c < N; ++c) {
+        const int32_t *o = orderings + c * S, *e = bounds + c * S;
+        int64_t F[PPO_MAX_STAGES], B[PPO_MAX_STAGES], cf[PPO_MAX_STAGES], cb[PPO_MAX_STAGES];
+        T_out[c] = INF;
+        if (!ordering_ok(o, S, D)) { fault |= PPO_FAULT_ORDERING; continue; }
+        if (!bounds_ok(e, S, L)) { fault |= PPO_FAULT_BOUNDS; continue; }
+        int f = plan_durations(L, D, S, M, PF, PB, XF, XB, o, e, F, B, cf, cb);
+        if (f) { fault |= f; continue; }
+        int64_t T = ppo_variant_makespan(variant, S, M, F, B, cf, cb);
+        if (T < 0) { nomem = 1; continue; }
+        T_out[c] = T;
+    }
+    free(own);
+    if (nomem) return PPO_ERR_NOMEM;
+    return fault;
+}

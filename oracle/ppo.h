@@ -157,6 +157,27 @@ int64_t ppo_pe_makespan(int S, int M, const int64_t *F, const int64_t *B,
                         const int64_t *cf, const int64_t *cb,
                         int64_t *start_out, int64_t *finish_out);
 
+/* Schedule variants, for comparison with the PE scheduler.  Same timing rule as
+ * the scheduling phase of Alg. 1 (an item starts when its microbatch has left
+ * the preceding block and its resource is idle; resources follow their lists):
+ *   PPO_SCHED_PE      Alg. 1 itself (equals ppo_pe_makespan)
+ *   PPO_SCHED_DUPLEX  Alg. 1 with separate channels for the forward and the
+ *                     backward transfers of a stage pair
+ *   PPO_SCHED_GPIPE   all forward passes before any backward pass on every
+ *                     stage and channel (the GPipe schedule as Sec. II describes
+ *                     it), microbatches in order; last stage's F and B separate
+ * F, B per stage; cf, cb per channel with entry 0 unused. */
+#define PPO_SCHED_PE 0
+#define PPO_SCHED_DUPLEX 1
+#define PPO_SCHED_GPIPE 2
+int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F,
+                             const int64_t *B, const int64_t *cf, const int64_t *cb);
+int ppo_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
+                                  const int64_t *PF, const int64_t *PB,
+                                  const int64_t *XF, const int64_t *XB,
+                                  const int32_t *orderings, const int32_t *bounds,
+                                  int64_t *T_out);
+
 /* Recursive device ordering (Alg. 2, Sec. IV-B): find a minimum cut of the
  * GPU graph, order the two sides recursively, first side first.  The graph
  * is undirected with weight bw[u][v] + bw[v][u] on edge {u, v} (twice the

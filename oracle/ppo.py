@@ -55,6 +55,7 @@ def lib():
             build()
         _lib = ctypes.CDLL(_SO)
         _lib.ppo_pe_makespan.restype = ctypes.c_int64
+        _lib.ppo_variant_makespan.restype = ctypes.c_int64
         _lib.ppo_get_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -210,6 +211,29 @@ def pe_makespan(F, B, cf, cb, M, want_times=False):
     fi = np.full((J, M), -1, np.int64) if want_times else None
     T = int(lib().ppo_pe_makespan(S, M, _p(F), _p(B), _p(cf), _p(cb), _p(st), _p(fi)))
     return (T, st, fi) if want_times else T
+
+
+SCHED_PE, SCHED_DUPLEX, SCHED_GPIPE = 0, 1, 2
+
+
+def variant_makespan(variant, F, B, cf, cb, M):
+    """Makespan of one pipeline under a schedule variant, from its durations."""
+    F, B = _i64(F), _i64(B)
+    S = F.shape[0]
+    cf = _i64(cf) if cf is not None else np.zeros(S, np.int64)
+    cb = _i64(cb) if cb is not None else np.zeros(S, np.int64)
+    return int(lib().ppo_variant_makespan(int(variant), S, M, _p(F), _p(B), _p(cf), _p(cb)))
+
+
+def schedule_makespan_variant(variant, L, D, S, N, M, PF, PB, XF, XB, orderings, bounds):
+    """-> (status, T[N])"""
+    orderings = _i32(orderings)
+    bounds = _i32(bounds)
+    T = np.empty(N, np.int64)
+    rc = lib().ppo_schedule_makespan_variant(int(variant), L, D, S, ctypes.c_int64(N), M, _p(_i64(PF)),
+                                             _p(_i64(PB)), _p(_i64(XF)), _p(_i64(XB)), _p(orderings),
+                                             _p(bounds), _p(T))
+    return rc, T
 
 
 def rdo_order(bw):

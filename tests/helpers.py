@@ -126,3 +126,79 @@ def event_sim(F, B, cf, cb, M):
     assert len(done) == J * M, "simulation stalled"
     T = max(done[(J, m)] for m in range(1, M + 1))
     return T, start
+
+
+def list_sim(blocks, M):
+    """Heap-driven simulation of serial resources that follow explicit service lists.
+    blocks: list of (resource id, duration, key) in the order a microbatch passes them, where
+    key(m) sorts the item (block, microbatch m) within its resource's list.
+    Returns (T, finish) with finish[(j, m)] for 0-based block j and 1-based m."""
+    J = len(blocks)
+    order = {}
+    for j, (r, d, key) in enumerate(blocks):
+        for m in range(1, M + 1):
+            order.setdefault(r, []).append((key(m), j, m))
+    for r in order:
+        order[r].sort()
+    pos = {r: 0 for r in order}
+    busy = {r: False for r in order}
+    done = {}
+    now = 0
+    events = []
+
+    def try_start(r):
+        if busy[r] or pos[r] >= len(order[r]):
+            return False
+        _, j, m = order[r][pos[r]]
+        if j > 0 and (j - 1, m) not in done:
+            return False
+        busy[r] = True
+        heapq.heappush(events, (now + blocks[j][1], r, j, m))
+        pos[r] += 1
+        return True
+
+    while True:
+        moved = True
+        while moved:
+            moved = False
+            while events and events[0][0] == now:
+                _, r, j, m = heapq.heappop(events)
+                done[(j, m)] = now
+                busy[r] = False
+                moved = True
+            for r in order:
+                if try_start(r):
+                    moved = True
+        if not events:
+            break
+        now = events[0][0]
+    assert len(done) == J * M, "simulation stalled"
+    return max(done[(J - 1, m)] for m in range(1, M + 1)), done
+
+
+def variant_blocks(variant, F, B, cf, cb):
+    """Block list of a schedule variant for list_sim.  'pe' and 'duplex': blocks of the PE
+    scheduler (last stage merged), served by (sweep, block) with sweep = m + j; 'duplex' gives
+    the backward transfers their own channels.  'gpipe': last stage's F and B separate, every
+    resource serves all forward items, then all backward items, microbatches in order."""
+    S = len(F)
+    blocks = []
+    merged = variant != "gpipe"
+
+    def add(res, dur, fwd):
+        j = len(blocks)
+        if variant == "gpipe":
+            blocks.append((res, dur, (lambda m, fwd=fwd, j=j: (0 if fwd else 1, j, m))))
+        else:
+            blocks.append((res, dur, (lambda m, j=j: (m + j, j))))
+
+    for n in range(S):
+        if n:
+            add(("c", n), cf[n], True)
+        add(("s", n), F[n] + B[n] if (n == S - 1 and merged) else F[n], True)
+    for n in range(S - 1, -1, -1):
+        if not (n == S - 1 and merged):
+            add(("s", n), B[n], False)
+        if n:
+            add(("cb", n) if variant == "duplex" else ("c", n), cb[n], False)
+    return blocks

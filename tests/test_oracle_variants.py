@@ -1,0 +1,92 @@
+"""Pins for the oracle's schedule variants (duplex channels, GPipe order): hand-worked
+schedules, closed forms and an independent simulation with explicit service lists."""
+import numpy as np
+import pytest
+
+from conftest import read_golden
+from helpers import list_sim, variant_blocks
+
+NAMES = {0: "pe", 1: "duplex", 2: "gpipe"}
+
+
+def random_pipeline(seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    S = int(rng.integers(1, 6))
+    M = int(rng.integers(1, 9))
+    z = rng.random() < 0.3
+    F = rng.integers(0 if z else 1, 20, size=S).tolist()
+    B = rng.integers(0 if z else 1, 30, size=S).tolist()
+    cf = [0] + rng.integers(0, 25, size=S - 1).tolist()
+    cb = [0] + rng.integers(0, 25, size=S - 1).tolist()
+    return S, M, F, B, cf, cb
+
+
+def test_handworked(ppo):
+    g = read_golden("variants_handworked.txt")
+    F, B, c, M = g["A_F"][0], g["A_B"][0], g["A_c"][0], g["A_M"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_PE, F, B, c, c, M) == g["A_T_pe"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_DUPLEX, F, B, c, c, M) == g["A_T_duplex"][0][0]
+    F, B, c, M = g["B_F"][0], g["B_B"][0], g["B_c"][0], g["B_M"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_GPIPE, F, B, c, c, M) == g["B_T_gpipe"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_GPIPE, [3] * 3, [5] * 3, [0] * 3, [0] * 3, 4) == g["C_T_gpipe"][0][0]
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_pe_variant_is_the_pe_scheduler(ppo, seed):
+    S, M, F, B, cf, cb = random_pipeline(seed)
+    assert ppo.variant_makespan(ppo.SCHED_PE, F, B, cf, cb, M) == ppo.pe_makespan(F, B, cf, cb, M)
+
+
+@pytest.mark.parametrize("seed", range(100, 140))
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_against_the_list_simulation(ppo, seed, variant):
+    S, M, F, B, cf, cb = random_pipeline(seed)
+    T, _ = list_sim(variant_blocks(NAMES[variant], F, B, cf, cb), M)
+    assert ppo.variant_makespan(variant, F, B, cf, cb, M) == T
+
+
+@pytest.mark.parametrize("S,M", [(1, 1), (1, 5), (2, 3), (4, 6), (6, 2)])
+def test_gpipe_closed_form_without_transfers(ppo, S, M):
+    # uniform stages, free links: forward wave (M + S - 1) F, then backward wave (M + S - 1) B
+    assert ppo.variant_makespan(ppo.SCHED_GPIPE, [7] * S, [11] * S, [0] * S, [0] * S, M) == (M + S - 1) * 18
+
+
+def test_bounds(ppo):
+    # every variant needs at least M times the busiest resource and one microbatch's full path
+    for seed in range(200, 230):
+        S, M, F, B, cf, cb = random_pipeline(seed)
+        path = sum(F) + sum(B) + sum(cf) + sum(cb)
+        for variant in (0, 1, 2):
+            T = ppo.variant_makespan(variant, F, B, cf, cb, M)
+            busiest = max([f + b for f, b in zip(F, B)] +
+                          ([max(x, y) if variant == 1 else x + y for x, y in zip(cf[1:], cb[1:])] or [0]))
+            assert T >= max(path, M * busiest)
+
+
+def test_one_stage_all_variants_agree(ppo):
+    for M in (1, 4):
+        assert {ppo.variant_makespan(v, [5], [9], [0], [0], M) for v in (0, 1, 2)} == {14 * M}
+
+
+def test_batch_function(ppo):
+    from paper_2204_10562_amd import workloads
+    w = workloads.tiny()
+    rc, PF, PB, XF, XB = ppo.prefix_costs(w.fwd, w.bwd, w.actf, w.actb, w.bw)
+    rc, C, bounds = ppo.partition_dp(w.L, 4, 4, 24, PF, PB, XF, XB, None)
+    rc, T0 = ppo.schedule_makespan(w.L, 4, 4, 24, 8, PF, PB, XF, XB, None, bounds)
+    rc, T = ppo.schedule_makespan_variant(ppo.SCHED_PE, w.L, 4, 4, 24, 8, PF, PB, XF, XB, None, bounds)
+    assert rc == 0
+    np.testing.assert_array_equal(T, T0)
+    orders = workloads.all_orderings(4)
+    for variant in (1, 2):
+        rc, T = ppo.schedule_makespan_variant(variant, w.L, 4, 4, 24, 8, PF, PB, XF, XB, None, bounds)
+        assert rc == 0
+        for c in (0, 7, 23):
+            e = [0] + bounds[c].tolist()
+            o = orders[c]
+            F = [int(PF[e[i + 1]] - PF[e[i]]) for i in range(4)]
+            B = [int(PB[e[i + 1]] - PB[e[i]]) for i in range(4)]
+            cf = [0] + [int(XF[(o[n - 1] * 4 + o[n]) * w.L + e[n] - 1]) for n in range(1, 4)]
+            cb = [0] + [int(XB[(o[n - 1] * 4 + o[n]) * w.L + e[n] - 1]) for n in range(1, 4)]
+            assert T[c] == list_sim(variant_blocks(NAMES[variant], F, B, cf, cb), 8)[0]
+    assert ppo.schedule_makespan_variant(7, w.L, 4, 4, 24, 8, PF, PB, XF, XB, None, bounds)[0] == ppo.ERR_INVALID_ARG
