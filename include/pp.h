@@ -153,6 +153,30 @@ int pp_schedule_makespan(int L, int D, int S, int64_t N, int M,
                          int64_t *T_out, int32_t *status, void *stream);
 
 /*
+ * pp_schedule_makespan under a comparison schedule.  The timing rule is that of
+ * Alg. 1's scheduling phase in every case (an item starts when its microbatch
+ * has left the preceding block and its resource is idle; resources follow their
+ * service lists); what changes is the resources or the lists:
+ *   PP_SCHED_PE      Alg. 1 itself (same as pp_schedule_makespan)
+ *   PP_SCHED_DUPLEX  Alg. 1's blocks and ordering phase, but the forward and the
+ *                    backward transfers of a stage pair use separate channels
+ *   PP_SCHED_GPIPE   every stage and channel serves all forward items before
+ *                    any backward item, microbatches in order (the schedule
+ *                    Sec. II attributes to GPipe: all FP before any BP); the
+ *                    last stage's forward and backward are separate items
+ * Same arguments, limits and faults as pp_schedule_makespan; an unknown variant
+ * returns PP_ERR_INVALID_ARG.
+ */
+#define PP_SCHED_PE 0
+#define PP_SCHED_DUPLEX 1
+#define PP_SCHED_GPIPE 2
+int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
+                                 const int64_t *PF, const int64_t *PB,
+                                 const int64_t *XF, const int64_t *XB,
+                                 const int32_t *orderings, const int32_t *bounds,
+                                 int64_t *T_out, int32_t *status, void *stream);
+
+/*
  * The whole path: partition DP per candidate, makespan of each plan, and the
  * keep-the-minimum of the SPP listing (Alg. 3: replace only on strictly
  * smaller T while scanning candidates in index order, so the lowest index

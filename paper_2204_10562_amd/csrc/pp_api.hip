@@ -113,6 +113,22 @@ extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const
                               status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
+extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
+                                            const int64_t *PF, const int64_t *PB, const int64_t *XF,
+                                            const int64_t *XB, const int32_t *orderings,
+                                            const int32_t *bounds, int64_t *T_out, int32_t *status,
+                                            void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
+    if (variant == PP_SCHED_PE)
+        return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
+                                  status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
+    if (variant != PP_SCHED_DUPLEX && variant != PP_SCHED_GPIPE) return PP_ERR_INVALID_ARG;
+    return pp_launch_makespan_variant(variant, L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out,
+                                      status, (hipStream_t)stream);
+}
+
 extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const int32_t *M_list,
                                   const int64_t *PF, const int64_t *PB, const int64_t *XF,
                                   const int64_t *XB, const int32_t *orderings, pp_result *out,

@@ -131,6 +131,11 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
                            const int64_t *bw, const int32_t *orderings, const int32_t *bounds,
                            const int32_t *reps, const int64_t *W, int64_t *T_out, int32_t *status,
                            void *part, unsigned *ticket, pp_rep_result *out, hipStream_t st);
+// Makespan of given plans under a comparison schedule (PP_SCHED_DUPLEX, PP_SCHED_GPIPE).
+int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                               const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                               const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
+                               int32_t *status, hipStream_t st);
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
                      unsigned *ticket, pp_result *out, hipStream_t st);

@@ -44,6 +44,7 @@ struct mk_args {
     // search > 0 (arg-min only): the N entries are (candidate, stage count) pairs, entry
     // i = c*search + xi-1; the record of the winner is decoded accordingly
     int search;
+    int variant;  // k_makespan_variant only: PP_SCHED_*
     int32_t *status;
     // replicated stages (k_rep_makespan and the record of its arg-min; NULL otherwise): replica
     // counts laid out like bounds, prefix sums of the parameter sizes, activation sizes, the
@@ -76,9 +77,10 @@ __device__ __forceinline__ tc_pair wave_tc_min(tc_pair v) {
 // (called as put(block j (1-based), duration)).  Returns fault bits; on a fault or for a
 // dead lane all durations are 0.  `worst` gets the largest per-resource time f + b.
 // ST > 0 fixes the number of stages at compile time (block numbers become constants).
-template <int ST, typename Put>
+// `last(F, B)` receives the last stage's forward and backward times separately.
+template <int ST, typename Put, typename Last>
 __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, bool live,
-                                                long long &worst, Put put) {
+                                                long long &worst, Put put, Last last) {
     const int S = ST ? ST : a.S, L = a.L, D = a.D, R = 2 * S - 1;
     int fault = 0;
     if (live) {
@@ -123,6 +125,7 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
         const int r = 2 * n + 1;  // stage n is resource 2n+1, channel n is resource 2n
         if (n == S - 1) {
             put(R, F + Bk);  // merged forward+backward block of the last stage
+            last(F, Bk);
         } else {
             put(r, F);
             put(2 * R - r, Bk);
@@ -133,6 +136,12 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
         }
     }
     return fault;
+}
+
+template <int ST, typename Put>
+__device__ __forceinline__ int gather_durations(const mk_args &a, long long c, bool live,
+                                                long long &worst, Put put) {
+    return gather_durations<ST>(a, c, live, worst, put, [](long long, long long) {});
 }
 
 // The schedule is no longer than (M + 4S - 4) * C (Lemma 1): fault if that bound reaches 2^62.
@@ -529,6 +538,7 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
 static void plain_layout(mk_args &a, int S) {
     a.ord_stride = S; a.bnd_stride = S; a.bnd_off = 0; a.t_stride = 1; a.t_off = 0; a.search = 0;
     a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
+    a.variant = 0;
 }
 
 // Lanes per workgroup of the LDS kernel: as many as keep 2J rows of int64 within 64 KiB.
@@ -709,5 +719,105 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
     long long waves = (m.N + 63) / 64;
     if (waves > 1024) waves = 1024;
     hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves, 1), dim3(64), 0, st, m);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
+// ---------------------------------------------------------------- schedule variants
+
+// Comparison schedules with the timing rule of Alg. 1's scheduling phase, any S, one lane per
+// candidate, the lane's state in its own LDS column (rows [row][lane]).
+//   PP_SCHED_DUPLEX: the sweeps of the PE scheduler, but the forward and backward transfers of
+//     a stage pair have a channel each, so a channel block waits only for its own previous item.
+//   PP_SCHED_GPIPE: every stage and channel serves all forward items before any backward item
+//     (Sec. II: "all FP before starting any BP"), microbatches in order.  With that order the
+//     resources form a flow shop: the forward wave is busy[r] = max(busy[r], busy of the same
+//     microbatch on r-1) + forward time, resources 1..R, microbatch by microbatch; the backward
+//     wave the same in the other direction, each resource continuing from the end of its last
+//     forward item.  The last stage's forward and backward passes are separate items here.
+__global__ __launch_bounds__(64) void k_makespan_variant(mk_args a) {
+    extern __shared__ long long sm[];
+    const int lane = threadIdx.x, W = blockDim.x;
+    const int S = a.S, M = a.Ms[0];
+    const int R = 2 * S - 1, J = 2 * R - 1;
+    long long *dur = sm + lane;                    // rows 0..J-1: duration of block j = row + 1
+    long long *fin = sm + (size_t)J * W + lane;    // rows J..2J-1: finish times / busy-until times
+    const long long c = (long long)blockIdx.x * W + lane;
+    const bool live = c < a.N;
+    long long worst, lastF = 0, lastB = 0;
+    const int fault0 = gather_durations<0>(a, c, live, worst,
+                                           [&](int j, long long d) { dur[(size_t)(j - 1) * W] = d; },
+                                           [&](long long F, long long B) { lastF = F; lastB = B; });
+    const int fault = (live && !fault0) ? overflow_fault(worst, M, S) : fault0;
+    for (int j = 1; j <= J; ++j) fin[(size_t)(j - 1) * W] = 0;
+    long long T;
+    if (a.variant == PP_SCHED_GPIPE) {
+        // busy[r] lives in fin row r-1; forward time of resource r = dur of block r (the last
+        // stage's forward alone), backward time = dur of block 2R - r (the last stage's backward)
+        for (int m = 0; m < M; ++m) {
+            long long prev = 0;
+            for (int r = 1; r <= R; ++r) {
+                const long long d = r == R ? lastF : dur[(size_t)(r - 1) * W];
+                long long b = fin[(size_t)(r - 1) * W];
+                b = (b > prev ? b : prev) + d;
+                fin[(size_t)(r - 1) * W] = b;
+                prev = b;
+            }
+        }
+        for (int m = 0; m < M; ++m) {
+            long long prev = 0;
+            for (int r = R; r >= 1; --r) {
+                const long long d = r == R ? lastB : dur[(size_t)(2 * R - r - 1) * W];
+                long long b = fin[(size_t)(r - 1) * W];
+                b = (b > prev ? b : prev) + d;
+                fin[(size_t)(r - 1) * W] = b;
+                prev = b;
+            }
+        }
+        T = fin[0];
+    } else {
+        // the PE sweeps; even resources are channels: no partner block on the same resource
+        const int sweeps = M + 2 * R - 2;
+        for (int t = 1; t <= sweeps; ++t) {
+            const int jlo = max(1, t - M + 1), jhi = min(J, t);
+            const long long finR_prev = fin[(size_t)(R - 1) * W];
+            for (int j = min(jhi, R); j >= jlo; --j) {
+                long long idle = fin[(size_t)(j - 1) * W];
+                if (j & 1) idle = max(idle, fin[(size_t)((2 * R - j) - 1) * W]);
+                long long ready = j > 1 ? fin[(size_t)((j - 1) - 1) * W] : 0;
+                fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
+            }
+            for (int j = jhi; j >= max(jlo, R + 1); --j) {
+                long long idle = fin[(size_t)(j - 1) * W];
+                if (j & 1) idle = max(idle, fin[(size_t)((2 * R - j) - 1) * W]);
+                long long ready = j == R + 1 ? finR_prev : fin[(size_t)((j - 1) - 1) * W];
+                fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
+            }
+        }
+        T = fin[(size_t)(J - 1) * W];
+    }
+    if (live) {
+        if (fault) pp_raise(a.status, fault);
+        a.T_out[c] = fault ? PP_INF64 : T;
+    }
+}
+
+int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                               const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                               const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
+                               int32_t *status, hipStream_t st) {
+    mk_args a;
+    a.L = L; a.D = D; a.S = S; a.N = N; a.nM = 1;
+    for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = M;
+    a.PF = (const long long *)PF; a.PB = (const long long *)PB;
+    a.XF = (const long long *)XF; a.XB = (const long long *)XB;
+    a.orderings = orderings; a.bounds = bounds;
+    plain_layout(a, S);
+    a.variant = variant;
+    a.T_out = (long long *)T_out; a.status = status;
+    a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL;
+    const int W = lds_lanes(S);
+    const size_t lds = (size_t)2 * (4 * S - 3) * W * 8;
+    unsigned grid = (unsigned)((N + W - 1) / W);
+    hipLaunchKernelGGL(k_makespan_variant, dim3(grid), dim3(W), lds, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }

@@ -144,3 +144,13 @@ class GpuProblem:
             return self.take_status(), res
         return (self.take_status(), res, T.cpu().numpy().reshape(N, D), W.cpu().numpy().reshape(N, D),
                 b.cpu().numpy().reshape(N, tri), r.cpu().numpy().reshape(N, tri))
+
+    def makespan_variant(self, variant, M, bounds, orderings="default", N=None, S=None):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        b = torch.from_numpy(np.ascontiguousarray(bounds, dtype=np.int32).reshape(-1)).to(self.dev)
+        T = torch.empty(N, dtype=torch.int64, device=self.dev)
+        pp.pp_schedule_makespan_variant(variant, w.L, w.D, S, N, M, self.PF, self.PB, self.XF, self.XB, o, b,
+                                        T, self.status)
+        return self.take_status(), T.cpu().numpy()
