@@ -10,8 +10,10 @@
 // split index and min returns the smallest time with the lowest split), but the difference
 // term ((P[l] - P[k]) << K) | k is too large to keep in registers for the whole plane, so it
 // is formed on the fly: subtract, max and half a three-operand min per pair.  Only super-tiles
-// on or below the diagonal are visited; the last super-row has NTL <= 16 cell tiles, fixed at
-// compile time, so a model of 300 layers does not pay for 384.
+// on or below the diagonal are visited, from the diagonal leftwards, and the scan of a super-row
+// stops as soon as the difference term alone rules out everything further left; the last
+// super-row has NTL <= 16 cell tiles, fixed at compile time, so a model of 300 layers does not
+// pay for 384.
 //
 // Per wave in LDS: two rows of keys (the row being read, rewritten in place as g, and the row
 // being produced).  Split indices go to a per-wave table in global memory while the next row's
@@ -77,11 +79,15 @@ __device__ __forceinline__ void big_tile(int (&acc)[16], const int (&Pl)[16], co
     }
 }
 
-// One super-row of NTI cell tiles: all super-tiles J <= I, then the reduction over the 8 lanes
-// that share a cell, then the cells go to the next row.
+// One super-row of NTI cell tiles: the diagonal super-tile, then the super-tiles to its left
+// from the nearest on, then the reduction over the 8 lanes that share a cell, then the cells go
+// to the next row.  P[l] - P[k] grows as k falls, so once the smallest difference of a
+// super-tile (first cell of the row against the super-tile's last split) exceeds the largest
+// value any lane still holds, neither that super-tile nor any further left can lower or tie a
+// cell: the scan stops there.  Returns the first super-tile visited (for the work counter).
 template <int NTI>
-__device__ __forceinline__ void big_super_row(int I, const int *G, const int *sPk, int *nxt,
-                                              int la, int lb) {
+__device__ __forceinline__ int big_super_row(int I, const int *G, const int *sPk, int *nxt,
+                                             int la, int lb, int K) {
     int acc[16], Pl[16];
 #pragma unroll
     for (int i = 0; i < NTI; ++i) {
@@ -89,8 +95,22 @@ __device__ __forceinline__ void big_super_row(int I, const int *G, const int *sP
         Pl[i] = sPk[l] + l;  // P[l] << K
         acc[i] = PP_INF32;
     }
-    for (int J = 0; J < I; ++J) big_tile<NTI, 16, false>(acc, Pl, G + 128 * J, sPk + 128 * J, la, lb);
     big_tile<NTI, NTI, true>(acc, Pl, G + 128 * I, sPk + 128 * I, la, lb);
+    int J = I - 1;
+    for (; J >= 0; --J) {
+        if (J < I - 1) {
+            // largest value held by any lane for any cell of this super-row (as a time)
+            int ub = acc[0];
+#pragma unroll
+            for (int i = 1; i < NTI; ++i) ub = bmax(ub, acc[i]);
+            for (int off = 32; off; off >>= 1) ub = bmax(ub, __shfl_xor(ub, off));
+            const int first_l = 128 * I + 1, last_k = 128 * J + 127;
+            // (P[l] << K) - (P[k] << K) compared with the time part of the bound
+            const int dmin = (sPk[first_l] + first_l) - (sPk[last_k] + last_k);
+            if ((dmin >> K) > (ub >> K)) break;
+        }
+        big_tile<NTI, 16, false>(acc, Pl, G + 128 * J, sPk + 128 * J, la, lb);
+    }
 #pragma unroll
     for (int i = 0; i < NTI; ++i) {
         acc[i] = big_min_over_b(acc[i]);
@@ -100,6 +120,15 @@ __device__ __forceinline__ void big_super_row(int I, const int *G, const int *sP
 #pragma unroll
         for (int i = 0; i < NTI; ++i) nxt[128 * I + 8 * i + la + 1] = acc[i];
     }
+    return J + 1;
+}
+
+// (cell, split) pairs with cell in [a, b], split in [klo, cell - 1]
+__device__ __forceinline__ unsigned long long big_pairs(int a, int b, int klo) {
+    if (a <= klo) a = klo + 1;
+    if (b < a) return 0;
+    const unsigned long long lo = (unsigned long long)(a - klo), hi = (unsigned long long)(b - klo);
+    return (lo + hi) * (hi - lo + 1) / 2;
 }
 
 template <int NTL>
@@ -175,14 +204,18 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
             }
             big_lds_sync();
             if (n < S - 1) {
-                for (int I = 0; I + 1 < NI; ++I) big_super_row<16>(I, cur, sPk, nxt, la, lb);
-                big_super_row<NTL>(NI - 1, cur, sPk, nxt, la, lb);
+                for (int I = 0; I < NI; ++I) {
+                    const int J0 = I + 1 < NI ? big_super_row<16>(I, cur, sPk, nxt, la, lb, K)
+                                              : big_super_row<NTL>(I, cur, sPk, nxt, la, lb, K);
+                    const int a0 = 128 * I + 1 > n + 1 ? 128 * I + 1 : n + 1;
+                    const int b0 = 128 * I + 128 < L ? 128 * I + 128 : L;
+                    pairs += big_pairs(a0, b0, 128 * J0 > n ? 128 * J0 : n);
+                }
                 if (lane == 0) nxt[0] = PP_INF32;
                 big_lds_sync();
                 int *t = cur; cur = nxt; nxt = t;
                 const int top_n = cur[L];
                 if (lane == n) v_tops = top_n;
-                pairs += (unsigned long long)(L - n) * (L - n + 1) / 2;
             } else {
                 // only W[S-1][L] is needed of the last row
                 const int PL = sPk[L] + L;
