@@ -4,8 +4,8 @@
 // of C); transfer time over a link is size / bandwidth (Sec. III-B, c^f and c^b with one GPU
 // per stage), rounded up to whole microseconds per direction.
 //
-// Both kernels are bandwidth-trivial: 4L int64 in, 2(L+1) + 2 D^2 L int64 out.  The table
-// kernel gives every thread one (link, boundary) entry, so a wave reads consecutive
+// Both parts are bandwidth-trivial: 4L int64 in, 2(L+1) + 2 D^2 L int64 out.  The table
+// part gives every thread one (link, boundary) entry, so a wave reads consecutive
 // activation sizes and writes 64 consecutive int64 results (512-byte coalesced segments).
 #include "pp_common.h"
 
@@ -14,7 +14,7 @@
 // One workgroup scans both arrays.  Each thread owns a contiguous chunk; chunk totals are
 // scanned through LDS; a value that reaches 2^62 (also by wrap-around: each addend is below
 // 2^62, so a running sum cannot skip the interval [2^62, 2^64)) raises the overflow fault.
-__global__ __launch_bounds__(SCAN_THREADS) void k_prefix_scan(
+__device__ __forceinline__ void prefix_scan(
     int L, const long long *__restrict__ fwd, const long long *__restrict__ bwd,
     const long long *__restrict__ actf, const long long *__restrict__ actb,
     long long *__restrict__ PF, long long *__restrict__ PB, int32_t *status) {
@@ -65,12 +65,12 @@ __device__ __forceinline__ long long ceil_div_u(long long a, long long b) {
     return (long long)(q + ((unsigned long long)a - q * (unsigned long long)b != 0));
 }
 
-// one thread per table entry i = link * L + k, link = u*D+v
-__global__ __launch_bounds__(256) void k_transfer_tables(
-    int L, int D, const long long *__restrict__ actf, const long long *__restrict__ actb,
+// one thread per table entry i = link * L + k, link = u*D+v; `block` counts the table's blocks
+__device__ __forceinline__ void transfer_tables(
+    size_t block, int L, int D, const long long *__restrict__ actf, const long long *__restrict__ actb,
     const long long *__restrict__ bw, long long *__restrict__ XF, long long *__restrict__ XB,
     int32_t *status) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t i = block * blockDim.x + threadIdx.x;
     if (i >= (size_t)D * D * L) return;
     const int link = (int)(i / (size_t)L);
     const int k = (int)(i - (size_t)link * L);
@@ -93,6 +93,16 @@ __global__ __launch_bounds__(256) void k_transfer_tables(
     if (fault) pp_raise(status, fault);
 }
 
+// Workgroup 0 scans; the others fill the tables, which do not depend on the scan: one launch.
+__global__ __launch_bounds__(SCAN_THREADS) void k_prefix_costs(
+    int L, int D, const long long *__restrict__ fwd, const long long *__restrict__ bwd,
+    const long long *__restrict__ actf, const long long *__restrict__ actb,
+    const long long *__restrict__ bw, long long *__restrict__ PF, long long *__restrict__ PB,
+    long long *__restrict__ XF, long long *__restrict__ XB, int32_t *status) {
+    if (blockIdx.x == 0) prefix_scan(L, fwd, bwd, actf, actb, PF, PB, status);
+    else transfer_tables((size_t)blockIdx.x - 1, L, D, actf, actb, bw, XF, XB, status);
+}
+
 extern "C" int pp_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
                                const int64_t *act_fwd_bytes, const int64_t *act_bwd_bytes,
                                const int64_t *bw, int64_t *PF, int64_t *PB, int64_t *XF,
@@ -101,15 +111,12 @@ extern "C" int pp_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_
     if (!fwd_us || !bwd_us || !act_fwd_bytes || !bw || !PF || !PB || !XF || !XB)
         return PP_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_prefix_scan, dim3(1), dim3(SCAN_THREADS), 0, st, L,
-                       (const long long *)fwd_us, (const long long *)bwd_us,
-                       (const long long *)act_fwd_bytes, (const long long *)act_bwd_bytes,
-                       (long long *)PF, (long long *)PB, status);
-    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
     const size_t total = (size_t)D * D * L;
-    hipLaunchKernelGGL(k_transfer_tables, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, L, D,
-                       (const long long *)act_fwd_bytes, (const long long *)act_bwd_bytes,
-                       (const long long *)bw, (long long *)XF, (long long *)XB, status);
+    hipLaunchKernelGGL(k_prefix_costs, dim3((unsigned)(1 + (total + SCAN_THREADS - 1) / SCAN_THREADS)),
+                       dim3(SCAN_THREADS), 0, st, L, D, (const long long *)fwd_us,
+                       (const long long *)bwd_us, (const long long *)act_fwd_bytes,
+                       (const long long *)act_bwd_bytes, (const long long *)bw, (long long *)PF,
+                       (long long *)PB, (long long *)XF, (long long *)XB, status);
     if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
     return PP_OK;
 }
