@@ -25,8 +25,7 @@ static inline int pp_index_bits(int L) {
 #define PP_PACK_BLOCKS 64
 struct pp_ws_header {
     unsigned long long pmax[PP_PACK_BLOCKS];  // byte 0
-    unsigned ticket[65];  // byte 512: arrival counters of the arg-min, zeroed by the pack kernel
-    unsigned pad0[63];
+    unsigned pad0[128];  // byte 512
     // byte 1024: (cell, split) pairs the partition DP actually evaluated in this call (rows
     // shared between candidates are counted once), spread over 64 counters to keep the
     // atomics apart; byte 1536: DP rows computed (the single-cell last row counts too).
@@ -105,15 +104,15 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
                  const int32_t *user_ord, int stages, int64_t *C_out, int32_t *bounds_out,
                  void *ws, const pp_ws_layout &lay, int32_t *status, hipStream_t st);
 // Makespan of every candidate's plan for each of the nM microbatch counts in Ms (host array).
-// With part/ticket/C/out non-NULL the launch also finds, per microbatch count, the candidate
-// with the smallest T (lowest index on ties) and fills out[q]; *ticket must be 0 when the
-// kernel starts (it is 0 again when it ends).  T_out ([nM][N]) may then be NULL; T_scratch
+// With part/C/out non-NULL the launch also finds, per microbatch count, the candidate
+// with the smallest T (lowest index on ties) and fills out[q] (one pair of int64 per wave of
+// 64 candidates and microbatch count in part).  T_out ([nM][N]) may then be NULL; T_scratch
 // ([N]) is needed for S > 16 in that case.
 int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
-                       unsigned *ticket, pp_result *out, hipStream_t st);
+                       pp_result *out, hipStream_t st);
 // Stage-count search: makespan of the plan with xi stages of every candidate for xi = 1..S
 // (bounds [N][S(S+1)/2] and C [N][S] as pp_launch_dp leaves them with stages == 1), written to
 // T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest
@@ -122,15 +121,15 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              unsigned *ticket, pp_result *out, hipStream_t st);
+                              pp_result *out, hipStream_t st);
 // Makespan (Eq. 2) of the plans with replicated stages of every (candidate, stage count) and
-// the keep-the-minimum over them; arrays laid out as pp_plan_replicated documents.  *ticket
-// (65 counters) must be 0 when the last kernel starts.
+// the keep-the-minimum over them; arrays laid out as pp_plan_replicated documents; part holds
+// 1024 pairs of int64.
 int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, const int64_t *PB,
                            const int64_t *PA, const int64_t *actf, const int64_t *actb,
                            const int64_t *bw, const int32_t *orderings, const int32_t *bounds,
                            const int32_t *reps, const int64_t *W, int64_t *T_out, int32_t *status,
-                           void *part, unsigned *ticket, pp_rep_result *out, hipStream_t st);
+                           void *part, pp_rep_result *out, hipStream_t st);
 // Makespan of given plans under a comparison schedule (PP_SCHED_DUPLEX, PP_SCHED_GPIPE).
 int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int M, const int64_t *PF,
                                const int64_t *PB, const int64_t *XF, const int64_t *XB,
@@ -138,7 +137,7 @@ int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int 
                                int32_t *status, hipStream_t st);
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
-                     unsigned *ticket, pp_result *out, hipStream_t st);
+                     pp_result *out, hipStream_t st);
 
 // Largest time in the tables (all lanes of a full wave must call; result is uniform).
 __device__ __forceinline__ unsigned long long pp_vmax(const pp_ws_header *hdr) {

@@ -20,8 +20,8 @@
 // (M+4S-4) * largest block of Lemma 1 fits, else 64-bit, decided per wave; several
 // microbatch counts run side by side in one launch); for larger S they live in the lane's
 // own LDS column.
-// When asked to, each wave also reduces (T, candidate) to its minimum and the last wave to
-// finish reduces the per-wave minima to the winner record.
+// When asked to, each wave also reduces (T, candidate) to its minimum, and a one-workgroup
+// kernel launched next reduces the per-wave minima to the winner record.
 #include "pp_common.h"
 
 struct tc_pair { long long T, c; };
@@ -53,8 +53,8 @@ struct mk_args {
     const long long *PA, *actf, *actb, *bw, *W;
     pp_rep_result *rout;   // [nM] winner records with replica counts (instead of out)
     // arg-min (all NULL when not wanted)
-    tc_pair *part;         // [nM][waves]
-    unsigned *ticket;      // 1 + 64 counters, all 0 when the kernel starts and again when it ends
+    tc_pair *part;         // [nM][waves]: every wave's minimum, reduced by k_pick
+    long long n_part;      // k_pick: partials per microbatch count
     const long long *C;
     pp_result *out;        // [nM]
 };
@@ -149,7 +149,11 @@ __device__ __forceinline__ int overflow_fault(long long worst, int M, int S) {
     return worst > (PP_CAP62 - 1) / ((long long)M + 4 * S - 4) ? PP_FAULT_OVERFLOW : 0;
 }
 
-// Writes T of microbatch count q, raises faults, and (if wanted) leaves the wave's minimum.
+// Writes T of microbatch count q, raises faults, and (if wanted) leaves the wave's minimum in
+// its slot of the partials; k_pick, launched next on the same stream, reduces the partials.
+// (Plain stores and a kernel boundary: earlier versions let the last wave to arrive do the
+// final reduction, but the returned atomics and arrival counters that needs cost more than
+// the schedule itself once a launch has thousands of waves.)
 __device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool live, int fault,
                                      long long T, long long wave_id, long long n_waves) {
     if (live) {
@@ -159,98 +163,80 @@ __device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool 
     if (!a.part) return;
     tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
     v = wave_tc_min(v);
-    if ((threadIdx.x & 63) == 0) {
-        // Device-scope exchanges instead of plain stores plus a release fence: a fence at
-        // device scope writes back the whole L2 of the wave's XCD, and thousands of waves doing
-        // that one after another cost more than the schedule itself.  An exchange is performed
-        // at the coherent point, and its return value tells when.
-        tc_pair *slot = a.part + ((long long)q * n_waves + wave_id);
-        long long r0 = __hip_atomic_exchange(&slot->T, v.T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        long long r1 = __hip_atomic_exchange(&slot->c, v.c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("" ::"v"(r0), "v"(r1));  // both have returned before anything below is issued
-    }
+    if ((threadIdx.x & 63) == 0) a.part[(long long)q * n_waves + wave_id] = v;
 }
 
-// After a wave has emitted its minima: the last of the `arrivals` waves of the launch to get
-// here reduces all of them (n_waves per microbatch count) to the winner records.
-__device__ __forceinline__ void conclude(const mk_args &a, long long n_waves, long long arrivals) {
-    if (!a.part) return;
-    const int lane = threadIdx.x & 63;
-    unsigned last = 0;
-    if (lane == 0) {
-        // Arrival counting in two levels, so that thousands of waves do not queue on one
-        // address: wave w counts on sub-counter w % 64; whoever completes a sub-counter counts
-        // on the top counter; whoever completes that one has seen every wave arrive.
-        const unsigned long long w = (unsigned long long)blockIdx.y * gridDim.x + blockIdx.x;
-        const unsigned sub = (unsigned)(w & 63);
-        const unsigned quota = (unsigned)((arrivals - sub + 63) / 64);
-        const unsigned groups = arrivals < 64 ? (unsigned)arrivals : 64u;
-        // this wave's exchanges in emit() have returned, so they precede these increments
-        if (__hip_atomic_fetch_add(a.ticket + 1 + sub, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == quota - 1)
-            last = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == groups - 1;
-    }
-    last = __builtin_amdgcn_readfirstlane(last);
-    if (!last) return;
+// The winner record of microbatch count q from the minimum w over all entries.
+__device__ __forceinline__ void write_winner(const mk_args &a, int q, tc_pair w, int lane) {
     const int S = a.S;
-    for (int q = 0; q < a.nM; ++q) {
-        tc_pair w = {PP_INF64, INT64_MAX};
-        const tc_pair *part = a.part + (long long)q * n_waves;
-        for (long long i = lane; i < n_waves; i += 64) {
-            tc_pair o;
-            o.T = __hip_atomic_load(&part[i].T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            o.c = __hip_atomic_load(&part[i].c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            w = tc_min(w, o);
-        }
-        w = wave_tc_min(w);
-        const bool none = w.T == PP_INF64;
-        // the winner: candidate c with xi stages, its C at C[at_c], its bounds from bounds[at_b]
-        long long c = w.c, at_c = w.c, at_b = w.c * a.bnd_stride + a.bnd_off;
-        int xi = S;
-        if (a.search && !none) {
-            c = w.c / a.search;
-            xi = (int)(w.c - c * a.search) + 1;
-            at_b = c * ((long long)a.search * (a.search + 1) / 2) + xi * (xi - 1) / 2;
-        }
-        if (a.rout) {
-            // plan with replicated stages: xi bounds and replica counts, all D devices by rank
-            pp_rep_result *out = a.rout + q;
-            if (lane == 0) {
-                out->best_index = none ? -1 : c;
-                out->T = w.T;
-                out->W = none ? PP_INF64 : a.C[at_c];
-                out->S = none ? 0 : xi;
-            }
-            const bool in = lane < xi && !none;
-            out->bounds[lane] = in ? a.bounds[at_b + lane] : 0;
-            out->reps[lane] = in ? a.reps[at_b + lane] : 0;
-            out->order[lane] = (lane < a.D && !none) ? a.orderings[c * a.ord_stride + lane] : 0;
-            continue;
-        }
-        pp_result *out = a.out + q;
+    const bool none = w.T == PP_INF64;
+    // the winner: candidate c with xi stages, its C at C[at_c], its bounds from bounds[at_b]
+    long long c = w.c, at_c = w.c, at_b = w.c * a.bnd_stride + a.bnd_off;
+    int xi = S;
+    if (a.search && !none) {
+        c = w.c / a.search;
+        xi = (int)(w.c - c * a.search) + 1;
+        at_b = c * ((long long)a.search * (a.search + 1) / 2) + xi * (xi - 1) / 2;
+    }
+    if (a.rout) {
+        // plan with replicated stages: xi bounds and replica counts, all D devices by rank
+        pp_rep_result *out = a.rout + q;
         if (lane == 0) {
             out->best_index = none ? -1 : c;
             out->T = w.T;
-            out->C = none ? PP_INF64 : a.C[at_c];
-            out->S = xi;
+            out->W = none ? PP_INF64 : a.C[at_c];
+            out->S = none ? 0 : xi;
         }
-        // lane n writes bound n and device n (lanes xi.. write zeros)
-        int b = 0, o = 0;
-        if (lane < xi && !none) {
-            b = a.bounds[at_b + lane];
-            if (a.orderings) {
-                o = a.orderings[c * a.ord_stride + lane];
-            } else {
-                unsigned long long rem = (unsigned long long)c;
-                unsigned used = 0;
-                for (int n = 0; n <= lane; ++n) o = pp_unrank_next(a.D, n, rem, used);
-            }
-        }
-        out->bounds[lane] = b;
-        out->order[lane] = o;
+        const bool in = lane < xi && !none;
+        out->bounds[lane] = in ? a.bounds[at_b + lane] : 0;
+        out->reps[lane] = in ? a.reps[at_b + lane] : 0;
+        out->order[lane] = (lane < a.D && !none) ? a.orderings[c * a.ord_stride + lane] : 0;
+        return;
     }
-    // ready for the next launch (ordered by the kernel boundary)
-    __hip_atomic_store(a.ticket + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane == 0) __hip_atomic_store(a.ticket + 64, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    pp_result *out = a.out + q;
+    if (lane == 0) {
+        out->best_index = none ? -1 : c;
+        out->T = w.T;
+        out->C = none ? PP_INF64 : a.C[at_c];
+        out->S = xi;
+    }
+    // lane n writes bound n and device n (lanes xi.. write zeros)
+    int b = 0, o = 0;
+    if (lane < xi && !none) {
+        b = a.bounds[at_b + lane];
+        if (a.orderings) {
+            o = a.orderings[c * a.ord_stride + lane];
+        } else {
+            unsigned long long rem = (unsigned long long)c;
+            unsigned used = 0;
+            for (int n = 0; n <= lane; ++n) o = pp_unrank_next(a.D, n, rem, used);
+        }
+    }
+    out->bounds[lane] = b;
+    out->order[lane] = o;
+}
+
+// One workgroup per microbatch count: the minimum (T, index) of its n_part partials, lowest
+// index on ties, and the winner record.
+__global__ __launch_bounds__(256) void k_pick(mk_args a) {
+    __shared__ tc_pair sh[4];
+    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    const tc_pair *part = a.part + (long long)q * a.n_part;
+    tc_pair w = {PP_INF64, INT64_MAX};
+    for (long long i = tid; i < a.n_part; i += 256) w = tc_min(w, part[i]);
+    w = wave_tc_min(w);
+    if (lane == 0) sh[tid >> 6] = w;
+    __syncthreads();
+    if (tid < 64) {
+        w = tc_min(tc_min(sh[0], sh[1]), tc_min(sh[2], sh[3]));
+        write_winner(a, q, w, lane);
+    }
+}
+
+static int launch_pick(mk_args a, int nM, long long n_part, hipStream_t st) {
+    a.n_part = n_part;
+    hipLaunchKernelGGL(k_pick, dim3(nM), dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
 // ---------------------------------------------------------------- registers, S <= 16
@@ -362,7 +348,6 @@ __global__ __launch_bounds__(64) void k_makespan_regs(mk_args a) {
     if (__all(narrow)) T = sweep_regs<S, int>(dur, M, [](const int (&fin)[J + 1]) { return (long long)fin[J]; });
     else T = sweep_regs<S, long long>(dur, M, [](const long long (&fin)[J + 1]) { return fin[J]; });
     emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x);
-    conclude(a, gridDim.x, (long long)gridDim.x * gridDim.y);
 }
 
 // ---------------------------------------------------------------- replicated stages, S <= 16
@@ -525,12 +510,13 @@ __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
     // for it when W == 64
     emit(a, q, c, live, fq, fin[(size_t)(J - 1) * W], blockIdx.x, gridDim.x);
   }
-    conclude(a, gridDim.x, gridDim.x);
 }
+
+static long long regs_waves(long long N) { return (N + 63) / 64; }
 
 template <int S>
 static int launch_regs(const mk_args &a, hipStream_t st) {
-    unsigned grid = (unsigned)((a.N + 63) / 64);
+    unsigned grid = (unsigned)regs_waves(a.N);
     hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, a.nM), dim3(64), 0, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
@@ -569,7 +555,7 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
-                       unsigned *ticket, pp_result *out, hipStream_t st) {
+                       pp_result *out, hipStream_t st) {
     mk_args a;
     a.L = L; a.D = D; a.S = S; a.N = N;
     a.nM = nM;
@@ -579,31 +565,34 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
     a.orderings = orderings; a.bounds = bounds;
     plain_layout(a, S);
     a.T_out = (long long *)T_out; a.status = status;
-    a.part = (tc_pair *)part; a.ticket = ticket; a.C = (const long long *)C; a.out = out;
+    a.part = (tc_pair *)part; a.C = (const long long *)C; a.out = out;
     if (S > 16 && lds_lanes(S) != 64 && part) {
         // narrow workgroups: per microbatch count, T goes to memory and a separate pass finds
         // the minimum
         for (int q = 0; q < nM; ++q) {
             mk_args b = a;
             b.nM = 1; b.Ms[0] = Ms[q];
-            b.part = NULL; b.ticket = NULL; b.C = NULL; b.out = NULL;
+            b.part = NULL; b.C = NULL; b.out = NULL;
             b.T_out = T_out ? (long long *)T_out + (long long)q * N : (long long *)T_scratch;
             if (!b.T_out) return PP_ERR_INVALID_ARG;
             int rc = launch_makespan(b, st);
             if (rc) return rc;
             rc = pp_launch_argmin(D, S, N, (const int64_t *)b.T_out, C, bounds, orderings, part,
-                                  ticket, out + q, st);
+                                  out + q, st);
             if (rc) return rc;
         }
         return PP_OK;
     }
-    return launch_makespan(a, st);
+    int rc = launch_makespan(a, st);
+    if (rc || !part) return rc;
+    // one partial per wave of 64 candidates and microbatch count
+    return launch_pick(a, nM, S <= 16 ? regs_waves(N) : (N + 63) / 64, st);
 }
 
 // ---------------------------------------------------------------- stand-alone arg-min
 
-// Each wave reduces a strided share of T (blockIdx.y selects the microbatch count) and then
-// joins the same last-wave reduction.
+// Each wave reduces a strided share of T (blockIdx.y selects the microbatch count) to a partial
+// for k_pick.
 __global__ __launch_bounds__(64) void k_argmin(mk_args a) {
     const int lane = threadIdx.x, q = blockIdx.y;
     const long long *T = a.T_out + (long long)q * a.N;
@@ -617,12 +606,11 @@ __global__ __launch_bounds__(64) void k_argmin(mk_args a) {
     mk_args b = a;
     b.T_out = NULL;
     emit(b, q, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
-    conclude(b, gridDim.x, (long long)gridDim.x * gridDim.y);
 }
 
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
-                     unsigned *ticket, pp_result *out, hipStream_t st) {
+                     pp_result *out, hipStream_t st) {
     mk_args a;
     a.L = 0; a.D = D; a.S = S; a.N = N;
     a.nM = 1;
@@ -631,11 +619,12 @@ int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C
     a.orderings = orderings; a.bounds = bounds;
     plain_layout(a, S);
     a.T_out = (long long *)T; a.status = NULL;
-    a.part = (tc_pair *)part; a.ticket = ticket; a.C = (const long long *)C; a.out = out;
+    a.part = (tc_pair *)part; a.C = (const long long *)C; a.out = out;
     long long waves = (N + 63) / 64;
     if (waves > 1024) waves = 1024;
     hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves), dim3(64), 0, st, a);
-    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+    return launch_pick(a, 1, waves, st);
 }
 
 // ---------------------------------------------------------------- stage-count search
@@ -644,7 +633,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              unsigned *ticket, pp_result *out, hipStream_t st) {
+                              pp_result *out, hipStream_t st) {
     mk_args a;
     a.L = L; a.D = D; a.N = N; a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
@@ -652,7 +641,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
     a.XF = (const long long *)XF; a.XB = (const long long *)XB;
     a.orderings = orderings; a.bounds = bounds;
     a.T_out = (long long *)T_st; a.status = status;
-    a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL;
+    a.part = NULL; a.C = NULL; a.out = NULL;
     a.ord_stride = S; a.bnd_stride = (long long)S * (S + 1) / 2; a.t_stride = S; a.search = 0;
     a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
     // one launch per stage count: the schedules of xi stages on the first xi devices
@@ -666,11 +655,12 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
     // smallest T over all (candidate, stage count) pairs, lowest c*S + xi-1 on ties
     mk_args m = a;
     m.S = S; m.N = N * S; m.search = S;
-    m.part = (tc_pair *)part; m.ticket = ticket; m.C = (const long long *)C; m.out = out;
+    m.part = (tc_pair *)part; m.C = (const long long *)C; m.out = out;
     long long waves = (m.N + 63) / 64;
     if (waves > 1024) waves = 1024;
     hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves, nM), dim3(64), 0, st, m);
-    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+    return launch_pick(m, nM, waves, st);
 }
 
 // ---------------------------------------------------------------- replicated stages: launch
@@ -686,7 +676,7 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
                            const int64_t *PA, const int64_t *actf, const int64_t *actb,
                            const int64_t *bw, const int32_t *orderings, const int32_t *bounds,
                            const int32_t *reps, const int64_t *W, int64_t *T_out, int32_t *status,
-                           void *part, unsigned *ticket, pp_rep_result *out, hipStream_t st) {
+                           void *part, pp_rep_result *out, hipStream_t st) {
     if (D > 16) return PP_ERR_INVALID_ARG;
     mk_args a;
     a.L = L; a.D = D; a.N = N; a.nM = 1;
@@ -697,7 +687,7 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
     a.bw = (const long long *)bw; a.W = (const long long *)W;
     a.orderings = orderings; a.bounds = bounds; a.reps = reps;
     a.T_out = (long long *)T_out; a.status = status;
-    a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL; a.rout = NULL;
+    a.part = NULL; a.C = NULL; a.out = NULL; a.rout = NULL;
     a.ord_stride = D; a.bnd_stride = (long long)D * (D + 1) / 2; a.t_stride = D; a.search = 0;
     for (int xi = 1; xi <= D; ++xi) {
         a.S = xi;
@@ -715,11 +705,12 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
     // smallest T over all (candidate, stage count) pairs, lowest c*D + xi-1 on ties
     mk_args m = a;
     m.S = D; m.N = N * D; m.search = D;
-    m.part = (tc_pair *)part; m.ticket = ticket; m.C = (const long long *)W; m.rout = out;
+    m.part = (tc_pair *)part; m.C = (const long long *)W; m.rout = out;
     long long waves = (m.N + 63) / 64;
     if (waves > 1024) waves = 1024;
     hipLaunchKernelGGL(k_argmin, dim3((unsigned)waves, 1), dim3(64), 0, st, m);
-    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
+    return launch_pick(m, 1, waves, st);
 }
 
 // ---------------------------------------------------------------- schedule variants
@@ -814,7 +805,7 @@ int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int 
     plain_layout(a, S);
     a.variant = variant;
     a.T_out = (long long *)T_out; a.status = status;
-    a.part = NULL; a.ticket = NULL; a.C = NULL; a.out = NULL;
+    a.part = NULL; a.C = NULL; a.out = NULL;
     const int W = lds_lanes(S);
     const size_t lds = (size_t)2 * (4 * S - 3) * W * 8;
     unsigned grid = (unsigned)((N + W - 1) / W);

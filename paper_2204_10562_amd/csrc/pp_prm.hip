@@ -41,7 +41,6 @@ struct prm_args {
     int *bounds_out;   // [N][D(D+1)/2]
     int *reps_out;     // [N][D(D+1)/2]
     long long *pre_out;  // [3][L+1]: prefix sums of fwd, bwd, alpha for the kernels that follow
-    unsigned *ticket;    // 65 arrival counters of the arg-min that follows, cleared here
     int32_t *status;
 };
 
@@ -439,7 +438,6 @@ __global__ __launch_bounds__(PRM_THREADS) void k_prm(prm_args a) {
     }
     __syncthreads();
     if (blockIdx.x == 0) {
-        for (int t = tid; t < 65; t += B) a.ticket[t] = 0;
         if (!sh.fault)
             for (int l = tid; l <= L; l += B) {
                 a.pre_out[l] = PF[l];
@@ -469,7 +467,7 @@ __global__ __launch_bounds__(256) void k_all_orderings(int D, long long N, int *
 
 // Workspace of pp_plan_replicated.
 struct rep_layout {
-    size_t slots_at, ord, pre, W, T, bounds, reps, part, ticket, total;
+    size_t slots_at, ord, pre, W, T, bounds, reps, part, total;
     int slots;
 };
 
@@ -486,7 +484,6 @@ static rep_layout rep_layout_of(int L, int D, int64_t N) {
     w.bounds = off;   off += pp_align256((size_t)N * tri * 4);
     w.reps = off;     off += pp_align256((size_t)N * tri * 4);
     w.part = off;     off += pp_align256((size_t)1024 * 16);
-    w.ticket = off;   off += pp_align256(65 * 4);
     w.total = off;
     return w;
 }
@@ -546,11 +543,10 @@ extern "C" int pp_plan_replicated(int L, int D, int64_t N, int M, const int64_t 
     a.slot_bytes = prm_slot_bytes(L, D);
     a.W_out = (long long *)W; a.bounds_out = bounds; a.reps_out = reps;
     a.pre_out = (long long *)pre;
-    a.ticket = (unsigned *)(base + lay.ticket);
     a.status = status;
     hipLaunchKernelGGL(k_prm, dim3(lay.slots), dim3(PRM_THREADS), prm_lds_bytes(L, D), st, a);
     if (hipGetLastError() != hipSuccess) return PP_ERR_HIP;
     return pp_launch_rep_makespan(L, D, N, M, pre, pre + (L + 1), pre + 2 * (L + 1), act_fwd_bytes,
                                   actb, bw, ord, bounds, reps, W, T, status, base + lay.part,
-                                  (unsigned *)(base + lay.ticket), out, st);
+                                  out, st);
 }
