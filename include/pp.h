@@ -97,16 +97,17 @@ int pp_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
  * The workspace must be 256-byte aligned; its contents need not be kept
  * between calls.
  *
- * Diagnostics: after pp_partition_dp or pp_best_plan the 64 uint64 counters
- * that start at byte PP_WS_PAIRS_EXECUTED of the workspace add up to the
- * number of (cell, split) pairs the dynamic program actually evaluated in
- * that call, and the 64 that start at byte PP_WS_ROWS_EXECUTED to the number
- * of DP rows it computed.  Rows that consecutive candidates share (equal
- * ordering prefixes) are computed and counted once, so these can be far
- * below N * pairs-per-candidate.
+ * Diagnostics: after pp_partition_dp or pp_best_plan the workspace holds, from
+ * byte PP_WS_WORK on, 64 records PP_WS_WORK_STRIDE bytes apart; the uint64 at
+ * the start of each record adds up (over the 64) to the number of (cell,
+ * split) pairs the dynamic program actually evaluated in that call, the
+ * uint64 after it to the number of DP rows it computed.  Rows that
+ * consecutive candidates share (equal ordering prefixes) are computed and
+ * counted once, and the kernel for L > 128 skips splits that cannot matter, so
+ * these can be far below N * pairs-per-candidate.
  */
-#define PP_WS_PAIRS_EXECUTED 1024
-#define PP_WS_ROWS_EXECUTED 1536
+#define PP_WS_WORK 1024
+#define PP_WS_WORK_STRIDE 128
 size_t pp_workspace_bytes(int L, int D, int S, int64_t N);
 
 /*

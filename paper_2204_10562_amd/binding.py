@@ -279,16 +279,16 @@ def pp_rdo_order(D, bw_bytes_per_us):
     return list(order)
 
 
-PP_WS_PAIRS_EXECUTED = 1024
-PP_WS_ROWS_EXECUTED = 1536
+PP_WS_WORK = 1024
+PP_WS_WORK_STRIDE = 128
 
 
 def read_workspace_stats(workspace):
     """Diagnostic counters the last DP call left in the workspace header (see pp.h)."""
     import numpy as np
-    head = workspace[:2048].cpu().numpy().view(np.uint64)
-    return dict(pairs_executed=int(head[PP_WS_PAIRS_EXECUTED // 8:PP_WS_PAIRS_EXECUTED // 8 + 64].sum()),
-                rows_executed=int(head[PP_WS_ROWS_EXECUTED // 8:PP_WS_ROWS_EXECUTED // 8 + 64].sum()))
+    rec = workspace[PP_WS_WORK:PP_WS_WORK + 64 * PP_WS_WORK_STRIDE].cpu().numpy().view(np.uint64)
+    rec = rec.reshape(64, PP_WS_WORK_STRIDE // 8)
+    return dict(pairs_executed=int(rec[:, 0].sum()), rows_executed=int(rec[:, 1].sum()))
 
 
 def read_result(out, S=None, index=0):

@@ -26,18 +26,20 @@ static inline int pp_index_bits(int L) {
 struct pp_ws_header {
     unsigned long long pmax[PP_PACK_BLOCKS];  // byte 0
     unsigned pad0[128];  // byte 512
-    // byte 1024: (cell, split) pairs the partition DP actually evaluated in this call (rows
-    // shared between candidates are counted once), spread over 64 counters to keep the
-    // atomics apart; byte 1536: DP rows computed (the single-cell last row counts too).
-    // Zeroed by the pack kernel; the totals are the sums of the 64 entries.
-    unsigned long long pairs_executed[64];
-    unsigned long long rows_executed[64];
+    // byte 1024: work the partition DP actually did in this call, in 64 records of 128 bytes
+    // (atomics that hit one cache line are served one after another, so every record has a
+    // line of its own): (cell, split) pairs evaluated (rows shared between candidates are
+    // counted once) and DP rows computed (the single-cell last row counts too).  Zeroed by
+    // the pack kernel; the totals are the sums over the 64 records.
+    struct {
+        unsigned long long pairs, rows, pad[14];
+    } work[64];
 };
 
 __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long long pairs,
                                               unsigned long long rows, unsigned who) {
-    atomicAdd(&hdr->pairs_executed[who & 63], pairs);
-    atomicAdd(&hdr->rows_executed[who & 63], rows);
+    atomicAdd(&hdr->work[who & 63].pairs, pairs);
+    atomicAdd(&hdr->work[who & 63].rows, rows);
 }
 
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.

@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void k_prep(pack_args a) {
             }
             long long pl = a.PF[a.L] + a.PB[a.L];
             m = pl < 0 ? ~0ull : (unsigned long long)pl;
-            if (tid < 64) { a.hdr->pairs_executed[tid] = 0; a.hdr->rows_executed[tid] = 0; }
+            if (tid < 64) { a.hdr->work[tid].pairs = 0; a.hdr->work[tid].rows = 0; }
         }
         unsigned long long mx = pack_x(a, first, stride);
         m = mx > m ? mx : m;
