@@ -98,7 +98,7 @@ extern "C" int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM, const
                       workspace, lay, status, st);
     if (rc) return rc;
     return pp_launch_makespan_stages(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, C, T,
-                                     status, base + sl.part, out, st);
+                                     status, base + sl.part, out, (const pp_ws_header *)(base + lay.hdr), st);
 }
 
 extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
@@ -109,7 +109,7 @@ extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const
     if (rc) return rc;
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
     return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
-                              status, NULL, NULL, NULL, (hipStream_t)stream);
+                              status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
 extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
@@ -122,7 +122,7 @@ extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, in
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
     if (variant == PP_SCHED_PE)
         return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
-                                  status, NULL, NULL, NULL, (hipStream_t)stream);
+                                  status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
     if (variant != PP_SCHED_DUPLEX && variant != PP_SCHED_GPIPE) return PP_ERR_INVALID_ARG;
     return pp_launch_makespan_variant(variant, L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out,
                                       status, (hipStream_t)stream);
@@ -153,7 +153,8 @@ extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const 
                       workspace, lay, status, st);
     if (rc) return rc;
     return pp_launch_makespan(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, T_all,
-                              (int64_t *)(base + lay.T), status, C, base + lay.part, out, st);
+                              (int64_t *)(base + lay.T), status, C, base + lay.part, out,
+                              (const pp_ws_header *)(base + lay.hdr), st);
 }
 
 extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,

@@ -109,12 +109,13 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
 // With part/C/out non-NULL the launch also finds, per microbatch count, the candidate
 // with the smallest T (lowest index on ties) and fills out[q] (one pair of int64 per wave of
 // 64 candidates and microbatch count in part).  T_out ([nM][N]) may then be NULL; T_scratch
-// ([N]) is needed for S > 16 in that case.
+// ([N]) is needed for S > 16 in that case.  hdr: the workspace header the pack kernel has filled
+// for these tables (its largest time decides between 32-bit and 64-bit kernels), or NULL.
 int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
-                       pp_result *out, hipStream_t st);
+                       pp_result *out, const pp_ws_header *hdr, hipStream_t st);
 // Stage-count search: makespan of the plan with xi stages of every candidate for xi = 1..S
 // (bounds [N][S(S+1)/2] and C [N][S] as pp_launch_dp leaves them with stages == 1), written to
 // T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest
@@ -123,7 +124,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              pp_result *out, hipStream_t st);
+                              pp_result *out, const pp_ws_header *hdr, hipStream_t st);
 // Makespan (Eq. 2) of the plans with replicated stages of every (candidate, stage count) and
 // the keep-the-minimum over them; arrays laid out as pp_plan_replicated documents; part holds
 // 1024 pairs of int64.

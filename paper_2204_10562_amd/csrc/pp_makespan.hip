@@ -45,6 +45,9 @@ struct mk_args {
     // i = c*search + xi-1; the record of the winner is decoded accordingly
     int search;
     int variant;  // k_makespan_variant only: PP_SCHED_*
+    // workspace header with the largest time of the tables (NULL if there is none): lets every
+    // wave of a launch take the same decision between 32-bit and 64-bit finish times
+    const pp_ws_header *hdr;
     int32_t *status;
     // replicated stages (k_rep_makespan and the record of its arg-min; NULL otherwise): replica
     // counts laid out like bounds, prefix sums of the parameter sizes, activation sizes, the
@@ -470,6 +473,65 @@ __global__ __launch_bounds__(64) void k_rep_makespan(mk_args a) {
 
 // ---------------------------------------------------------------- LDS columns, any S
 
+// True if no finish time of any candidate of the launch can reach 2^31 for any of its
+// microbatch counts (Lemma 1's bound with the largest time of the tables); the same for every
+// lane of every wave.  False without a header.
+__device__ __forceinline__ bool launch_is_narrow(const mk_args &a) {
+    if (!a.hdr) return false;
+    unsigned long long vmax = 0;
+    for (int b = 0; b < PP_PACK_BLOCKS; ++b) vmax = a.hdr->pmax[b] > vmax ? a.hdr->pmax[b] : vmax;
+    int mmax = 1;
+    for (int q = 0; q < a.nM; ++q) mmax = a.Ms[q] > mmax ? a.Ms[q] : mmax;
+    return vmax <= 0x7fffffffull / (unsigned long long)(mmax + 4 * a.S - 4);
+}
+
+// 16 < S <= 32 with 32-bit times: the 4S-3 finish times of a lane in registers (blocks
+// unrolled, each update selected by a per-lane test of the sweep's window), the durations in
+// the lane's LDS column.  Runs only if the whole launch is narrow; k_makespan_lds, launched
+// with it, runs otherwise.
+template <int S>
+__global__ __launch_bounds__(64) void k_makespan_mid(mk_args a) {
+    constexpr int R = 2 * S - 1, J = 2 * R - 1;
+    extern __shared__ int smi[];
+    if (!launch_is_narrow(a)) return;
+    const int lane = threadIdx.x;
+    int *dur = smi + lane;  // [J][64]
+    const long long c = (long long)blockIdx.x * 64 + lane;
+    const bool live = c < a.N;
+    long long worst;
+    const int fault = gather_durations<S>(a, c, live, worst,
+                                          [&](int j, long long d) { dur[(j - 1) * 64] = (int)d; });
+    for (int q = 0; q < a.nM; ++q) {
+        const int M = a.Ms[q];
+        const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
+        int fin[J + 1];
+#pragma unroll
+        for (int j = 0; j <= J; ++j) fin[j] = 0;
+        const int sweeps = M + 2 * R - 2;
+        const unsigned width = (unsigned)(M - 1);
+        for (int t = 1; t <= sweeps; ++t) {
+            int jlo = t - M + 1;
+            asm volatile("" : "+v"(jlo));
+            const int finR_prev = fin[R];
+#pragma unroll
+            for (int j = R; j >= 1; --j) {
+                int idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+                int ready = j > 1 ? fin[j - 1] : 0;
+                int nv = (idle > ready ? idle : ready) + dur[(j - 1) * 64];
+                fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
+            }
+#pragma unroll
+            for (int j = J; j >= R + 1; --j) {
+                int idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+                int ready = j == R + 1 ? finR_prev : fin[j - 1];
+                int nv = (idle > ready ? idle : ready) + dur[(j - 1) * 64];
+                fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
+            }
+        }
+        emit(a, q, c, live, fq, (long long)fin[J], blockIdx.x, gridDim.x);
+    }
+}
+
 // blockDim.x = lanes in use (64, or fewer when 2 * (4S-3) rows of 64 int64 would not fit in
 // 64 KiB of LDS); the lane's state lives in its own column [row][lane]: no bank conflicts, no
 // barriers.
@@ -477,6 +539,7 @@ __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
     extern __shared__ long long sm[];
     const int lane = threadIdx.x, W = blockDim.x;
     const int S = a.S;
+    if (S > 16 && S <= 32 && launch_is_narrow(a)) return;  // k_makespan_mid does this launch
     const int R = 2 * S - 1, J = 2 * R - 1;
     // rows 0..J-1: duration of block j = row+1; rows J..2J-1: its latest finish time
     long long *dur = sm + lane;
@@ -521,10 +584,18 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
+template <int S>
+static int launch_mid(const mk_args &a, hipStream_t st) {
+    unsigned grid = (unsigned)((a.N + 63) / 64);
+    hipLaunchKernelGGL(k_makespan_mid<S>, dim3(grid), dim3(64), (size_t)(4 * S - 3) * 64 * 4, st, a);
+    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+}
+
 static void plain_layout(mk_args &a, int S) {
     a.ord_stride = S; a.bnd_stride = S; a.bnd_off = 0; a.t_stride = 1; a.t_off = 0; a.search = 0;
     a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
     a.variant = 0;
+    a.hdr = NULL;
 }
 
 // Lanes per workgroup of the LDS kernel: as many as keep 2J rows of int64 within 64 KiB.
@@ -545,6 +616,17 @@ static int launch_makespan(const mk_args &a, hipStream_t st) {
 #undef CASE
     }
     const int W = lds_lanes(a.S);
+    if (a.hdr && a.S <= 32 && (W == 64 || !a.part)) {
+        // both kernels are enqueued; which one works depends on the data (see launch_is_narrow)
+        int rc = PP_ERR_INVALID_ARG;
+        switch (a.S) {
+#define CASE(n) case n: rc = launch_mid<n>(a, st); break;
+            CASE(17) CASE(18) CASE(19) CASE(20) CASE(21) CASE(22) CASE(23) CASE(24)
+            CASE(25) CASE(26) CASE(27) CASE(28) CASE(29) CASE(30) CASE(31) CASE(32)
+#undef CASE
+        }
+        if (rc) return rc;
+    }
     const size_t lds = (size_t)2 * (4 * a.S - 3) * W * 8;
     unsigned grid = (unsigned)((a.N + W - 1) / W);
     hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, a);
@@ -555,7 +637,7 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
-                       pp_result *out, hipStream_t st) {
+                       pp_result *out, const pp_ws_header *hdr, hipStream_t st) {
     mk_args a;
     a.L = L; a.D = D; a.S = S; a.N = N;
     a.nM = nM;
@@ -566,6 +648,7 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
     plain_layout(a, S);
     a.T_out = (long long *)T_out; a.status = status;
     a.part = (tc_pair *)part; a.C = (const long long *)C; a.out = out;
+    a.hdr = hdr;
     if (S > 16 && lds_lanes(S) != 64 && part) {
         // narrow workgroups: per microbatch count, T goes to memory and a separate pass finds
         // the minimum
@@ -633,7 +716,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              pp_result *out, hipStream_t st) {
+                              pp_result *out, const pp_ws_header *hdr, hipStream_t st) {
     mk_args a;
     a.L = L; a.D = D; a.N = N; a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
@@ -644,6 +727,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
     a.part = NULL; a.C = NULL; a.out = NULL;
     a.ord_stride = S; a.bnd_stride = (long long)S * (S + 1) / 2; a.t_stride = S; a.search = 0;
     a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
+    a.variant = 0; a.hdr = hdr;
     // one launch per stage count: the schedules of xi stages on the first xi devices
     for (int xi = 1; xi <= S; ++xi) {
         a.S = xi;

@@ -498,3 +498,22 @@ def test_whole_path_at_full_size(ppo, G, name, stride):
     rc, T0 = ppo.schedule_makespan(L, w.D, S, len(idx), M, PF, PB, XF, XB, sub, b0)
     assert rc == 0
     np.testing.assert_array_equal(T[idx], T0)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N,shift", [(811, 40, 20, 20, 70, 0), (812, 70, 32, 32, 40, 0), (813, 30, 17, 17, 65, 0),
+                                                  (814, 40, 20, 20, 70, 24), (815, 64, 25, 24, 33, 30)])
+def test_best_plan_between_17_and_32_stages(ppo, G, seed, L, D, S, N, shift):
+    # 32-bit times: finish times in registers; larger times: the LDS kernel, chosen on the device
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1, hi_time=9, hi_act=300)
+    if shift:
+        w.fwd = w.fwd << shift
+        w.bwd = w.bwd << shift
+        w.actf = w.actf << (shift - 3)
+        w.actb = w.actb << (shift - 3)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    for M in (1, 7, 60):
+        say("best_plan 17..32 stages", seed, L, D, S, N, "shift", shift, "M", M)
+        check_best(ppo, g, w, M, tables)
+    check_best_multi(ppo, g, w, (3, 50), tables)
