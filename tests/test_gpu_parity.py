@@ -517,3 +517,27 @@ def test_best_plan_between_17_and_32_stages(ppo, G, seed, L, D, S, N, shift):
         say("best_plan 17..32 stages", seed, L, D, S, N, "shift", shift, "M", M)
         check_best(ppo, g, w, M, tables)
     check_best_multi(ppo, g, w, (3, 50), tables)
+
+
+@pytest.mark.parametrize("seed", range(900, 960))
+def test_whole_path_random_shapes(ppo, G, seed):
+    # shapes drawn at random: every tile count of the L <= 128 kernel, ragged super-rows of the
+    # L > 128 kernel, S from 1 to D, caller's lists and all D! orderings
+    rng = np.random.Generator(np.random.PCG64(seed))
+    L = int(rng.integers(1, 129)) if seed % 3 else int(rng.integers(129, 420))
+    D = int(rng.integers(1, 10))
+    S = int(rng.integers(1, min(L, D) + 1))
+    N = int(rng.integers(1, 160))
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1 if seed % 2 else 0.0, hi_time=int(rng.integers(2, 200)),
+                               hi_act=int(rng.integers(1, 5000)))
+    if S == D and D <= 5 and seed % 4 == 0:
+        import math
+        w.orderings = None
+        w.N = math.factorial(D)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("random shape", seed, "L", L, "D", D, "S", S, "N", w.N)
+    check_dp(ppo, g, w)
+    Ms = (int(rng.integers(1, 5)), int(rng.integers(5, 80)))
+    check_best_multi(ppo, g, w, Ms, tables)
