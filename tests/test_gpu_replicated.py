@@ -170,3 +170,17 @@ def test_replicated_wide_values(ppo, G, seed, L, D, N, what):
         alpha = alpha << 34
     say("replicated wide", what, seed, L, D, N)
     check(ppo, G, w, alpha, 5)
+
+
+@pytest.mark.parametrize("seed", range(950, 980))
+def test_replicated_random_shapes(ppo, G, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    D = int(rng.integers(1, 9))
+    L = int(rng.integers(1, 60)) if seed % 3 else int(rng.integers(100, 200))
+    N = int(rng.integers(1, 40))
+    w = workloads.random_small(seed, L, D, D, N, zero_frac=0.1 if seed % 2 else 0.0, hi_time=int(rng.integers(2, 300)),
+                               hi_act=int(rng.integers(1, 9000)))
+    alpha = rng.integers(0, int(rng.integers(2, 10**6)), size=L).astype(np.int64)
+    M = int(rng.integers(1, 70))
+    say("replicated random", seed, "L", L, "D", D, "N", N, "M", M)
+    check(ppo, G, w, alpha, M)

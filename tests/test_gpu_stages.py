@@ -173,3 +173,19 @@ def test_stages_at_full_size(ppo, G, name, stride):
     assert res[0]["bounds"] == b0[pos, xi * (xi - 1) // 2: xi * (xi + 1) // 2].tolist()
     assert res[0]["order"] == v.orderings[pos, :xi].tolist()
     assert res[0]["C"] == C0[pos, xi - 1]
+
+
+@pytest.mark.parametrize("seed", range(960, 990))
+def test_stages_random_shapes(ppo, G, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    L = int(rng.integers(1, 129)) if seed % 3 else int(rng.integers(129, 300))
+    D = int(rng.integers(1, 10))
+    S = int(rng.integers(1, min(L, D) + 1))
+    N = int(rng.integers(1, 120))
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1 if seed % 2 else 0.0, hi_time=int(rng.integers(2, 200)),
+                               hi_act=int(rng.integers(1, 5000)))
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("stages random", seed, "L", L, "D", D, "S", S, "N", N)
+    check_stages(ppo, g, w, (int(rng.integers(1, 6)), int(rng.integers(6, 70))), tables)
