@@ -48,6 +48,44 @@ __device__ __forceinline__ int min_over_b(int v) {
     return v;
 }
 
+// Min over the 8 lanes that share a = lane/8 for NT values at once.  The first step pairs
+// lane b with lane 7-b and lets the lanes b < 4 reduce value i and the lanes b >= 4 value
+// i + H (H = ceil(NT/2)) into the same register, so the two remaining steps run on half as
+// many registers.  Afterwards v[i], i < H, holds the minimum of value i on lanes b < 4 and of
+// value i + H (if there is one) on lanes b >= 4.
+// The compiler does not see that the statements below are DPP operations, so the wait states
+// DPP needs after a write of its source register are given explicitly: the empty statements
+// pin every producer before the first s_nop, and every step is separated from the next.
+template <int NT>
+__device__ __forceinline__ void min_over_b_halves(int (&v)[NT]) {
+    constexpr int H = (NT + 1) / 2;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) asm volatile("" : "+v"(v[i]));
+    asm volatile("s_nop 1");
+#pragma unroll
+    for (int i = 0; i < H; ++i) {
+        asm volatile("v_min_i32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0x5"
+                     : "+v"(v[i]));
+        if (i + H < NT)
+            asm volatile("v_min_i32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xa"
+                         : "+v"(v[i])
+                         : "v"(v[i + H]));
+    }
+    asm volatile("s_nop 1");
+#pragma unroll
+    for (int i = 0; i < H; ++i)
+        asm volatile("v_min_i32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf"
+                     : "+v"(v[i]));
+    asm volatile("s_nop 1");
+#pragma unroll
+    for (int i = 0; i < H; ++i)
+        asm volatile("v_min_i32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+                     : "+v"(v[i]));
+    asm volatile("s_nop 1");
+#pragma unroll
+    for (int i = 0; i < H; ++i) asm volatile("" : "+v"(v[i]));
+}
+
 __device__ __forceinline__ void lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -123,6 +161,9 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     };
     const unsigned long long smask = S >= 64 ? ~0ull : ((1ull << S) - 1);
     const int top_lane = ((L - 1) & 7) * 8;  // a lane that owns cell L (in tile NT-1)
+    constexpr int H = (NT + 1) / 2;
+    // where this lane stores the cells it holds after a row's reduction (b = 0 or 4 only)
+    const int wofs = la + 1 + (lb >> 2) * 8 * H;
 
     // finished candidates pend0 .. pend0+pending-1 wait for their plans to be written out;
     // lane q keeps the key of cell (S-1, L) of pending candidate q (-1: its ordering was bad)
@@ -277,11 +318,15 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
 #pragma unroll
                 for (int j = 0; j < NT; ++j) asm volatile("" : "+v"(Pk[j]));
             }
-            const int *prow = rows + (n - 1) * RS;
             int *nrow = rows + n * RS;
+            // the previous row is read through an index of its own, so that the NT reads are
+            // one address and NT immediate offsets (seen as nrow minus a constant the offsets
+            // would be negative, which the instruction cannot hold)
+            int pidx = (n - 1) * RS + lb;
+            asm volatile("" : "+v"(pidx));
             int g[NT];
 #pragma unroll
-            for (int j = 0; j < NT; ++j) g[j] = prow[8 * j + lb];
+            for (int j = 0; j < NT; ++j) g[j] = rows[pidx + 8 * j];
 #pragma unroll
             for (int j = 0; j < NT; ++j) asm volatile("" : "+v"(g[j]));  // all reads in flight at once
 #pragma unroll
@@ -301,24 +346,24 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                     for (int j = 0; j <= i; ++j) v = imin(v, imax(g[j], dkey(i, j)));
                     acc[i] = v;
                 }
-#pragma unroll
-                for (int i = 0; i < NT; ++i) {
-                    acc[i] = min_over_b(acc[i]);
-                    asm volatile("" : "+v"(acc[i]));
-                }
+                min_over_b_halves<NT>(acc);
                 pairs += (unsigned long long)((L - n) * (L - n + 1) / 2);
                 ++nrows;
                 const int slot = arena_used++;
-                const int top_n = __builtin_amdgcn_readlane(acc[NT - 1], top_lane);
+                const int top_n = NT == 1 ? __builtin_amdgcn_readlane(acc[0], top_lane)
+                                          : __builtin_amdgcn_readlane(acc[NT - 1 - H], top_lane + 4);
                 if (lane == n) { v_cur = slot; v_tops = top_n; }
-                if (lb == 0) {
-                    unsigned char *arow = arena + slot * RB;
+                unsigned char *arow = arena + slot * RB;
+                // lanes b = 0 hold tiles 0..H-1, lanes b = 4 tiles H..NT-1 (one fewer if NT is odd)
+                if ((lb & 3) == 0) {
+                    // keys first, then bytes: stores of one kind in a row can be paired
 #pragma unroll
-                    for (int i = 0; i < NT; ++i) {
-                        nrow[8 * i + la + 1] = acc[i];
-                        // low byte of the key: the split index in its low K <= 7 bits
-                        arow[8 * i + la + 1] = (unsigned char)acc[i];
-                    }
+                    for (int i = 0; i < H; ++i)
+                        if (i + H < NT || lb == 0) nrow[8 * i + wofs] = acc[i];
+                    // low byte of the key: the split index in its low K <= 7 bits
+#pragma unroll
+                    for (int i = 0; i < H; ++i)
+                        if (i + H < NT || lb == 0) arow[8 * i + wofs] = (unsigned char)acc[i];
                 }
                 lds_sync();
             } else {
