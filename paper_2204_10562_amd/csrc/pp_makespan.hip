@@ -81,9 +81,12 @@ __device__ __forceinline__ tc_pair wave_tc_min(tc_pair v) {
 // dead lane all durations are 0.  `worst` gets the largest per-resource time f + b.
 // ST > 0 fixes the number of stages at compile time (block numbers become constants).
 // `last(F, B)` receives the last stage's forward and backward times separately.
+// With parts > 1 only the stages n with n % parts == part are looked up (and reported through
+// put/last); `worst` then covers those stages only.
 template <int ST, typename Put, typename Last>
 __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, bool live,
-                                                long long &worst, Put put, Last last) {
+                                                long long &worst, Put put, Last last,
+                                                int part = 0, int parts = 1) {
     const int S = ST ? ST : a.S, L = a.L, D = a.D, R = 2 * S - 1;
     int fault = 0;
     if (live) {
@@ -113,16 +116,19 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
         if (live && !fault) {
             int o_n = a.orderings ? a.orderings[c * a.ord_stride + n] : pp_unrank_next(D, n, rem, used);
             int e = a.bounds[c * a.bnd_stride + a.bnd_off + n];
-            F = a.PF[e] - a.PF[e_prev];
-            Bk = a.PB[e] - a.PB[e_prev];
-            if (n) {
-                size_t at = ((size_t)o_prev * D + o_n) * L + (size_t)(e_prev - 1);
-                cf = a.XF[at];
-                cb = a.XB[at];
+            if (parts == 1 || n % parts == part) {
+                F = a.PF[e] - a.PF[e_prev];
+                Bk = a.PB[e] - a.PB[e_prev];
+                if (n) {
+                    size_t at = ((size_t)o_prev * D + o_n) * L + (size_t)(e_prev - 1);
+                    cf = a.XF[at];
+                    cb = a.XB[at];
+                }
             }
             e_prev = e;
             o_prev = o_n;
         }
+        if (parts != 1 && n % parts != part) continue;
         long long w = F + Bk > cf + cb ? F + Bk : cf + cb;
         worst = w > worst ? w : worst;
         const int r = 2 * n + 1;  // stage n is resource 2n+1, channel n is resource 2n
@@ -244,6 +250,16 @@ static int launch_pick(mk_args a, int nM, long long n_part, hipStream_t st) {
 
 // ---------------------------------------------------------------- registers, S <= 16
 
+// med3(old, fresh, sel) for 0 <= old <= fresh < 2^31: fresh if the scalar sel is all ones, old if it is 0.
+__device__ __forceinline__ int keep_or_take(int old, int fresh, unsigned sel) {
+    int r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(old), "v"(fresh), "s"(sel));
+    return r;
+}
+__device__ __forceinline__ long long keep_or_take(long long old, long long fresh, unsigned sel) {
+    return sel ? fresh : old;
+}
+
 // One sweep restricted to blocks LO..HI (compile-time), no validity tests.
 template <int S, typename V, int LO, int HI>
 __device__ __forceinline__ void sweep_blocks(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1]) {
@@ -288,31 +304,54 @@ __device__ __forceinline__ void ramp_down(V (&fin)[4 * S - 3 + 1], const V (&dur
 // backward block on stage 0.  Block j works in sweep t iff t-M+1 <= j <= t.  When the
 // pipeline fills completely (M >= J-1) the sweeps split into a ramp-up (blocks 1..t), a
 // steady phase (all blocks) and a ramp-down (blocks t-M+1..J) whose block ranges are known at
-// compile time; otherwise every block update is selected by a per-lane compare.
+// compile time.  A shorter pipeline still has such a ramp-up (its first M sweeps) and ramp-down
+// (its last M-1); in the sweeps between them, and in every sweep for S > 8 (where unrolling
+// every sweep would be too much code), every block is computed and the update is kept or
+// dropped by a select: with 32-bit times a median of three against a per-block scalar that is
+// 0 or all ones (finish times never decrease, so med3(old, new, ~0) = new and
+// med3(old, new, 0) = old), with 64-bit times a per-lane compare.
 // `result(fin)` turns the final finish times into the value returned.
-template <int S, typename V, typename Result>
-__device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S - 3 + 1], int M, Result result) {
+// Sweep t with every block computed and the update of the blocks outside [t-M+1, t] dropped.
+template <int S, typename V>
+__device__ __forceinline__ void sweep_selected(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1], int t, int M) {
     constexpr int R = 2 * S - 1, J = 2 * R - 1;
-    V dur[J + 1], fin[J + 1];
+    const V finR_prev = fin[R];
+    if constexpr (sizeof(V) == 4) {
+        // bit j of `act`: block j works in this sweep
+        const int jlo = t - M + 1 > 1 ? t - M + 1 : 1, jhi = t < J ? t : J;
+        const unsigned long long act = ((2ull << jhi) - 1) & ~((1ull << jlo) - 1);
+        // groups of G blocks without an active one are skipped altogether
+        constexpr int G = 5;
 #pragma unroll
-    for (int j = 1; j <= J; ++j) { dur[j] = (V)dur64[j]; fin[j] = 0; }
-    dur[0] = fin[0] = 0;
-    if constexpr (S <= 8) {
-        if (M >= J - 1) {
-            ramp_up<S, V, 1>(fin, dur);
-            for (int t = J; t <= M; ++t) sweep_blocks<S, V, 1, J>(fin, dur);
-            ramp_down<S, V, 1>(fin, dur);
-            return result(fin);
+        for (int jh = R; jh >= 1; jh -= G) {
+            const int jl = jh - G + 1 > 1 ? jh - G + 1 : 1;
+            if (!(act & (((2ull << jh) - 1) & ~((1ull << jl) - 1)))) continue;
+#pragma unroll
+            for (int j = jh; j >= jl; --j) {
+                V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+                V ready = j > 1 ? fin[j - 1] : (V)0;
+                V nv = (idle > ready ? idle : ready) + dur[j];
+                fin[j] = keep_or_take(fin[j], nv, (act >> j) & 1 ? ~0u : 0u);
+            }
         }
-    }
-    const int sweeps = M + 2 * R - 2;
-    const unsigned width = (unsigned)(M - 1);
-    for (int t = 1; t <= sweeps; ++t) {
+#pragma unroll
+        for (int jh = J; jh >= R + 1; jh -= G) {
+            const int jl = jh - G + 1 > R + 1 ? jh - G + 1 : R + 1;
+            if (!(act & (((2ull << jh) - 1) & ~((1ull << jl) - 1)))) continue;
+#pragma unroll
+            for (int j = jh; j >= jl; --j) {
+                V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+                V ready = j == R + 1 ? finR_prev : fin[j - 1];
+                V nv = (idle > ready ? idle : ready) + dur[j];
+                fin[j] = keep_or_take(fin[j], nv, (act >> j) & 1 ? ~0u : 0u);
+            }
+        }
+    } else {
         // j is in [t-M+1, t] iff (unsigned)(j - (t-M+1)) <= M-1; kept in a vector register so
         // that the tests run on the vector unit next to the arithmetic
+        const unsigned width = (unsigned)(M - 1);
         int jlo = t - M + 1;
         asm volatile("" : "+v"(jlo));
-        const V finR_prev = fin[R];
 #pragma unroll
         for (int j = R; j >= 1; --j) {
             V idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
@@ -328,20 +367,115 @@ __device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S -
             fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
         }
     }
+}
+
+// The first M sweeps of a pipeline that never fills (M <= J-2): blocks 1..t.
+template <int S, typename V, int T>
+__device__ __forceinline__ void ramp_up_to(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1], int M) {
+    if constexpr (T <= 4 * S - 5) {
+        if (T > M) return;
+        sweep_blocks<S, V, 1, T>(fin, dur);
+        ramp_up_to<S, V, T + 1>(fin, dur, M);
+    }
+}
+
+// The last sweeps of a pipeline, blocks U+1..J for every U+1 >= lo.
+template <int S, typename V, int U>
+__device__ __forceinline__ void ramp_down_from(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1], int lo) {
+    if constexpr (U <= 4 * S - 4) {
+        if (U + 1 >= lo) sweep_blocks<S, V, U + 1, 4 * S - 3>(fin, dur);
+        ramp_down_from<S, V, U + 1>(fin, dur, lo);
+    }
+}
+
+// Sweeps M+1..J of a pipeline that never fills, for a microbatch count known at compile time:
+// the window of M blocks moves up by one block per sweep.
+template <int S, typename V, int M, int T>
+__device__ __forceinline__ void slide_window(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1]) {
+    if constexpr (T <= 4 * S - 3) {
+        sweep_blocks<S, V, T - M + 1, T>(fin, dur);
+        slide_window<S, V, M, T + 1>(fin, dur);
+    }
+}
+
+// Picks the instance of slide_window for the run-time microbatch count m (1 <= m <= J-2).
+template <int S, typename V, int M>
+__device__ __forceinline__ void slide_window_for(V (&fin)[4 * S - 3 + 1], const V (&dur)[4 * S - 3 + 1], int m) {
+    if constexpr (M <= 4 * S - 5) {
+        if (m == M) {
+            slide_window<S, V, M, M + 1>(fin, dur);
+            return;
+        }
+        slide_window_for<S, V, M + 1>(fin, dur, m);
+    }
+}
+
+template <int S, typename V, typename Result>
+__device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S - 3 + 1], int M, Result result) {
+    constexpr int R = 2 * S - 1, J = 2 * R - 1;
+    V dur[J + 1], fin[J + 1];
+#pragma unroll
+    for (int j = 1; j <= J; ++j) { dur[j] = (V)dur64[j]; fin[j] = 0; }
+    dur[0] = fin[0] = 0;
+    if constexpr (S <= 8) {
+        if (M >= J - 1) {
+            ramp_up<S, V, 1>(fin, dur);
+            for (int t = J; t <= M; ++t) sweep_blocks<S, V, 1, J>(fin, dur);
+            ramp_down<S, V, 1>(fin, dur);
+        } else {
+            ramp_up_to<S, V, 1>(fin, dur, M);                                   // sweeps 1..M
+            if constexpr (sizeof(V) == 4) slide_window_for<S, V, 1>(fin, dur, M);       // sweeps M+1..J
+            else for (int t = M + 1; t <= J; ++t) sweep_selected<S, V>(fin, dur, t, M);
+            ramp_down_from<S, V, 1>(fin, dur, J - M + 2);                       // sweeps J+1..J+M-1
+        }
+        return result(fin);
+    }
+    const int sweeps = M + 2 * R - 2;
+    for (int t = 1; t <= sweeps; ++t) sweep_selected<S, V>(fin, dur, t, M);
     return result(fin);
 }
 
+// Microbatch counts handled by one workgroup of k_makespan_regs (one wave each).
+#define MK_REGS_WAVES 4
+
+// One wave per (64 candidates, microbatch count).  The waves of a workgroup serve the same 64
+// candidates for up to MK_REGS_WAVES counts: the scattered table lookups of the gather, which
+// cost more than the schedule itself for small M, are split between them by stage and
+// exchanged through LDS (dynamic, (J + 1 + waves) * 64 * 8 bytes; none for a single wave).
 template <int S>
-__global__ __launch_bounds__(64) void k_makespan_regs(mk_args a) {
-    constexpr int J = 4 * S - 3;
-    const int lane = threadIdx.x;
+__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a) {
+    constexpr int R = 2 * S - 1, J = 4 * S - 3;
+    extern __shared__ __align__(16) long long sh_dur[];  // [J+1][64] durations, [64] worst
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const long long c = (long long)blockIdx.x * 64 + lane;
     const bool live = c < a.N;
     long long dur[J + 1];
     long long worst;
-    const int fault = gather_durations<S>(a, c, live, worst, [&](int j, long long d) { dur[j] = d; });
-    // blockIdx.y selects the microbatch count: the counts run side by side, not in a loop
-    const int q = blockIdx.y;
+    int fault;
+    if (nw == 1) {
+        fault = gather_durations<S>(a, c, live, worst, [&](int j, long long d) { dur[j] = d; });
+    } else {
+        long long mine;
+        fault = gather_durations<S>(a, c, live, mine,
+                                    [&](int j, long long d) { sh_dur[j * 64 + lane] = d; },
+                                    [](long long, long long) {}, w, nw);
+        sh_dur[(J + 1) * 64 + w * 64 + lane] = mine;
+        __syncthreads();
+#pragma unroll
+        for (int j = 1; j <= J; ++j) dur[j] = sh_dur[j * 64 + lane];
+        worst = 0;
+        for (int v = 0; v < nw; ++v) {
+            const long long o = sh_dur[(J + 1) * 64 + v * 64 + lane];
+            worst = o > worst ? o : worst;
+        }
+    }
+    // The wave's microbatch count: the counts run side by side, not in a loop.  (Wave w takes
+    // count w in every workgroup: the hardware already starts successive workgroups of a
+    // compute unit on successive SIMDs, so the waves with the largest count spread out; a
+    // rotation of the assignment on top of that was measured to undo it.)
+    const int q = blockIdx.y * nw + w;
+    if (q >= a.nM) return;
     const int M = a.Ms[q];
     const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
     // 32-bit arithmetic if no finish time of any lane can reach 2^31
@@ -580,7 +714,9 @@ static long long regs_waves(long long N) { return (N + 63) / 64; }
 template <int S>
 static int launch_regs(const mk_args &a, hipStream_t st) {
     unsigned grid = (unsigned)regs_waves(a.N);
-    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, a.nM), dim3(64), 0, st, a);
+    const int nw = a.nM < MK_REGS_WAVES ? a.nM : MK_REGS_WAVES;
+    const size_t lds = nw > 1 ? (size_t)(4 * S - 3 + 1 + nw) * 64 * 8 : 0;
+    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 

@@ -285,6 +285,25 @@ def test_makespan_any_valid_plan(ppo, G, seed, L, D, S, N):
         np.testing.assert_array_equal(T, T0)
 
 
+@pytest.mark.parametrize("S", [2, 3, 4, 5, 6, 7, 8, 11])
+def test_makespan_every_microbatch_count_around_pipeline_fill(ppo, G, S):
+    # M = 1 .. 4S-1: pipelines that never fill (M < 4S-4, one specialised middle phase per M
+    # for S <= 8), the boundary, and full ones
+    seed, L, D, N = 700 + S, 3 * S + 7, S + 1, 150
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1, hi_time=9, hi_act=700)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    b = random_bounds(rng, N, S, L)
+    PF, PB, XF, XB = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(PF, PB, XF, XB)
+    for M in range(1, 4 * S):
+        say("makespan S", S, "M", M)
+        st, T = g.makespan(M, b)
+        rc, T0 = ppo.schedule_makespan(L, D, S, N, M, PF, PB, XF, XB, w.orderings, b)
+        assert st == 0 and rc == 0
+        np.testing.assert_array_equal(T, T0)
+
+
 @pytest.mark.parametrize("name,N,M", [("hetero", 500, 32), ("stress", 200, 128)])
 def test_makespan_large_shapes_subset(ppo, G, name, N, M):
     w = workloads.CONFIGS[name](N=N)
@@ -412,6 +431,18 @@ def test_best_plan_multi_full_configs(ppo, G, name):
     assert g.prefix() == 0
     say("best_plan_multi", name, w.Ms)
     check_best_multi(ppo, g, w, w.Ms, oracle_tables(ppo, w))
+
+
+@pytest.mark.parametrize("Ms", [(7,), (3, 40), (40, 3, 9), (5, 6, 7, 8), (2, 30, 4, 50, 6),
+                                (9, 8, 7, 6, 5, 4), (1, 1, 33, 33, 2, 2, 64)])
+def test_best_plan_multi_list_lengths(ppo, G, Ms):
+    # the waves of a workgroup share one gather for up to four counts: whole and partial groups
+    w = workloads.random_small(811, 40, 7, 6, 333, zero_frac=0.1, hi_time=9, hi_act=900)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("best_plan_multi list", Ms)
+    check_best_multi(ppo, g, w, Ms, tables)
 
 
 @pytest.mark.parametrize("seed,L,D,S,N", SMALL)
