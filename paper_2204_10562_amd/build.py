@@ -9,30 +9,55 @@ _ROOT = os.path.dirname(_PKG)
 LIB_PATH = os.environ.get("PP_LIBPP") or os.path.join(_PKG, "libpp.so")
 
 HIPCC_FLAGS = [
-    "-shared", "-fPIC", "--offload-arch=gfx950", "-O3", "-std=c++17",
+    "-fPIC", "--offload-arch=gfx950", "-O3", "-std=c++17",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
+OBJ_DIR = os.path.join(_ROOT, "_build")
 
 
 def sources():
     return sorted(glob.glob(os.path.join(_PKG, "csrc", "*.hip")))
 
 
-def build_libpp(verbose=False):
-    """Compile every HIP source under csrc/ into paper_2204_10562_amd/libpp.so."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(_ROOT, "include"),
-                                   "-I", os.path.join(_PKG, "csrc")] + sources() + ["-o", LIB_PATH]
+def _headers():
+    return glob.glob(os.path.join(_PKG, "csrc", "*.h")) + glob.glob(os.path.join(_ROOT, "include", "*.h"))
+
+
+def _run(cmd, verbose):
     if verbose:
-        print(" ".join(cmd))
+        print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build_libpp(verbose=False, incremental=False):
+    """Compile every HIP source under csrc/ (one hipcc per file, side by side) and link them
+    into paper_2204_10562_amd/libpp.so.  incremental=True keeps objects newer than their
+    source and every header."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_PKG, "csrc")]
+    newest_header = max(os.path.getmtime(h) for h in _headers())
+    jobs, objs = [], []
+    for src in sources():
+        obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+        objs.append(obj)
+        fresh = (incremental and os.path.exists(obj)
+                 and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header))
+        if not fresh:
+            jobs.append([hipcc, "-c"] + HIPCC_FLAGS + inc + [src, "-o", obj])
+    workers = max(1, min(len(jobs), os.cpu_count() or 1, 8))
+    with ThreadPoolExecutor(workers) as pool:
+        list(pool.map(lambda c: _run(c, verbose), jobs))
+    _run([hipcc, "-shared"] + HIPCC_FLAGS + objs + ["-o", LIB_PATH], verbose)
     return LIB_PATH
 
 
 if __name__ == "__main__":
-    print(build_libpp(verbose=True))
+    import sys
+    print(build_libpp(verbose=True, incremental="--incremental" in sys.argv))

@@ -255,6 +255,10 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         for (int j = 0; j < NT; ++j) x[j] = xp[j];
     };
 
+    // prio_until[k-1]: the last candidate with at least k quarters of the chunk still to do
+    long long prio_until[3];
+    for (int k = 1; k <= 3; ++k) prio_until[k - 1] = c1 - ((long long)k * a.chunk + 3) / 4;
+
     // first candidate of the chunk (bad ones are recorded and skipped)
     long long c = c0;
     int first = inspect(v_o);
@@ -280,10 +284,11 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         if (a.prio) {
             // Of the waves that share a SIMD the one with the larger share of its chunk still to
             // do issues first, so that they finish together and none runs alone at the end.
-            const int left = (int)(((c1 - c) * 4) / a.chunk);
-            if (left >= 3) __builtin_amdgcn_s_setprio(3);
-            else if (left == 2) __builtin_amdgcn_s_setprio(2);
-            else if (left == 1) __builtin_amdgcn_s_setprio(1);
+            // (quarters still to do = floor(4 (c1 - c) / chunk), compared against thresholds
+            // worked out once: a division here costs as much as a tenth of a row)
+            if (c <= prio_until[2]) __builtin_amdgcn_s_setprio(3);
+            else if (c <= prio_until[1]) __builtin_amdgcn_s_setprio(2);
+            else if (c <= prio_until[0]) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
         const bool more = c + 1 < c1;
