@@ -29,6 +29,8 @@ struct tc_pair { long long T, c; };
 struct mk_args {
     int L, D, S, nM;
     int Ms[PP_MAX_M_LIST];  // microbatch counts; the plans are evaluated once per entry
+    // k_makespan_regs: wave slot i (blockIdx.y * waves + wave) serves count Ms[order[i]]
+    unsigned char order[PP_MAX_M_LIST];
     long long N;
     const long long *PF, *PB, *XF, *XB;
     const int *orderings;  // NULL = all D! orderings, candidate index = lexicographic rank
@@ -470,12 +472,14 @@ __global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a)
             worst = o > worst ? o : worst;
         }
     }
-    // The wave's microbatch count: the counts run side by side, not in a loop.  (Wave w takes
-    // count w in every workgroup: the hardware already starts successive workgroups of a
-    // compute unit on successive SIMDs, so the waves with the largest count spread out; a
-    // rotation of the assignment on top of that was measured to undo it.)
-    const int q = blockIdx.y * nw + w;
-    if (q >= a.nM) return;
+    // The wave's microbatch count: the counts run side by side, not in a loop, largest count
+    // in wave 0 so that the longest wave is placed first.  Wave w takes the same
+    // slot in every workgroup: the hardware already starts successive workgroups of a compute
+    // unit on successive SIMDs, so the waves with the largest count spread out; a rotation of
+    // the assignment on top of that was measured to undo it.
+    const int slot = blockIdx.y * nw + w;
+    if (slot >= a.nM) return;
+    const int q = a.order[slot];
     const int M = a.Ms[q];
     const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
     // 32-bit arithmetic if no finish time of any lane can reach 2^31
@@ -716,7 +720,14 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
     unsigned grid = (unsigned)regs_waves(a.N);
     const int nw = a.nM < MK_REGS_WAVES ? a.nM : MK_REGS_WAVES;
     const size_t lds = nw > 1 ? (size_t)(4 * S - 3 + 1 + nw) * 64 * 8 : 0;
-    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, a);
+    mk_args b = a;
+    // wave slots in descending order of the microbatch count (stable: equal counts keep theirs)
+    for (int i = 0; i < PP_MAX_M_LIST; ++i) b.order[i] = (unsigned char)i;
+    for (int i = 1; i < a.nM; ++i)
+        for (int k = i; k > 0 && a.Ms[b.order[k]] > a.Ms[b.order[k - 1]]; --k) {
+            unsigned char t = b.order[k]; b.order[k] = b.order[k - 1]; b.order[k - 1] = t;
+        }
+    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, b);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
