@@ -44,7 +44,7 @@ __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long l
 
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.
 struct pp_ws_layout {
-    size_t hdr, p32, x32, xkt, ord, arg, bounds, C, T, part, total;
+    size_t hdr, p32, x32, xkt, xct, ord, arg, bounds, C, T, part, total;
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
@@ -60,6 +60,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.p32 = off;    off += pp_align256((size_t)(L + 17) * 4);  // padded to a whole tile
     w.x32 = off;    off += pp_align256((size_t)D * D * L * 4);
     w.xkt = off;    off += pp_align256((size_t)D * D * 8 * w.nt * 4);
+    w.xct = off;    off += pp_align256((size_t)D * D * 16 * ((w.nt + 1) / 2) * 4);
     w.ord = off;    off += pp_align256((size_t)N * S * 4);
     w.slots = (int)(N < PP_DP_SLOTS ? N : PP_DP_SLOTS);
     w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 128) * 2);  // rows padded to 128 cells

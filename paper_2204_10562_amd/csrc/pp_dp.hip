@@ -28,7 +28,7 @@ struct pack_args {
     size_t total;  // D*D*L
     const long long *PF, *PB, *XF, *XB;
     pp_ws_header *hdr;
-    int *p32, *x32, *xkt, *ord;  // ord != NULL: write all D! orderings in lexicographic order
+    int *p32, *x32, *xkt, *xct, *ord;  // ord != NULL: write all D! orderings in lexicographic order
 };
 
 // x32[link*L + k] = XF + XB at cut position k (k layers before the cut), k = 1..L-1; entry 0
@@ -61,6 +61,25 @@ __device__ void pack_xkt(const pack_args &a, unsigned first, unsigned stride) {
             key = (int)(((unsigned)x << a.K) | (unsigned)k);
         }
         a.xkt[i] = key;
+    }
+}
+
+// The same keys once more in the layout of the cells a lane holds after a row's reduction
+// (lane (a, b) holds the cells l = 8 (h H + r) + a + 1, h = b / 4, r = 0..H-1, H = ceil(nt / 2)):
+// xct[((link*8 + a)*2 + h)*H + r] = (x << K) | l, infinite for l >= L or a tile beyond nt.
+__device__ void pack_xct(const pack_args &a, unsigned first, unsigned stride) {
+    if (!a.nt) return;
+    const unsigned H = (unsigned)(a.nt + 1) / 2, per_link = 16u * H, n = (unsigned)a.D * a.D * per_link;
+    for (unsigned i = first; i < n; i += stride) {
+        unsigned link = i / per_link, r0 = i - link * per_link;
+        unsigned la = r0 / (2 * H), h = (r0 / H) & 1u, r = r0 % H;
+        int tile = (int)(h * H + r), l = 8 * tile + (int)la + 1;
+        int key = PP_INF32;
+        if (tile < a.nt && l < a.L) {
+            long long x = a.XF[(size_t)link * a.L + l - 1] + a.XB[(size_t)link * a.L + l - 1];
+            key = (int)(((unsigned)x << a.K) | (unsigned)l);
+        }
+        a.xct[i] = key;
     }
 }
 
@@ -127,6 +146,7 @@ __global__ __launch_bounds__(256) void k_prep(pack_args a) {
         unsigned long long mx = pack_x(a, first, stride);
         m = mx > m ? mx : m;
         pack_xkt(a, first, stride);
+        pack_xct(a, first, stride);
         for (int off = 32; off; off >>= 1) {
             unsigned long long o = __shfl_xor(m, off);
             m = o > m ? o : m;
@@ -156,6 +176,7 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
     a.p32 = (int *)(base + lay.p32);
     a.x32 = (int *)(base + lay.x32);
     a.xkt = (int *)(base + lay.xkt);
+    a.xct = (int *)(base + lay.xct);
     a.ord = orderings ? NULL : (int *)(base + lay.ord);
     *ord = orderings ? orderings : (const int32_t *)(base + lay.ord);
     int grid = PP_PACK_BLOCKS;
@@ -248,6 +269,7 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         t.L = L; t.D = D; t.S = S; t.K = a.K; t.N = N;
         t.validate = a.validate;
         t.xkt = (const int *)(base + lay.xkt);
+        t.xct = (const int *)(base + lay.xct);
         int cus = 256;
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||

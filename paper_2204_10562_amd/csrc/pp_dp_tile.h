@@ -15,6 +15,7 @@ struct dp_tile_args {
     int hoist;        // keep the candidate-independent difference keys in registers
     int prio;         // waves raise their issue priority with the share of their chunk still to do
     const int *xkt;   // [link][b][j] keys ((XF+XB) << K) | k for k = 8j+b, infinite if k == 0 or k >= L
+    const int *xct;   // [link][a][h][r] the same keys for the cells l = 8(hH+r)+a+1, H = ceil(nt/2)
     dp_args g;        // tables, outputs and the generic fallback's arguments
 };
 

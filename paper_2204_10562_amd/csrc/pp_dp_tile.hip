@@ -30,6 +30,7 @@
 #define DPP_QUAD_XOR1 0xB1     // quad_perm:[1,0,3,2]
 #define DPP_QUAD_XOR2 0x4E     // quad_perm:[2,3,0,1]
 #define DPP_HALF_MIRROR 0x141  // row_half_mirror: lane b <-> 7-b within each 8 lanes
+#define DPP_ROW_ROR8 0x128     // row_ror:8: lane <-> lane + 8 within each 16 lanes
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
@@ -151,6 +152,26 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         // index 0 (no layers before the split) is infeasible in every row
         for (int n = lane; n < S; n += 64) rows[n * RS] = PP_INF32;
         lds_sync();
+    }
+
+    // FUSE: cell (S-1, L), the only cell of the last row that is needed, is computed at the
+    // end of row S-2 from that row's cells while they are still in registers: after the
+    // reduction a lane holds the cells l = 8 (h H + r) + a + 1 (h = b / 4, r = 0..H-1), and
+    // DL[r] = ((P[L] - P[l]) << K) | l (infinite for l >= L) is the difference key of cell L
+    // against the split after l layers.
+    constexpr bool FUSE = HOIST;
+    constexpr int HC = (NT + 1) / 2;
+    int DL[FUSE ? HC : 1];
+    if (FUSE) {
+        const int plk = a.g.p32[L];
+#pragma unroll
+        for (int r = 0; r < HC; ++r) {
+            const int tile = (lb >> 2) * HC + r, l = 8 * tile + la + 1;
+            int d = ((plk - a.g.p32[l]) << K) | l;
+            d = (tile < NT && l < L) ? d : PP_INF32;
+            asm volatile("" : "+v"(d));
+            DL[r] = d;
+        }
     }
 
     // the difference key of block (i, j)
@@ -296,19 +317,39 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         int first_n = -2, v_link_n = 0;  // next candidate: -2 none, -1 bad ordering
         bool flush_after = false;
 
+        // candidate finished with key `top` in cell (S-1, L): remember it and the arena rows of
+        // its path
+        auto finish_candidate = [&](int top) __attribute__((always_inline)) {
+            if (lane == pending) v_top = top;
+            if (lane < S) slots[pending * S + lane] = (unsigned char)v_cur;
+            if (stages && lane < S) tops[pending * S + lane] = v_tops;
+            ++pending;
+        };
+
         // One DP row.  xc holds this row's channel keys; the keys of the row computed next are
         // fetched into xf while this one is computed.  After the candidate's last row that is
         // the first row of the next candidate (looked at here), or, if there is none, this
         // row's keys once more.
         auto row = [&](int n, int (&xc)[NT], int (&xf)[NT]) __attribute__((always_inline)) {
             int next_link = __builtin_amdgcn_readlane(v_link, n + 1 < S ? n + 1 : n);
-            if (n == S - 1 && more) {
+            // the candidate ends with this row: the last row itself, or row S-2 with cell
+            // (S-1, L) worked out at its end
+            const bool fused = FUSE && n == S - 2;
+            int xl[HC];
+            if (fused) {
+                const int *xp = a.xct + ((size_t)next_link * 16 + (la * 2 + (lb >> 2))) * HC;
+#pragma unroll
+                for (int r = 0; r < HC; ++r) xl[r] = xp[r];
+            }
+            if ((n == S - 1 || fused) && more) {
                 v_prev = v_o;
                 have_prev = true;
                 first_n = inspect(v_on);
                 if (first_n >= 0) {
-                    // rows first_n..S-2 need arena rows; one more pending candidate needs a lane
-                    if (arena_used + (S - 1 - first_n) > DPT_ARENA_ROWS || pending + 2 > DPT_PENDING) {
+                    // rows first_n..S-2 need arena rows (and so does this row, if it is row
+                    // S-2); one more pending candidate needs a lane
+                    if (arena_used + (fused ? 1 : 0) + (S - 1 - first_n) > DPT_ARENA_ROWS ||
+                        pending + 2 > DPT_PENDING) {
                         flush_after = true;
                         first_n = 1;
                     }
@@ -370,6 +411,22 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                     for (int i = 0; i < H; ++i)
                         if (i + H < NT || lb == 0) arow[8 * i + wofs] = (unsigned char)acc[i];
                 }
+                if (fused) {
+                    int m = PP_INF32;
+#pragma unroll
+                    for (int r = 0; r < HC; ++r) {
+                        int wk;
+                        asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(wk) : "s"(kmask), "v"(xl[r]), "v"(acc[r]));
+                        m = imin(m, imax(imax(wk, xl[r]), DL[r]));
+                    }
+                    m = dpp_min<DPP_HALF_MIRROR>(m);  // the two halves of the row
+                    m = dpp_min<DPP_ROW_ROR8>(m);     // a and a + 1
+                    const int top = imin(imin(__builtin_amdgcn_readlane(m, 0), __builtin_amdgcn_readlane(m, 16)),
+                                         imin(__builtin_amdgcn_readlane(m, 32), __builtin_amdgcn_readlane(m, 48)));
+                    pairs += (unsigned long long)(L - (S - 1));
+                    ++nrows;
+                    finish_candidate(top);
+                }
                 lds_sync();
             } else {
                 // only W[S-1][L] is needed of the last row; L lies in tile NT-1
@@ -380,26 +437,23 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
                 v = min_over_b(v);
                 pairs += (unsigned long long)(L - n);
                 ++nrows;
-                const int top = __builtin_amdgcn_readlane(v, top_lane);
-                // candidate finished: remember its key and the arena rows of its path
-                if (lane == pending) v_top = top;
-                if (lane < S) slots[pending * S + lane] = (unsigned char)v_cur;
-                if (stages && lane < S) tops[pending * S + lane] = v_tops;
-                ++pending;
+                finish_candidate(__builtin_amdgcn_readlane(v, top_lane));
             }
         };
         // rows alternate between the two key buffers, so that no row has to copy them; only a
         // candidate with an odd number of rows moves the last fetch into xk once
         int xn[NT];
+        // (with FUSE the last row is a row of its own only when no other row is computed)
+        const int end = (FUSE && first <= S - 2) ? S - 1 : S;
         for (int n = first;;) {
             row(n, xk, xn);
-            if (++n >= S) {
+            if (++n >= end) {
 #pragma unroll
                 for (int j = 0; j < NT; ++j) xk[j] = xn[j];
                 break;
             }
             row(n, xn, xk);
-            if (++n >= S) break;
+            if (++n >= end) break;
         }
 
         if (flush_after) flush();
