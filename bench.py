@@ -25,7 +25,7 @@ ALU_PEAK_OPS = 256 * 4 * 16 * 2.4e9
 OPS_PER_PAIR = 3  # subtract, max, min on 32-bit keys per (cell, split) pair
 # HBM bytes per k_dp_tile<16> launch on the GPT workload: scaled FETCH_SIZE + WRITE_SIZE from
 # two rocprofv3 --pmc runs (profiles/dp_tile_gpt_hbm_traffic.txt)
-DP_TRAFFIC_BYTES = {"gpt": 3.53e6}
+DP_TRAFFIC_BYTES = {"gpt": 3.76e6}
 
 
 def log(*a):
