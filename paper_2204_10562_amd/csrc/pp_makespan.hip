@@ -14,12 +14,12 @@
 // candidate and all lanes run the same uniform loop.
 //
 // Two kernels: for S <= 16 the 4S-3 durations and finish times of a lane live in registers
-// (blocks unrolled; when the pipeline fills, the block ranges of the ramp-up, steady and
-// ramp-down sweeps are compile-time constants, otherwise each update is selected by a
-// per-lane test of the sweep's window of working blocks; 32-bit when the bound
-// (M+4S-4) * largest block of Lemma 1 fits, else 64-bit, decided per wave; several
-// microbatch counts run side by side in one launch); for larger S they live in the lane's
-// own LDS column.
+// (blocks unrolled; for S <= 8 the block ranges of the ramp-up, steady or sliding-window and
+// ramp-down sweeps are compile-time constants, otherwise every block is computed in every
+// sweep and its update kept or dropped; 32-bit when the bound (M+4S-4) * largest block of
+// Lemma 1 fits, else 64-bit, decided per wave; several microbatch counts run side by side,
+// one wave each, in workgroups that share the gather of the block durations); for larger S
+// they live in the lane's own LDS column.
 // When asked to, each wave also reduces (T, candidate) to its minimum, and a one-workgroup
 // kernel launched next reduces the per-wave minima to the winner record.
 #include "pp_common.h"
