@@ -10,9 +10,10 @@
 // The term ((P[l] - P[k]) << K) | k does not depend on the candidate or the row: every lane
 // computes its NT(NT+1)/2 values once (invalid pairs k >= l hold the infinite key) and keeps
 // them in registers for the lifetime of the wave.  A row then costs, per (cell, split) pair,
-// one max and half a three-operand min, plus a 3-step DPP min over the 8 lanes that share a
-// cell and 2 operations per split to build g.  The rows of the current candidate live in LDS,
-// one private slice per wave, so there are no barriers.
+// one max and half a three-operand min, plus a DPP min over the 8 lanes that share a cell
+// (2 operations per tile) and 2 operations per split to build g.  The rows of the current
+// candidate live in LDS, one private slice per wave, so there are no barriers.  The single
+// cell of the last row that is needed is worked out at the end of row S-2, from registers.
 //
 // Row n of a candidate depends only on the first n+1 devices of its ordering.  A wave walks
 // a contiguous chunk of candidates and recomputes only the rows from the first position in
