@@ -31,6 +31,10 @@ struct mk_args {
     int Ms[PP_MAX_M_LIST];  // microbatch counts; the plans are evaluated once per entry
     // k_makespan_regs: wave slot i (blockIdx.y * waves + wave) serves count Ms[order[i]]
     unsigned char order[PP_MAX_M_LIST];
+    // k_makespan_regs8: nonzero = blockIdx.z + 1 is the number of stages xi, the plan with xi
+    // stages is read from the triangular bounds array and T goes to column xi-1 (S, bnd_off and
+    // t_off are then ignored)
+    int all_xi;
     long long N;
     const long long *PF, *PB, *XF, *XB;
     const int *orderings;  // NULL = all D! orderings, candidate index = lexicographic rank
@@ -90,6 +94,8 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
                                                 long long &worst, Put put, Last last,
                                                 int part = 0, int parts = 1) {
     const int S = ST ? ST : a.S, L = a.L, D = a.D, R = 2 * S - 1;
+    // (k_makespan_regs8 with all_xi: the plan with ST stages of the triangular array)
+    const int bnd_off = (ST && a.all_xi) ? ST * (ST - 1) / 2 : a.bnd_off;
     int fault = 0;
     if (live) {
         if (a.orderings) {
@@ -102,7 +108,7 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
         }
         int prev = 0;
         for (int n = 0; n < S; ++n) {
-            int e = a.bounds[c * a.bnd_stride + a.bnd_off + n];
+            int e = a.bounds[c * a.bnd_stride + bnd_off + n];
             if (e <= prev || e > L) fault |= PP_FAULT_BOUNDS;
             prev = e;
         }
@@ -117,7 +123,7 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
         long long F = 0, Bk = 0, cf = 0, cb = 0;
         if (live && !fault) {
             int o_n = a.orderings ? a.orderings[c * a.ord_stride + n] : pp_unrank_next(D, n, rem, used);
-            int e = a.bounds[c * a.bnd_stride + a.bnd_off + n];
+            int e = a.bounds[c * a.bnd_stride + bnd_off + n];
             if (parts == 1 || n % parts == part) {
                 F = a.PF[e] - a.PF[e_prev];
                 Bk = a.PB[e] - a.PB[e_prev];
@@ -166,10 +172,10 @@ __device__ __forceinline__ int overflow_fault(long long worst, int M, int S) {
 // final reduction, but the returned atomics and arrival counters that needs cost more than
 // the schedule itself once a launch has thousands of waves.)
 __device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool live, int fault,
-                                     long long T, long long wave_id, long long n_waves) {
+                                     long long T, long long wave_id, long long n_waves, int t_off) {
     if (live) {
         if (fault) { T = PP_INF64; pp_raise(a.status, fault); }
-        if (a.T_out) a.T_out[((long long)q * a.N + c) * a.t_stride + a.t_off] = T;
+        if (a.T_out) a.T_out[((long long)q * a.N + c) * a.t_stride + t_off] = T;
     }
     if (!a.part) return;
     tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
@@ -445,7 +451,7 @@ __device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S -
 // cost more than the schedule itself for small M, are split between them by stage and
 // exchanged through LDS (dynamic, (J + 1 + waves) * 64 * 8 bytes; none for a single wave).
 template <int S>
-__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a) {
+__device__ __forceinline__ void regs_body(const mk_args &a) {
     constexpr int R = 2 * S - 1, J = 4 * S - 3;
     extern __shared__ __align__(16) long long sh_dur[];  // [J+1][64] durations, [64] worst
     const int lane = threadIdx.x & 63;
@@ -488,7 +494,30 @@ __global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a)
     long long T;
     if (__all(narrow)) T = sweep_regs<S, int>(dur, M, [](const int (&fin)[J + 1]) { return (long long)fin[J]; });
     else T = sweep_regs<S, long long>(dur, M, [](const long long (&fin)[J + 1]) { return fin[J]; });
-    emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x);
+    emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x, a.all_xi ? S - 1 : a.t_off);
+}
+
+// 9 <= S <= 16: one kernel per S.
+template <int S>
+__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a) {
+    regs_body<S>(a);
+}
+
+// S <= 8: one kernel for all of them, so that the stage-count search can evaluate the plans of
+// every stage count xi = 1..S in a single launch (blockIdx.z = xi - 1) instead of S launches
+// whose fixed costs add up.
+__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs8(mk_args a) {
+    // (the arguments stay untouched: a modified copy would live in scratch memory)
+    switch (a.all_xi ? (int)blockIdx.z + 1 : a.S) {
+        case 1: regs_body<1>(a); break;
+        case 2: regs_body<2>(a); break;
+        case 3: regs_body<3>(a); break;
+        case 4: regs_body<4>(a); break;
+        case 5: regs_body<5>(a); break;
+        case 6: regs_body<6>(a); break;
+        case 7: regs_body<7>(a); break;
+        case 8: regs_body<8>(a); break;
+    }
 }
 
 // ---------------------------------------------------------------- replicated stages, S <= 16
@@ -666,7 +695,7 @@ __global__ __launch_bounds__(64) void k_makespan_mid(mk_args a) {
                 fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
             }
         }
-        emit(a, q, c, live, fq, (long long)fin[J], blockIdx.x, gridDim.x);
+        emit(a, q, c, live, fq, (long long)fin[J], blockIdx.x, gridDim.x, a.t_off);
     }
 }
 
@@ -709,17 +738,18 @@ __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
     }
     // with fewer than 64 lanes the arg-min would need another reduction; the host only asks
     // for it when W == 64
-    emit(a, q, c, live, fq, fin[(size_t)(J - 1) * W], blockIdx.x, gridDim.x);
+    emit(a, q, c, live, fq, fin[(size_t)(J - 1) * W], blockIdx.x, gridDim.x, a.t_off);
   }
 }
 
 static long long regs_waves(long long N) { return (N + 63) / 64; }
 
+// S = 0: the kernel for all S <= 8 (a.S, or every stage count 1..a.S if a.all_xi is set).
 template <int S>
 static int launch_regs(const mk_args &a, hipStream_t st) {
     unsigned grid = (unsigned)regs_waves(a.N);
     const int nw = a.nM < MK_REGS_WAVES ? a.nM : MK_REGS_WAVES;
-    const size_t lds = nw > 1 ? (size_t)(4 * S - 3 + 1 + nw) * 64 * 8 : 0;
+    const size_t lds = nw > 1 ? (size_t)(4 * (S ? S : a.S) - 3 + 1 + nw) * 64 * 8 : 0;
     mk_args b = a;
     // wave slots in descending order of the microbatch count (stable: equal counts keep theirs)
     for (int i = 0; i < PP_MAX_M_LIST; ++i) b.order[i] = (unsigned char)i;
@@ -727,7 +757,11 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
         for (int k = i; k > 0 && a.Ms[b.order[k]] > a.Ms[b.order[k - 1]]; --k) {
             unsigned char t = b.order[k]; b.order[k] = b.order[k - 1]; b.order[k - 1] = t;
         }
-    hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, b);
+    if constexpr (S == 0)
+        hipLaunchKernelGGL(k_makespan_regs8, dim3(grid, (a.nM + nw - 1) / nw, a.all_xi ? a.S : 1),
+                           dim3(64 * nw), lds, st, b);
+    else
+        hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, b);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
@@ -756,9 +790,9 @@ static int lds_lanes(int S) {
 // Register kernel for a.S <= 16, LDS kernel beyond.  With a.part set the LDS kernel must run
 // full waves (lds_lanes(a.S) == 64).
 static int launch_makespan(const mk_args &a, hipStream_t st) {
+    if (a.S <= 8) return launch_regs<0>(a, st);
     switch (a.S) {
 #define CASE(n) case n: return launch_regs<n>(a, st);
-        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
         CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
 #undef CASE
     }
@@ -785,7 +819,7 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
                        pp_result *out, const pp_ws_header *hdr, hipStream_t st) {
-    mk_args a;
+    mk_args a = {};
     a.L = L; a.D = D; a.S = S; a.N = N;
     a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
@@ -835,13 +869,13 @@ __global__ __launch_bounds__(64) void k_argmin(mk_args a) {
     // candidate; T_out must not be rewritten
     mk_args b = a;
     b.T_out = NULL;
-    emit(b, q, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x);
+    emit(b, q, v.c, v.c != INT64_MAX, 0, v.T, blockIdx.x, gridDim.x, b.t_off);
 }
 
 int pp_launch_argmin(int D, int S, int64_t N, const int64_t *T, const int64_t *C,
                      const int32_t *bounds, const int32_t *orderings, void *part,
                      pp_result *out, hipStream_t st) {
-    mk_args a;
+    mk_args a = {};
     a.L = 0; a.D = D; a.S = S; a.N = N;
     a.nM = 1;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = 1;
@@ -864,7 +898,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
                               pp_result *out, const pp_ws_header *hdr, hipStream_t st) {
-    mk_args a;
+    mk_args a = {};
     a.L = L; a.D = D; a.N = N; a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;
@@ -875,13 +909,22 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
     a.ord_stride = S; a.bnd_stride = (long long)S * (S + 1) / 2; a.t_stride = S; a.search = 0;
     a.reps = NULL; a.PA = a.actf = a.actb = a.bw = a.W = NULL; a.rout = NULL;
     a.variant = 0; a.hdr = hdr;
-    // one launch per stage count: the schedules of xi stages on the first xi devices
-    for (int xi = 1; xi <= S; ++xi) {
-        a.S = xi;
-        a.bnd_off = xi * (xi - 1) / 2;
-        a.t_off = xi - 1;
+    if (S <= 8) {
+        // the schedules of xi stages on the first xi devices, every xi in one launch
+        a.S = S; a.all_xi = 1;
+        a.bnd_off = 0; a.t_off = 0;
         int rc = launch_makespan(a, st);
         if (rc) return rc;
+        a.all_xi = 0;
+    } else {
+        // one launch per stage count
+        for (int xi = 1; xi <= S; ++xi) {
+            a.S = xi;
+            a.bnd_off = xi * (xi - 1) / 2;
+            a.t_off = xi - 1;
+            int rc = launch_makespan(a, st);
+            if (rc) return rc;
+        }
     }
     // smallest T over all (candidate, stage count) pairs, lowest c*S + xi-1 on ties
     mk_args m = a;
@@ -909,7 +952,7 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
                            const int32_t *reps, const int64_t *W, int64_t *T_out, int32_t *status,
                            void *part, pp_rep_result *out, hipStream_t st) {
     if (D > 16) return PP_ERR_INVALID_ARG;
-    mk_args a;
+    mk_args a = {};
     a.L = L; a.D = D; a.N = N; a.nM = 1;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = M;
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;
@@ -1027,7 +1070,7 @@ int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int 
                                const int64_t *PB, const int64_t *XF, const int64_t *XB,
                                const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                                int32_t *status, hipStream_t st) {
-    mk_args a;
+    mk_args a = {};
     a.L = L; a.D = D; a.S = S; a.N = N; a.nM = 1;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = M;
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;
