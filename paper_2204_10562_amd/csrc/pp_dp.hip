@@ -94,7 +94,9 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
         unsigned long long digits_hi = 0;
         if (D <= 12) {
             unsigned rem = (unsigned)c;
-            for (int i = 1; i <= D; ++i) {  // i = D - n
+#pragma unroll
+            for (int i = 1; i <= 12; ++i) {  // i = D - n; unrolled: divisions by constants
+                if (i > D) break;
                 unsigned q = rem / (unsigned)i;
                 unsigned long long dg = rem - q * (unsigned)i;
                 rem = q;

@@ -240,7 +240,16 @@ __global__ __launch_bounds__(256) void k_pick(mk_args a) {
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
     const tc_pair *part = a.part + (long long)q * a.n_part;
     tc_pair w = {PP_INF64, INT64_MAX};
-    for (long long i = tid; i < a.n_part; i += 256) w = tc_min(w, part[i]);
+    // four loads in flight per thread: the partials come straight from the kernel before, so
+    // each round is a trip to memory
+    const tc_pair none = {PP_INF64, INT64_MAX};
+    for (long long i = tid; i < a.n_part; i += 1024) {
+        tc_pair p0 = part[i];
+        tc_pair p1 = i + 256 < a.n_part ? part[i + 256] : none;
+        tc_pair p2 = i + 512 < a.n_part ? part[i + 512] : none;
+        tc_pair p3 = i + 768 < a.n_part ? part[i + 768] : none;
+        w = tc_min(tc_min(w, p0), tc_min(p1, tc_min(p2, p3)));
+    }
     w = wave_tc_min(w);
     if (lane == 0) sh[tid >> 6] = w;
     __syncthreads();
