@@ -165,12 +165,20 @@ int pp_schedule_makespan(int L, int D, int S, int64_t N, int M,
  *                    any backward item, microbatches in order (the schedule
  *                    Sec. II attributes to GPipe: all FP before any BP); the
  *                    last stage's forward and backward are separate items
+ *   PP_SCHED_ADDITIVE  stages are the only resources: the transfers over a
+ *                    stage's inbound link are part of that stage's passes
+ *                    (forward block of stage n: XF + F, backward block:
+ *                    B + XB; the last stage's merged block all four), so a
+ *                    microbatch passes 2S-1 blocks; Alg. 1's ordering and
+ *                    scheduling phases on that list ("stage cost = compute
+ *                    plus transfer" instead of overlapping channels)
  * Same arguments, limits and faults as pp_schedule_makespan; an unknown variant
  * returns PP_ERR_INVALID_ARG.
  */
 #define PP_SCHED_PE 0
 #define PP_SCHED_DUPLEX 1
 #define PP_SCHED_GPIPE 2
+#define PP_SCHED_ADDITIVE 3
 int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
                                  const int64_t *PF, const int64_t *PB,
                                  const int64_t *XF, const int64_t *XB,

@@ -957,13 +957,19 @@ int ppo_spp_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
  *   PPO_SCHED_GPIPE   every stage and channel serves all its forward items (microbatch
  *                     order) before any backward item: "all FP before any BP" (Sec. II).
  *                     The last stage's forward and backward are separate blocks here.
+ *   PPO_SCHED_ADDITIVE  stages are the only resources; the transfers into a stage (forward
+ *                     activations in, backward gradients out over the same link) are added
+ *                     to that stage's forward and backward blocks.  2S-1 blocks per
+ *                     microbatch, PE's ordering phase on that list.
  */
 int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F, const int64_t *B,
                              const int64_t *cf, const int64_t *cb) {
     if (S < 1 || S > PPO_MAX_STAGES || M < 1 || !F || !B || (S > 1 && (!cf || !cb))) return -1;
-    if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE) return -1;
+    if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE &&
+        variant != PPO_SCHED_ADDITIVE) return -1;
     const int merged = variant != PPO_SCHED_GPIPE;       /* last stage: one block or two */
-    const int J = merged ? 4 * S - 3 : 4 * S - 2;          /* blocks per microbatch */
+    const int folded = variant == PPO_SCHED_ADDITIVE;    /* transfers inside the stage blocks */
+    const int J = folded ? 2 * S - 1 : merged ? 4 * S - 3 : 4 * S - 2;  /* blocks per microbatch */
     const int nres = 3 * S;                                 /* stages, fwd channels, bwd channels */
     int *res = (int *)malloc((size_t)(J + 1) * sizeof(int));
     int *is_fwd = (int *)malloc((size_t)(J + 1) * sizeof(int));
@@ -984,7 +990,19 @@ int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F, const 
     /* the blocks a microbatch passes, in order: forward through the stages and channels,
      * then backward; resources: stage n = n, forward channel n = S + n, backward channel
      * n = 2S + n (or S + n as well when both directions share the channel) */
-    {
+    if (folded) {
+        int j = 0;
+        for (int n = 0; n < S; ++n) {
+            ++j; res[j] = n; is_fwd[j] = 1;
+            dur[j] = F[n] + (n ? cf[n] : 0);
+            if (n == S - 1) dur[j] += B[n] + (n ? cb[n] : 0);
+        }
+        for (int n = S - 2; n >= 0; --n) {
+            ++j; res[j] = n; is_fwd[j] = 0;
+            dur[j] = B[n] + (n ? cb[n] : 0);
+        }
+        if (j != J) goto out;
+    } else {
         int j = 0;
         for (int n = 0; n < S; ++n) {
             if (n) { ++j; res[j] = S + n; dur[j] = cf[n]; is_fwd[j] = 1; }
@@ -1066,7 +1084,8 @@ int ppo_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, i
     int rc = check_common(L, D, S, N, orderings);
     if (rc) return rc;
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PPO_ERR_INVALID_ARG;
-    if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE)
+    if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE &&
+        variant != PPO_SCHED_ADDITIVE)
         return PPO_ERR_INVALID_ARG;
     int32_t *own = NULL;
     if (!orderings) {

@@ -166,10 +166,17 @@ int64_t ppo_pe_makespan(int S, int M, const int64_t *F, const int64_t *B,
  *   PPO_SCHED_GPIPE   all forward passes before any backward pass on every
  *                     stage and channel (the GPipe schedule as Sec. II describes
  *                     it), microbatches in order; last stage's F and B separate
+ *   PPO_SCHED_ADDITIVE  no channels as resources: a stage's inbound transfers are
+ *                     part of its passes (forward block of stage n takes
+ *                     cf[n] + F[n], backward block B[n] + cb[n]; the last stage's
+ *                     merged block all four), so a microbatch passes 2S-1 blocks
+ *                     on S resources; ordering and scheduling phases of Alg. 1
+ *                     on that shorter list ("stage cost = compute plus transfer")
  * F, B per stage; cf, cb per channel with entry 0 unused. */
 #define PPO_SCHED_PE 0
 #define PPO_SCHED_DUPLEX 1
 #define PPO_SCHED_GPIPE 2
+#define PPO_SCHED_ADDITIVE 3
 int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F,
                              const int64_t *B, const int64_t *cf, const int64_t *cb);
 int ppo_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,

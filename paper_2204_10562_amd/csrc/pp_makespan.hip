@@ -1008,6 +1008,8 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
 //     microbatch on r-1) + forward time, resources 1..R, microbatch by microbatch; the backward
 //     wave the same in the other direction, each resource continuing from the end of its last
 //     forward item.  The last stage's forward and backward passes are separate items here.
+//   PP_SCHED_ADDITIVE: the sweeps of the PE scheduler over the 2S-1 stage blocks alone, each
+//     with the transfers over the stage's inbound link added to its duration.
 __global__ __launch_bounds__(64) void k_makespan_variant(mk_args a) {
     extern __shared__ long long sm[];
     const int lane = threadIdx.x, W = blockDim.x;
@@ -1049,25 +1051,48 @@ __global__ __launch_bounds__(64) void k_makespan_variant(mk_args a) {
         }
         T = fin[0];
     } else {
-        // the PE sweeps; even resources are channels: no partner block on the same resource
-        const int sweeps = M + 2 * R - 2;
+        // The PE sweeps over a list of 2Rv-1 blocks on Rv resources, block j and block 2Rv-j on
+        // the same one.  DUPLEX: the standard list, but even resources are channels, whose two
+        // blocks do not wait for each other.  ADDITIVE: the stage blocks only.
+        int Rv = R;
+        const bool pair_all = a.variant == PP_SCHED_ADDITIVE;
+        if (pair_all && S > 1) {
+            // stage n's forward block 2n+1 and backward block 2R-(2n+1) of the standard list
+            // take in the channel blocks 2n and 2R-2n; the merged block R both of its channel's.
+            // New list: forward of stage n at n+1, merged block at S, backward of stage n at
+            // 2S-1-n.  Built in the finish-time rows first, then moved.
+            for (int n = 0; n < S - 1; ++n) {
+                const int jf = 2 * n + 1, jb = 2 * R - jf;
+                long long df = dur[(size_t)(jf - 1) * W], db = dur[(size_t)(jb - 1) * W];
+                if (n) { df += dur[(size_t)(jf - 2) * W]; db += dur[(size_t)jb * W]; }
+                fin[(size_t)n * W] = df;
+                fin[(size_t)(2 * S - 2 - n) * W] = db;
+            }
+            fin[(size_t)(S - 1) * W] = dur[(size_t)(R - 1) * W] + dur[(size_t)(R - 2) * W] + dur[(size_t)R * W];
+            for (int j = 1; j <= 2 * S - 1; ++j) {
+                dur[(size_t)(j - 1) * W] = fin[(size_t)(j - 1) * W];
+                fin[(size_t)(j - 1) * W] = 0;
+            }
+            Rv = S;
+        }
+        const int Jv = 2 * Rv - 1, sweeps = M + Jv - 1;
         for (int t = 1; t <= sweeps; ++t) {
-            const int jlo = max(1, t - M + 1), jhi = min(J, t);
-            const long long finR_prev = fin[(size_t)(R - 1) * W];
-            for (int j = min(jhi, R); j >= jlo; --j) {
+            const int jlo = max(1, t - M + 1), jhi = min(Jv, t);
+            const long long finR_prev = fin[(size_t)(Rv - 1) * W];
+            for (int j = min(jhi, Rv); j >= jlo; --j) {
                 long long idle = fin[(size_t)(j - 1) * W];
-                if (j & 1) idle = max(idle, fin[(size_t)((2 * R - j) - 1) * W]);
+                if (pair_all || (j & 1)) idle = max(idle, fin[(size_t)((2 * Rv - j) - 1) * W]);
                 long long ready = j > 1 ? fin[(size_t)((j - 1) - 1) * W] : 0;
                 fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
             }
-            for (int j = jhi; j >= max(jlo, R + 1); --j) {
+            for (int j = jhi; j >= max(jlo, Rv + 1); --j) {
                 long long idle = fin[(size_t)(j - 1) * W];
-                if (j & 1) idle = max(idle, fin[(size_t)((2 * R - j) - 1) * W]);
-                long long ready = j == R + 1 ? finR_prev : fin[(size_t)((j - 1) - 1) * W];
+                if (pair_all || (j & 1)) idle = max(idle, fin[(size_t)((2 * Rv - j) - 1) * W]);
+                long long ready = j == Rv + 1 ? finR_prev : fin[(size_t)((j - 1) - 1) * W];
                 fin[(size_t)(j - 1) * W] = max(idle, ready) + dur[(size_t)(j - 1) * W];
             }
         }
-        T = fin[(size_t)(J - 1) * W];
+        T = fin[(size_t)(Jv - 1) * W];
     }
     if (live) {
         if (fault) pp_raise(a.status, fault);

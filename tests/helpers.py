@@ -180,7 +180,9 @@ def variant_blocks(variant, F, B, cf, cb):
     """Block list of a schedule variant for list_sim.  'pe' and 'duplex': blocks of the PE
     scheduler (last stage merged), served by (sweep, block) with sweep = m + j; 'duplex' gives
     the backward transfers their own channels.  'gpipe': last stage's F and B separate, every
-    resource serves all forward items, then all backward items, microbatches in order."""
+    resource serves all forward items, then all backward items, microbatches in order.
+    'additive': 2S-1 stage blocks (last stage merged), transfers added to the stage they lead into,
+    served by (sweep, block) on that shorter list."""
     S = len(F)
     blocks = []
     merged = variant != "gpipe"
@@ -192,6 +194,16 @@ def variant_blocks(variant, F, B, cf, cb):
         else:
             blocks.append((res, dur, (lambda m, j=j: (m + j, j))))
 
+    if variant == "additive":
+        # stages only; a stage's passes include the transfers over its inbound link
+        for n in range(S):
+            d = F[n] + (cf[n] if n else 0)
+            if n == S - 1:
+                d += B[n] + (cb[n] if n else 0)
+            add(("s", n), d, True)
+        for n in range(S - 2, -1, -1):
+            add(("s", n), B[n] + (cb[n] if n else 0), False)
+        return blocks
     for n in range(S):
         if n:
             add(("c", n), cf[n], True)

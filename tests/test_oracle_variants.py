@@ -1,4 +1,5 @@
-"""Pins for the oracle's schedule variants (duplex channels, GPipe order): hand-worked
+"""Pins for the oracle's schedule variants (duplex channels, GPipe order, transfers added to the
+stages): hand-worked
 schedules, closed forms and an independent simulation with explicit service lists."""
 import numpy as np
 import pytest
@@ -6,7 +7,7 @@ import pytest
 from conftest import read_golden
 from helpers import list_sim, variant_blocks
 
-NAMES = {0: "pe", 1: "duplex", 2: "gpipe"}
+NAMES = {0: "pe", 1: "duplex", 2: "gpipe", 3: "additive"}
 
 
 def random_pipeline(seed):
@@ -28,6 +29,9 @@ def test_handworked(ppo):
     assert ppo.variant_makespan(ppo.SCHED_DUPLEX, F, B, c, c, M) == g["A_T_duplex"][0][0]
     F, B, c, M = g["B_F"][0], g["B_B"][0], g["B_c"][0], g["B_M"][0][0]
     assert ppo.variant_makespan(ppo.SCHED_GPIPE, F, B, c, c, M) == g["B_T_gpipe"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_ADDITIVE, F, B, c, c, M) == g["B_T_additive"][0][0]
+    F, B, c, M = g["A_F"][0], g["A_B"][0], g["A_c"][0], g["A_M"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_ADDITIVE, F, B, c, c, M) == g["A_T_additive"][0][0]
     assert ppo.variant_makespan(ppo.SCHED_GPIPE, [3] * 3, [5] * 3, [0] * 3, [0] * 3, 4) == g["C_T_gpipe"][0][0]
 
 
@@ -38,7 +42,7 @@ def test_pe_variant_is_the_pe_scheduler(ppo, seed):
 
 
 @pytest.mark.parametrize("seed", range(100, 140))
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 def test_against_the_list_simulation(ppo, seed, variant):
     S, M, F, B, cf, cb = random_pipeline(seed)
     T, _ = list_sim(variant_blocks(NAMES[variant], F, B, cf, cb), M)
@@ -51,21 +55,45 @@ def test_gpipe_closed_form_without_transfers(ppo, S, M):
     assert ppo.variant_makespan(ppo.SCHED_GPIPE, [7] * S, [11] * S, [0] * S, [0] * S, M) == (M + S - 1) * 18
 
 
+@pytest.mark.parametrize("S,M", [(1, 3), (3, 1), (3, 4), (5, 7), (7, 2), (9, 12)])
+def test_additive_equals_pe_scheduler_on_odd_lists(ppo, S, M):
+    # In the PE list every resource, stage or channel, owns block j and block 2R-j.  The additive
+    # list of S = 2S'-1 stages with free links is therefore exactly the PE list of S' stages in
+    # which the odd additive stages play the channels (2S-1 = 4S'-3 blocks either way).
+    Sp = (S + 1) // 2
+    rng = np.random.Generator(np.random.PCG64(900 + S * 31 + M))
+    F = rng.integers(1, 20, size=S).tolist()
+    B = rng.integers(1, 30, size=S).tolist()
+    zero = [0] * S
+    T = ppo.variant_makespan(ppo.SCHED_ADDITIVE, F, B, zero, zero, M)
+    # PE pipeline: stage n' = additive stage 2n', channel n' (n' >= 1) = additive stage 2n'-1
+    Fp, Bp = F[0::2], B[0::2]
+    cfp, cbp = [0] + F[1::2], [0] + B[1::2]
+    assert len(Fp) == Sp and len(cfp) == Sp
+    assert T == ppo.pe_makespan(Fp, Bp, cfp, cbp, M)
+
+
+def test_additive_with_free_links_and_one_microbatch_is_the_path(ppo):
+    assert ppo.variant_makespan(ppo.SCHED_ADDITIVE, [3, 4, 5], [6, 7, 8], [0, 10, 20], [0, 30, 40], 1) == 133
+
+
 def test_bounds(ppo):
     # every variant needs at least M times the busiest resource and one microbatch's full path
     for seed in range(200, 230):
         S, M, F, B, cf, cb = random_pipeline(seed)
         path = sum(F) + sum(B) + sum(cf) + sum(cb)
-        for variant in (0, 1, 2):
+        for variant in (0, 1, 2, 3):
             T = ppo.variant_makespan(variant, F, B, cf, cb, M)
             busiest = max([f + b for f, b in zip(F, B)] +
                           ([max(x, y) if variant == 1 else x + y for x, y in zip(cf[1:], cb[1:])] or [0]))
+            if variant == 3:
+                busiest = max(f + b + x + y for f, b, x, y in zip(F, B, cf, cb))
             assert T >= max(path, M * busiest)
 
 
 def test_one_stage_all_variants_agree(ppo):
     for M in (1, 4):
-        assert {ppo.variant_makespan(v, [5], [9], [0], [0], M) for v in (0, 1, 2)} == {14 * M}
+        assert {ppo.variant_makespan(v, [5], [9], [0], [0], M) for v in (0, 1, 2, 3)} == {14 * M}
 
 
 def test_batch_function(ppo):
