@@ -172,6 +172,13 @@ int pp_schedule_makespan(int L, int D, int S, int64_t N, int M,
  *                    microbatch passes 2S-1 blocks; Alg. 1's ordering and
  *                    scheduling phases on that list ("stage cost = compute
  *                    plus transfer" instead of overlapping channels)
+ *   PP_SCHED_FIFO    Alg. 1 read strictly: only computation blocks follow the
+ *                    lists; a channel that is idle starts the waiting transfer
+ *                    whose preceding block finished first (equal times: the
+ *                    one earlier in the order of Alg. 1's first phase).
+ *                    Evaluated as an event simulation that commits the item
+ *                    with the earliest start next (equal starts: the lowest
+ *                    resource, resources numbered along the pipeline)
  * Same arguments, limits and faults as pp_schedule_makespan; an unknown variant
  * returns PP_ERR_INVALID_ARG.
  */
@@ -179,6 +186,7 @@ int pp_schedule_makespan(int L, int D, int S, int64_t N, int M,
 #define PP_SCHED_DUPLEX 1
 #define PP_SCHED_GPIPE 2
 #define PP_SCHED_ADDITIVE 3
+#define PP_SCHED_FIFO 4
 int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
                                  const int64_t *PF, const int64_t *PB,
                                  const int64_t *XF, const int64_t *XB,

@@ -948,6 +948,90 @@ int ppo_spp_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
 /* ------------------------------------------------------------------ */
 
 /*
+ * Alg. 1 with channels that serve by readiness (Sec. IV-A, scheduling phase: "the successor
+ * communication block is immediately run upon the channel becoming idle"; only computation
+ * blocks are entered into the lists U_s).  Blocks j = 1..J = 4S-3 on resources
+ * r(j) = min(j, 2R - j), R = 2S-1, odd resources are stages.  Every block handles the
+ * microbatches in index order (stages by their lists, a channel's two directions each first
+ * come first served), so nxt[j] is the next microbatch of block j.
+ *   stage r:   next item = the earlier of (nxt[r], r) and (nxt[2R-r], 2R-r) in the order of
+ *              the first phase (sweep m + j - 1, then block); it can start once its microbatch
+ *              has left the preceding block;
+ *   channel r: of the (at most two) head items whose microbatch has left the preceding
+ *              block, the one that left it first; equal times: earlier in the first phase's
+ *              order.
+ * The item with the earliest start max(ready, resource idle) over all resources is committed
+ * next (equal starts: lowest resource), until all J M items are done.
+ */
+static int64_t fifo_makespan(int S, int M, const int64_t *F, const int64_t *B,
+                             const int64_t *cf, const int64_t *cb) {
+    const int R = 2 * S - 1, J = 2 * R - 1;
+    int64_t *dur = (int64_t *)malloc((size_t)(J + 1) * sizeof(int64_t));
+    int64_t *done = (int64_t *)malloc((size_t)(J + 1) * (M + 1) * sizeof(int64_t));
+    int64_t *idle = (int64_t *)calloc((size_t)R + 1, sizeof(int64_t));
+    int *nxt = (int *)malloc((size_t)(J + 1) * sizeof(int));
+    int64_t T = -1;
+    if (!dur || !done || !idle || !nxt) goto out;
+    for (int n = 0; n < S; ++n) {
+        const int r = 2 * n + 1;
+        if (n == S - 1) dur[R] = F[n] + B[n];
+        else { dur[r] = F[n]; dur[2 * R - r] = B[n]; }
+        if (n) { dur[r - 1] = cf[n]; dur[2 * R - (r - 1)] = cb[n]; }
+    }
+    for (int j = 1; j <= J; ++j) nxt[j] = 1;
+    for (size_t i = 0; i < (size_t)(J + 1) * (M + 1); ++i) done[i] = -1;
+#define DONE(j, m) done[(size_t)(j) * (M + 1) + (m)]
+    for (long long left = (long long)J * M; left > 0; --left) {
+        int best_r = 0, best_j = 0;
+        int64_t best_start = 0;
+        for (int r = 1; r <= R; ++r) {
+            const int ja = r, jb = 2 * R - r;
+            int j = 0;
+            int64_t ready = 0;
+            if (r & 1) {
+                /* the stage's list */
+                int pick = 0;
+                const int has_a = nxt[ja] <= M, has_b = jb != ja && nxt[jb] <= M;
+                if (has_a && (!has_b || nxt[ja] + ja <= nxt[jb] + jb)) pick = ja;
+                else if (has_b) pick = jb;
+                if (!pick) continue;
+                if (pick > 1 && DONE(pick - 1, nxt[pick]) < 0) continue;
+                j = pick;
+                ready = pick > 1 ? DONE(pick - 1, nxt[pick]) : 0;
+            } else {
+                /* the channel's waiting heads */
+                for (int k = 0; k < 2; ++k) {
+                    const int jj = k ? jb : ja;
+                    if (nxt[jj] > M) continue;
+                    const int64_t rd = DONE(jj - 1, nxt[jj]);
+                    if (rd < 0) continue;
+                    if (!j || rd < ready ||
+                        (rd == ready && (nxt[jj] + jj < nxt[j] + j ||
+                                         (nxt[jj] + jj == nxt[j] + j && jj < j)))) {
+                        j = jj;
+                        ready = rd;
+                    }
+                }
+                if (!j) continue;
+            }
+            const int64_t start = max2(ready, idle[r]);
+            if (!best_r || start < best_start) { best_r = r; best_j = j; best_start = start; }
+        }
+        if (!best_r) goto out; /* cannot happen: block 1 or a successor is always available */
+        const int64_t fin = best_start + dur[best_j];
+        DONE(best_j, nxt[best_j]) = fin;
+        idle[best_r] = fin;
+        nxt[best_j]++;
+    }
+    T = 0;
+    for (int m = 1; m <= M; ++m) T = max2(T, DONE(J, m));
+#undef DONE
+out:
+    free(dur); free(done); free(idle); free(nxt);
+    return T;
+}
+
+/*
  * A schedule variant is a block list per microbatch, a resource per block and a service
  * order per resource; the timing rule is the scheduling phase of Alg. 1 in every case (an
  * item starts when its microbatch has left the preceding block and the resource is idle).
@@ -961,10 +1045,12 @@ int ppo_spp_replicated(int L, int D, int64_t N, int M, const int64_t *fwd_us,
  *                     activations in, backward gradients out over the same link) are added
  *                     to that stage's forward and backward blocks.  2S-1 blocks per
  *                     microbatch, PE's ordering phase on that list.
+ *   PPO_SCHED_FIFO    channels serve by readiness instead of by list: fifo_makespan above.
  */
 int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F, const int64_t *B,
                              const int64_t *cf, const int64_t *cb) {
     if (S < 1 || S > PPO_MAX_STAGES || M < 1 || !F || !B || (S > 1 && (!cf || !cb))) return -1;
+    if (variant == PPO_SCHED_FIFO) return fifo_makespan(S, M, F, B, cf, cb);
     if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE &&
         variant != PPO_SCHED_ADDITIVE) return -1;
     const int merged = variant != PPO_SCHED_GPIPE;       /* last stage: one block or two */
@@ -1085,7 +1171,7 @@ int ppo_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, i
     if (rc) return rc;
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PPO_ERR_INVALID_ARG;
     if (variant != PPO_SCHED_PE && variant != PPO_SCHED_DUPLEX && variant != PPO_SCHED_GPIPE &&
-        variant != PPO_SCHED_ADDITIVE)
+        variant != PPO_SCHED_ADDITIVE && variant != PPO_SCHED_FIFO)
         return PPO_ERR_INVALID_ARG;
     int32_t *own = NULL;
     if (!orderings) {

@@ -172,11 +172,19 @@ int64_t ppo_pe_makespan(int S, int M, const int64_t *F, const int64_t *B,
  *                     merged block all four), so a microbatch passes 2S-1 blocks
  *                     on S resources; ordering and scheduling phases of Alg. 1
  *                     on that shorter list ("stage cost = compute plus transfer")
+ *   PPO_SCHED_FIFO    Alg. 1 read strictly: only computation blocks follow the
+ *                     lists U_s; a channel, whenever idle, starts the waiting
+ *                     transfer whose preceding block finished first (equal
+ *                     times: the one earlier in the order of Alg. 1's first
+ *                     phase).  Evaluated as an event simulation that always
+ *                     commits the item with the earliest start next (equal
+ *                     starts: the lowest resource).
  * F, B per stage; cf, cb per channel with entry 0 unused. */
 #define PPO_SCHED_PE 0
 #define PPO_SCHED_DUPLEX 1
 #define PPO_SCHED_GPIPE 2
 #define PPO_SCHED_ADDITIVE 3
+#define PPO_SCHED_FIFO 4
 int64_t ppo_variant_makespan(int variant, int S, int M, const int64_t *F,
                              const int64_t *B, const int64_t *cf, const int64_t *cb);
 int ppo_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,

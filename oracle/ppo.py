@@ -213,7 +213,7 @@ def pe_makespan(F, B, cf, cb, M, want_times=False):
     return (T, st, fi) if want_times else T
 
 
-SCHED_PE, SCHED_DUPLEX, SCHED_GPIPE, SCHED_ADDITIVE = 0, 1, 2, 3
+SCHED_PE, SCHED_DUPLEX, SCHED_GPIPE, SCHED_ADDITIVE, SCHED_FIFO = 0, 1, 2, 3, 4
 
 
 def variant_makespan(variant, F, B, cf, cb, M):

@@ -164,7 +164,7 @@ def pp_schedule_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out
         _ptr(status, i32, 1, "status"), _stream()))
 
 
-PP_SCHED_PE, PP_SCHED_DUPLEX, PP_SCHED_GPIPE, PP_SCHED_ADDITIVE = 0, 1, 2, 3
+PP_SCHED_PE, PP_SCHED_DUPLEX, PP_SCHED_GPIPE, PP_SCHED_ADDITIVE, PP_SCHED_FIFO = 0, 1, 2, 3, 4
 
 
 def pp_schedule_makespan_variant(variant, L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out, status):

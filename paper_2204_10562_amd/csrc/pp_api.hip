@@ -123,7 +123,8 @@ extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, in
     if (variant == PP_SCHED_PE)
         return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
                                   status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
-    if (variant != PP_SCHED_DUPLEX && variant != PP_SCHED_GPIPE && variant != PP_SCHED_ADDITIVE)
+    if (variant != PP_SCHED_DUPLEX && variant != PP_SCHED_GPIPE && variant != PP_SCHED_ADDITIVE &&
+        variant != PP_SCHED_FIFO)
         return PP_ERR_INVALID_ARG;
     return pp_launch_makespan_variant(variant, L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out,
                                       status, (hipStream_t)stream);

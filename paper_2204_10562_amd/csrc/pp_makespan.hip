@@ -1010,6 +1010,8 @@ int pp_launch_rep_makespan(int L, int D, int64_t N, int M, const int64_t *PF, co
 //     forward item.  The last stage's forward and backward passes are separate items here.
 //   PP_SCHED_ADDITIVE: the sweeps of the PE scheduler over the 2S-1 stage blocks alone, each
 //     with the transfers over the stage's inbound link added to its duration.
+//   PP_SCHED_FIFO: Alg. 1 with channels that serve by readiness instead of by list (only
+//     computation blocks enter the lists U_s in the listing): an event simulation.
 __global__ __launch_bounds__(64) void k_makespan_variant(mk_args a) {
     extern __shared__ long long sm[];
     const int lane = threadIdx.x, W = blockDim.x;
@@ -1050,6 +1052,61 @@ __global__ __launch_bounds__(64) void k_makespan_variant(mk_args a) {
             }
         }
         T = fin[0];
+    } else if (a.variant == PP_SCHED_FIFO) {
+        // Event simulation, one committed item per iteration (the same in every lane): every
+        // block handles the microbatches in index order, nxt[j] is block j's next one.  A
+        // stage's next item is the earlier of its two blocks' heads in list order (sweep
+        // m + j - 1, then block); a channel takes, of its heads whose microbatch has left the
+        // preceding block, the one that left it first (equal: earlier in list order).  The item
+        // with the earliest start over all resources is committed (equal: lowest resource).
+        // A microbatch is in exactly one place, so one "left its last block at" time per
+        // microbatch in flight is enough; the first stage's list keeps at most J in flight,
+        // so they live in a ring of Q >= J slots (Q a power of two).
+        int Q = 1;
+        while (Q < J) Q <<= 1;
+        long long *idle = fin;                              // rows J..J+R-1: resource r at r-1
+        long long *ring = fin + (size_t)R * W;              // Q rows
+        long long *nxt = ring + (size_t)Q * W;              // J rows: block j at j-1
+        for (int r = 0; r < R; ++r) idle[(size_t)r * W] = 0;
+        for (int q = 0; q < Q; ++q) ring[(size_t)q * W] = 0;
+        for (int j = 0; j < J; ++j) nxt[(size_t)j * W] = 1;
+        T = 0;
+        for (long long left = (long long)J * M; left > 0; --left) {
+            int best_r = 0, best_j = 0;
+            long long best_start = 0;
+            for (int r = 1; r <= R; ++r) {
+                const int ja = r, jb = 2 * R - r;
+                const int ma = (int)nxt[(size_t)(ja - 1) * W], mb = (int)nxt[(size_t)(jb - 1) * W];
+                // head (m, j) of a block is there once block j-1 has moved past m
+                const bool at_a = ma <= M && (ja == 1 || (int)nxt[(size_t)(ja - 2) * W] > ma);
+                const bool at_b = jb != ja && mb <= M && (int)nxt[(size_t)(jb - 2) * W] > mb;
+                const long long ra = ja == 1 ? 0 : ring[(size_t)(ma & (Q - 1)) * W];
+                const long long rb = ring[(size_t)(mb & (Q - 1)) * W];
+                int j = 0;
+                if (r & 1) {
+                    const bool has_a = ma <= M, has_b = jb != ja && mb <= M;
+                    if (has_a && (!has_b || ma + ja <= mb + jb)) j = at_a ? ja : 0;
+                    else if (has_b) j = at_b ? jb : 0;
+                } else {
+                    const bool a_first = ra < rb || (ra == rb && ma + ja <= mb + jb);
+                    if (at_a && (!at_b || a_first)) j = ja;
+                    else if (at_b) j = jb;
+                }
+                const long long ready = j == ja ? ra : rb;
+                const long long busy = idle[(size_t)(r - 1) * W];
+                const long long start = ready > busy ? ready : busy;
+                if (j && (!best_r || start < best_start)) { best_r = r; best_j = j; best_start = start; }
+            }
+            // (there always is one: block 1 or the successor of a finished item)
+            if (best_r) {
+                const long long f = best_start + dur[(size_t)(best_j - 1) * W];
+                const int m = (int)nxt[(size_t)(best_j - 1) * W];
+                ring[(size_t)(m & (Q - 1)) * W] = f;
+                idle[(size_t)(best_r - 1) * W] = f;
+                nxt[(size_t)(best_j - 1) * W] = m + 1;
+                if (best_j == J) T = f > T ? f : T;
+            }
+        }
     } else {
         // The PE sweeps over a list of 2Rv-1 blocks on Rv resources, block j and block 2Rv-j on
         // the same one.  DUPLEX: the standard list, but even resources are channels, whose two
@@ -1114,8 +1171,18 @@ int pp_launch_makespan_variant(int variant, int L, int D, int S, int64_t N, int 
     a.variant = variant;
     a.T_out = (long long *)T_out; a.status = status;
     a.part = NULL; a.C = NULL; a.out = NULL;
-    const int W = lds_lanes(S);
-    const size_t lds = (size_t)2 * (4 * S - 3) * W * 8;
+    int W = lds_lanes(S);
+    const int J = 4 * S - 3, R = 2 * S - 1;
+    size_t rows = (size_t)2 * J;
+    if (variant == PP_SCHED_FIFO) {
+        // durations, resource idle times, a power-of-two ring of J or more, next microbatches
+        int Q = 1;
+        while (Q < J) Q <<= 1;
+        rows = (size_t)J + R + Q + J;
+        W = 64;
+        while (rows * W * 8 > 64 * 1024) W >>= 1;
+    }
+    const size_t lds = rows * W * 8;
     unsigned grid = (unsigned)((N + W - 1) / W);
     hipLaunchKernelGGL(k_makespan_variant, dim3(grid), dim3(W), lds, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;

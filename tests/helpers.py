@@ -128,6 +128,71 @@ def event_sim(F, B, cf, cb, M):
     return T, start
 
 
+def fifo_sim(F, B, cf, cb, M):
+    """Clock-driven simulation of Alg. 1 read strictly: stages follow their lists (sweep
+    m + j - 1, then block), a channel that is idle takes, of the transfers waiting for it, the
+    one that has waited longest (equal: earlier in list order).  Positive durations only (with
+    zero-length work "the same instant" is ambiguous).  Returns T."""
+    S = len(F)
+    R = 2 * S - 1
+    J = 2 * R - 1
+    res = lambda j: j if j <= R else 2 * R - j
+    dur = {}
+    for n in range(S):
+        r = 2 * n + 1
+        if n == S - 1:
+            dur[R] = F[n] + B[n]
+        else:
+            dur[r], dur[2 * R - r] = F[n], B[n]
+        if n:
+            dur[r - 1], dur[2 * R - (r - 1)] = cf[n], cb[n]
+    assert all(d >= 1 for d in dur.values())
+    stage_list = {r: sorted((m + j - 1, j, m) for j in range(1, J + 1) if res(j) == r for m in range(1, M + 1))
+                  for r in range(1, R + 1, 2)}
+    pos = {r: 0 for r in stage_list}
+    waiting = {r: [] for r in range(2, R + 1, 2)}   # (arrival time, list key, j, m)
+    arrived = {}                                     # (j, m) -> time its microbatch reached block j
+    for m in range(1, M + 1):
+        arrived[(1, m)] = 0
+    free_at = {r: 0 for r in range(1, R + 1)}
+    running = []                                     # heap of (finish, r, j, m)
+    finished = 0
+    T = 0
+    now = 0
+    while finished < J * M:
+        progressed = True
+        while progressed:
+            progressed = False
+            for r in range(1, R + 1):
+                if free_at[r] > now or any(x[1] == r for x in running):
+                    continue
+                if r % 2:
+                    if pos[r] >= len(stage_list[r]):
+                        continue
+                    _, j, m = stage_list[r][pos[r]]
+                    if (j, m) not in arrived:
+                        continue
+                    pos[r] += 1
+                else:
+                    if not waiting[r]:
+                        continue
+                    waiting[r].sort()
+                    _, _, j, m = waiting[r].pop(0)
+                heapq.heappush(running, (now + dur[j], r, j, m))
+                free_at[r] = now + dur[j]
+                progressed = True
+        now = running[0][0]
+        while running and running[0][0] == now:
+            _, r, j, m = heapq.heappop(running)
+            finished += 1
+            T = max(T, now)
+            if j < J:
+                arrived[(j + 1, m)] = now
+                if res(j + 1) % 2 == 0:
+                    waiting[res(j + 1)].append((now, (m + j, j + 1), j + 1, m))
+    return T
+
+
 def list_sim(blocks, M):
     """Heap-driven simulation of serial resources that follow explicit service lists.
     blocks: list of (resource id, duration, key) in the order a microbatch passes them, where

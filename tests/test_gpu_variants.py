@@ -38,7 +38,7 @@ def test_variants_adversarial_small(ppo, G, seed, L, D, S, N):
     g = G(w)
     g.set_tables(*tables)
     bounds = random_bounds(np.random.Generator(np.random.PCG64(seed)), N, S, L)
-    for variant in (0, 1, 2, 3):
+    for variant in (0, 1, 2, 3, 4):
         for M in (1, 3, 40):
             say("variant", variant, "small", seed, L, D, S, N, "M", M)
             st, T = g.makespan_variant(variant, M, bounds)
@@ -57,7 +57,7 @@ def test_variants_on_the_dp_plans(ppo, G, name):
     assert st == 0
     M = w.Ms[-1]
     st, T_pe = g.makespan(M, bounds)
-    for variant in (0, 1, 2, 3):
+    for variant in (0, 1, 2, 3, 4):
         say("variant", variant, name, "M", M)
         st, T = g.makespan_variant(variant, M, bounds)
         rc, T0 = ppo.schedule_makespan_variant(variant, w.L, w.D, w.S, w.N, M, *tables, w.orderings, bounds)
@@ -74,7 +74,7 @@ def test_variants_large_shapes_subset(ppo, G):
         assert g.prefix() == 0
         tables = oracle_tables(ppo, w)
         st, C, bounds = g.dp()
-        for variant in (1, 2, 3):
+        for variant in (1, 2, 3, 4):
             say("variant", variant, name, N)
             st, T = g.makespan_variant(variant, w.Ms[-1], bounds)
             rc, T0 = ppo.schedule_makespan_variant(variant, w.L, w.D, w.S, w.N, w.Ms[-1], *tables, w.orderings, bounds)
@@ -89,7 +89,7 @@ def test_variants_faults(ppo, G):
     g.set_tables(*tables)
     bounds = random_bounds(np.random.Generator(np.random.PCG64(4)), 32, 4, 20)
     bad = bounds.copy(); bad[7, 1] = bad[7, 0]
-    for variant in (1, 2, 3):
+    for variant in (1, 2, 3, 4):
         say("variant fault", variant)
         st, T = g.makespan_variant(variant, 3, bad)
         rc, T0 = ppo.schedule_makespan_variant(variant, 20, 5, 4, 32, 3, *tables, w.orderings, bad)

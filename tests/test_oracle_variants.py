@@ -1,11 +1,11 @@
 """Pins for the oracle's schedule variants (duplex channels, GPipe order, transfers added to the
-stages): hand-worked
+stages, channels that serve by readiness): hand-worked
 schedules, closed forms and an independent simulation with explicit service lists."""
 import numpy as np
 import pytest
 
 from conftest import read_golden
-from helpers import list_sim, variant_blocks
+from helpers import fifo_sim, list_sim, variant_blocks
 
 NAMES = {0: "pe", 1: "duplex", 2: "gpipe", 3: "additive"}
 
@@ -32,6 +32,10 @@ def test_handworked(ppo):
     assert ppo.variant_makespan(ppo.SCHED_ADDITIVE, F, B, c, c, M) == g["B_T_additive"][0][0]
     F, B, c, M = g["A_F"][0], g["A_B"][0], g["A_c"][0], g["A_M"][0][0]
     assert ppo.variant_makespan(ppo.SCHED_ADDITIVE, F, B, c, c, M) == g["A_T_additive"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_FIFO, F, B, c, c, M) == g["A_T_fifo"][0][0]
+    F, B, c, M = g["D_F"][0], g["D_B"][0], g["D_c"][0], g["D_M"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_PE, F, B, c, c, M) == g["D_T_pe"][0][0]
+    assert ppo.variant_makespan(ppo.SCHED_FIFO, F, B, c, c, M) == g["D_T_fifo"][0][0]
     assert ppo.variant_makespan(ppo.SCHED_GPIPE, [3] * 3, [5] * 3, [0] * 3, [0] * 3, 4) == g["C_T_gpipe"][0][0]
 
 
@@ -47,6 +51,46 @@ def test_against_the_list_simulation(ppo, seed, variant):
     S, M, F, B, cf, cb = random_pipeline(seed)
     T, _ = list_sim(variant_blocks(NAMES[variant], F, B, cf, cb), M)
     assert ppo.variant_makespan(variant, F, B, cf, cb, M) == T
+
+
+def positive_pipeline(seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    S = int(rng.integers(1, 7))
+    M = int(rng.integers(1, 12))
+    hi = int(rng.choice([3, 20, 200]))   # narrow ranges give many equal times
+    F = rng.integers(1, hi + 1, size=S).tolist()
+    B = rng.integers(1, 2 * hi + 1, size=S).tolist()
+    cf = [0] + rng.integers(1, hi + 1, size=S - 1).tolist()
+    cb = [0] + rng.integers(1, hi + 1, size=S - 1).tolist()
+    return S, M, F, B, cf, cb
+
+
+@pytest.mark.parametrize("seed", range(300, 420))
+def test_readiness_order_against_the_clock_simulation(ppo, seed):
+    S, M, F, B, cf, cb = positive_pipeline(seed)
+    assert ppo.variant_makespan(ppo.SCHED_FIFO, F, B, cf, cb, M) == fifo_sim(F, B, cf, cb, M)
+
+
+def test_readiness_order_differs_from_list_order_sometimes(ppo):
+    # the two readings of the channel rule are not the same schedule (so the test above can
+    # tell them apart), and neither is always the faster one
+    less = more = 0
+    for seed in range(300, 420):
+        S, M, F, B, cf, cb = positive_pipeline(seed)
+        a = ppo.variant_makespan(ppo.SCHED_FIFO, F, B, cf, cb, M)
+        b = ppo.variant_makespan(ppo.SCHED_PE, F, B, cf, cb, M)
+        less += a < b
+        more += a > b
+    assert less > 0
+    print("readiness order faster in", less, "slower in", more, "of 120")
+
+
+def test_readiness_order_equals_list_order_without_shared_channels(ppo):
+    # with one stage there is no channel; with one microbatch nothing ever waits
+    assert ppo.variant_makespan(ppo.SCHED_FIFO, [5], [9], [0], [0], 6) == 84
+    for seed in range(40):
+        S, _, F, B, cf, cb = positive_pipeline(seed)
+        assert ppo.variant_makespan(ppo.SCHED_FIFO, F, B, cf, cb, 1) == sum(F) + sum(B) + sum(cf) + sum(cb)
 
 
 @pytest.mark.parametrize("S,M", [(1, 1), (1, 5), (2, 3), (4, 6), (6, 2)])
@@ -82,7 +126,7 @@ def test_bounds(ppo):
     for seed in range(200, 230):
         S, M, F, B, cf, cb = random_pipeline(seed)
         path = sum(F) + sum(B) + sum(cf) + sum(cb)
-        for variant in (0, 1, 2, 3):
+        for variant in (0, 1, 2, 3, 4):
             T = ppo.variant_makespan(variant, F, B, cf, cb, M)
             busiest = max([f + b for f, b in zip(F, B)] +
                           ([max(x, y) if variant == 1 else x + y for x, y in zip(cf[1:], cb[1:])] or [0]))
@@ -93,7 +137,7 @@ def test_bounds(ppo):
 
 def test_one_stage_all_variants_agree(ppo):
     for M in (1, 4):
-        assert {ppo.variant_makespan(v, [5], [9], [0], [0], M) for v in (0, 1, 2, 3)} == {14 * M}
+        assert {ppo.variant_makespan(v, [5], [9], [0], [0], M) for v in (0, 1, 2, 3, 4)} == {14 * M}
 
 
 def test_batch_function(ppo):
