@@ -98,7 +98,8 @@ extern "C" int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM, const
                       workspace, lay, status, st);
     if (rc) return rc;
     return pp_launch_makespan_stages(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, C, T,
-                                     status, base + sl.part, out, (const pp_ws_header *)(base + lay.hdr), st);
+                                     status, base + sl.part, out, (const pp_ws_header *)(base + lay.hdr),
+                                     orderings == NULL, st);
 }
 
 extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,

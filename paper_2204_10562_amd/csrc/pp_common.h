@@ -121,11 +121,12 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
 // (bounds [N][S(S+1)/2] and C [N][S] as pp_launch_dp leaves them with stages == 1), written to
 // T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest
 // candidate and then lowest xi on ties, into out[q].  part must hold 1024 * nM pairs of int64.
+// lex: `orderings` is the library's own list of all D! orderings in lexicographic order.
 int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int *Ms,
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              pp_result *out, const pp_ws_header *hdr, hipStream_t st);
+                              pp_result *out, const pp_ws_header *hdr, int lex, hipStream_t st);
 // Makespan (Eq. 2) of the plans with replicated stages of every (candidate, stage count) and
 // the keep-the-minimum over them; arrays laid out as pp_plan_replicated documents; part holds
 // 1024 pairs of int64.

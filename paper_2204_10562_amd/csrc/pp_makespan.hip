@@ -35,6 +35,10 @@ struct mk_args {
     // stages is read from the triangular bounds array and T goes to column xi-1 (S, bnd_off and
     // t_off are then ignored)
     int all_xi;
+    // With all_xi and the library's own list of all D! orderings in lexicographic order:
+    // share[xi] = (D - xi)! consecutive candidates share their first xi devices and with them
+    // the plan of xi stages, so it is scheduled once per such block (share[xi] = 1: no sharing)
+    long long share[9];
     long long N;
     const long long *PF, *PB, *XF, *XB;
     const int *orderings;  // NULL = all D! orderings, candidate index = lexicographic rank
@@ -459,13 +463,16 @@ __device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S -
 // candidates for up to MK_REGS_WAVES counts: the scattered table lookups of the gather, which
 // cost more than the schedule itself for small M, are split between them by stage and
 // exchanged through LDS (dynamic, (J + 1 + waves) * 64 * 8 bytes; none for a single wave).
-template <int S>
+template <int S, bool SHARE = false>
 __device__ __forceinline__ void regs_body(const mk_args &a) {
     constexpr int R = 2 * S - 1, J = 4 * S - 3;
     extern __shared__ __align__(16) long long sh_dur[];  // [J+1][64] durations, [64] worst
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
-    const long long c = (long long)blockIdx.x * 64 + lane;
+    // one lane per candidate, or per block of `f` candidates that share this plan
+    const long long f = SHARE ? a.share[S <= 8 ? S : 0] : 1;
+    if (SHARE && (long long)blockIdx.x * 64 * f >= a.N) return;  // (the whole workgroup)
+    const long long c = ((long long)blockIdx.x * 64 + lane) * f;
     const bool live = c < a.N;
     long long dur[J + 1];
     long long worst;
@@ -494,8 +501,13 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
     // the assignment on top of that was measured to undo it.
     const int slot = blockIdx.y * nw + w;
     if (slot >= a.nM) return;
-    const int q = a.order[slot];
-    const int M = a.Ms[q];
+    // (selected with constant indices: a run-time index into the argument struct can make the
+    // compiler keep a copy of all of it in scratch memory, which cost 12 us per launch)
+    int q = 0, M = 1;
+#pragma unroll
+    for (int i = 0; i < PP_MAX_M_LIST; ++i) q = i == slot ? (int)a.order[i] : q;
+#pragma unroll
+    for (int i = 0; i < PP_MAX_M_LIST; ++i) M = i == q ? a.Ms[i] : M;
     const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
     // 32-bit arithmetic if no finish time of any lane can reach 2^31
     const bool narrow = fq || !live || worst <= (long long)0x7fffffff / ((long long)M + 4 * S - 4);
@@ -503,7 +515,15 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
     long long T;
     if (__all(narrow)) T = sweep_regs<S, int>(dur, M, [](const int (&fin)[J + 1]) { return (long long)fin[J]; });
     else T = sweep_regs<S, long long>(dur, M, [](const long long (&fin)[J + 1]) { return fin[J]; });
-    emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x, a.all_xi ? S - 1 : a.t_off);
+    if (!SHARE || f == 1) {
+        emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x, a.all_xi ? S - 1 : a.t_off);
+        return;
+    }
+    // every candidate of the lane's block gets the block's T
+    if (live && fq) pp_raise(a.status, fq);
+    if (fq) T = PP_INF64;
+    for (long long i = 0; i < f; ++i)
+        if (c + i < a.N) a.T_out[((long long)q * a.N + c + i) * a.t_stride + (S - 1)] = T;
 }
 
 // 9 <= S <= 16: one kernel per S.
@@ -526,6 +546,22 @@ __global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs8(mk_args a
         case 6: regs_body<6>(a); break;
         case 7: regs_body<7>(a); break;
         case 8: regs_body<8>(a); break;
+    }
+}
+
+// The same for the stage-count search over the library's own lexicographic list of all D!
+// orderings (always with all_xi): plans shared by blocks of consecutive candidates are
+// scheduled once per block.  A kernel of its own so that the plain one stays as lean as it is.
+__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs8_shared(mk_args a) {
+    switch ((int)blockIdx.z + 1) {
+        case 1: regs_body<1, true>(a); break;
+        case 2: regs_body<2, true>(a); break;
+        case 3: regs_body<3, true>(a); break;
+        case 4: regs_body<4, true>(a); break;
+        case 5: regs_body<5, true>(a); break;
+        case 6: regs_body<6, true>(a); break;
+        case 7: regs_body<7, true>(a); break;
+        case 8: regs_body<8, true>(a); break;
     }
 }
 
@@ -766,9 +802,14 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
         for (int k = i; k > 0 && a.Ms[b.order[k]] > a.Ms[b.order[k - 1]]; --k) {
             unsigned char t = b.order[k]; b.order[k] = b.order[k - 1]; b.order[k - 1] = t;
         }
-    if constexpr (S == 0)
-        hipLaunchKernelGGL(k_makespan_regs8, dim3(grid, (a.nM + nw - 1) / nw, a.all_xi ? a.S : 1),
-                           dim3(64 * nw), lds, st, b);
+    if constexpr (S == 0) {
+        if (a.all_xi && a.share[a.S > 2 ? a.S - 2 : 0] > 1)
+            hipLaunchKernelGGL(k_makespan_regs8_shared, dim3(grid, (a.nM + nw - 1) / nw, a.S),
+                               dim3(64 * nw), lds, st, b);
+        else
+            hipLaunchKernelGGL(k_makespan_regs8, dim3(grid, (a.nM + nw - 1) / nw, a.all_xi ? a.S : 1),
+                               dim3(64 * nw), lds, st, b);
+    }
     else
         hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, b);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
@@ -906,7 +947,7 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              pp_result *out, const pp_ws_header *hdr, hipStream_t st) {
+                              pp_result *out, const pp_ws_header *hdr, int lex, hipStream_t st) {
     mk_args a = {};
     a.L = L; a.D = D; a.N = N; a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
@@ -922,6 +963,13 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
         // the schedules of xi stages on the first xi devices, every xi in one launch
         a.S = S; a.all_xi = 1;
         a.bnd_off = 0; a.t_off = 0;
+        for (int xi = 0; xi <= 8; ++xi) {
+            long long fct = 1;
+            if (lex && xi >= 1) for (int i = 2; i <= D - xi; ++i) fct *= i;  // D = S <= 8 here
+            // (long blocks are not worth it: few waves would write thousands of entries each,
+            // and the plans with few stages are the cheap ones anyway)
+            a.share[xi] = fct <= 32 ? fct : 1;
+        }
         int rc = launch_makespan(a, st);
         if (rc) return rc;
         a.all_xi = 0;
