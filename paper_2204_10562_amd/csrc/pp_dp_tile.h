@@ -14,6 +14,7 @@ struct dp_tile_args {
     int validate;     // orderings came from the caller: check them
     int hoist;        // keep the candidate-independent difference keys in registers
     int prio;         // waves raise their issue priority with the share of their chunk still to do
+    int prio_left[3]; // priority k+1 while more than prio_left[k] candidates of the chunk are left
     const int *xkt;   // [link][b][j] keys ((XF+XB) << K) | k for k = 8j+b, infinite if k == 0 or k >= L
     const int *xct;   // [link][a][h][r] the same keys for the cells l = 8(hH+r)+a+1, H = ceil(nt/2)
     dp_args g;        // tables, outputs and the generic fallback's arguments

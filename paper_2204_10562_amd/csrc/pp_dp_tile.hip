@@ -277,9 +277,10 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         for (int j = 0; j < NT; ++j) x[j] = xp[j];
     };
 
-    // prio_until[k-1]: the last candidate with at least k quarters of the chunk still to do
+    // prio_until[k]: the last candidate with more than prio_left[k] candidates still to do
+    // (itself included)
     long long prio_until[3];
-    for (int k = 1; k <= 3; ++k) prio_until[k - 1] = c1 - ((long long)k * a.chunk + 3) / 4;
+    for (int k = 0; k < 3; ++k) prio_until[k] = c1 - 1 - a.prio_left[k];
 
     // first candidate of the chunk (bad ones are recorded and skipped)
     long long c = c0;
@@ -304,10 +305,9 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         // about to receive) the channel keys of row `first`
         fresh = false;
         if (a.prio) {
-            // Of the waves that share a SIMD the one with the larger share of its chunk still to
-            // do issues first, so that they finish together and none runs alone at the end.
-            // (quarters still to do = floor(4 (c1 - c) / chunk), compared against thresholds
-            // worked out once: a division here costs as much as a tenth of a row)
+            // Of the waves that share a SIMD the one with more of its chunk still to do issues
+            // first, so that they finish together and none runs alone at the end (levels from
+            // thresholds worked out once: a division here costs as much as a tenth of a row).
             if (c <= prio_until[2]) __builtin_amdgcn_s_setprio(3);
             else if (c <= prio_until[1]) __builtin_amdgcn_s_setprio(2);
             else if (c <= prio_until[0]) __builtin_amdgcn_s_setprio(1);
