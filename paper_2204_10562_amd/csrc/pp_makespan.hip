@@ -31,6 +31,11 @@ struct mk_args {
     int Ms[PP_MAX_M_LIST];  // microbatch counts; the plans are evaluated once per entry
     // k_makespan_regs: wave slot i (blockIdx.y * waves + wave) serves count Ms[order[i]]
     unsigned char order[PP_MAX_M_LIST];
+    // k_makespan_regs8: a workgroup holds `groups` groups of waves, each group one wave per
+    // microbatch count for its own 64 candidates; wave w of group g takes slot
+    // (slot_perm >> 2 (4 g + w)) & 3 of its four
+    int groups;
+    unsigned slot_perm;
     // k_makespan_regs8: nonzero = blockIdx.z + 1 is the number of stages xi, the plan with xi
     // stages is read from the triangular bounds array and T goes to column xi-1 (S, bnd_off and
     // t_off are then ignored)
@@ -184,7 +189,7 @@ __device__ __forceinline__ void emit(const mk_args &a, int q, long long c, bool 
     if (!a.part) return;
     tc_pair v = {live ? T : PP_INF64, live ? c : INT64_MAX};
     v = wave_tc_min(v);
-    if ((threadIdx.x & 63) == 0) a.part[(long long)q * n_waves + wave_id] = v;
+    if ((threadIdx.x & 63) == 0 && wave_id < n_waves) a.part[(long long)q * n_waves + wave_id] = v;
 }
 
 // The winner record of microbatch count q from the minimum w over all entries.
@@ -456,8 +461,10 @@ __device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S -
     return result(fin);
 }
 
-// Microbatch counts handled by one workgroup of k_makespan_regs (one wave each).
+// Microbatch counts handled by one group of waves of k_makespan_regs (one wave each), and the
+// most groups a workgroup of k_makespan_regs8 holds.
 #define MK_REGS_WAVES 4
+#define MK_REGS_GROUPS 3
 
 // One wave per (64 candidates, microbatch count).  The waves of a workgroup serve the same 64
 // candidates for up to MK_REGS_WAVES counts: the scattered table lookups of the gather, which
@@ -466,14 +473,20 @@ __device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S -
 template <int S, bool SHARE = false>
 __device__ __forceinline__ void regs_body(const mk_args &a) {
     constexpr int R = 2 * S - 1, J = 4 * S - 3;
-    extern __shared__ __align__(16) long long sh_dur[];  // [J+1][64] durations, [64] worst
+    extern __shared__ __align__(16) long long sh_all[];  // per group: [J+1][64] durations, [nw][64] worst
+    long long *sh_dur = sh_all;
     const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    // wave w of nw in group g of G: a group serves 64 candidates
+    const int G = a.groups, nw = (int)(blockDim.x >> 6) / G;
+    const int wall = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = wall / nw, w = wall - g * nw;
+    const long long group = (long long)blockIdx.x * G + g;
     // one lane per candidate, or per block of `f` candidates that share this plan
     const long long f = SHARE ? a.share[S <= 8 ? S : 0] : 1;
-    if (SHARE && (long long)blockIdx.x * 64 * f >= a.N) return;  // (the whole workgroup)
-    const long long c = ((long long)blockIdx.x * 64 + lane) * f;
+    if (SHARE && (long long)blockIdx.x * 64 * f >= a.N) return;  // (the whole workgroup; G = 1)
+    const long long c = (group * 64 + lane) * f;
     const bool live = c < a.N;
+    sh_dur += (size_t)g * (J + 1 + nw) * 64;
     long long dur[J + 1];
     long long worst;
     int fault;
@@ -494,12 +507,11 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
             worst = o > worst ? o : worst;
         }
     }
-    // The wave's microbatch count: the counts run side by side, not in a loop, largest count
-    // in wave 0 so that the longest wave is placed first.  Wave w takes the same
-    // slot in every workgroup: the hardware already starts successive workgroups of a compute
-    // unit on successive SIMDs, so the waves with the largest count spread out; a rotation of
-    // the assignment on top of that was measured to undo it.
-    const int slot = blockIdx.y * nw + w;
+    // The wave's microbatch count: the counts run side by side, not in a loop.
+    // Which wave of a group takes which count differs between the groups of a workgroup
+    // (slot_perm, chosen by the host): see launch_regs.
+    const int ws = (a.slot_perm >> (2 * (g * 4 + w))) & 3;
+    const int slot = blockIdx.y * nw + ws;
     if (slot >= a.nM) return;
     // (selected with constant indices: a run-time index into the argument struct can make the
     // compiler keep a copy of all of it in scratch memory, which cost 12 us per launch)
@@ -516,7 +528,7 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
     if (__all(narrow)) T = sweep_regs<S, int>(dur, M, [](const int (&fin)[J + 1]) { return (long long)fin[J]; });
     else T = sweep_regs<S, long long>(dur, M, [](const long long (&fin)[J + 1]) { return fin[J]; });
     if (!SHARE || f == 1) {
-        emit(a, q, c, live, fq, T, blockIdx.x, gridDim.x, a.all_xi ? S - 1 : a.t_off);
+        emit(a, q, c, live, fq, T, group, (a.N + 63) / 64, a.all_xi ? S - 1 : a.t_off);
         return;
     }
     // every candidate of the lane's block gets the block's T
@@ -535,7 +547,7 @@ __global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a)
 // S <= 8: one kernel for all of them, so that the stage-count search can evaluate the plans of
 // every stage count xi = 1..S in a single launch (blockIdx.z = xi - 1) instead of S launches
 // whose fixed costs add up.
-__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs8(mk_args a) {
+__global__ __launch_bounds__(64 * MK_REGS_WAVES * MK_REGS_GROUPS) void k_makespan_regs8(mk_args a) {
     // (the arguments stay untouched: a modified copy would live in scratch memory)
     switch (a.all_xi ? (int)blockIdx.z + 1 : a.S) {
         case 1: regs_body<1>(a); break;
@@ -802,13 +814,56 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
         for (int k = i; k > 0 && a.Ms[b.order[k]] > a.Ms[b.order[k - 1]]; --k) {
             unsigned char t = b.order[k]; b.order[k] = b.order[k - 1]; b.order[k - 1] = t;
         }
+    // A launch of a few hundred workgroups is bound by the SIMD that gets the most work, and
+    // the waves' work differs by the microbatch count.  The waves of a workgroup go to the four
+    // SIMDs of its compute unit in cyclic order (recorded hardware ids), but where the next
+    // workgroup starts varies, so with one group of four waves per workgroup two or three of
+    // the longest waves often meet on one SIMD.  With four different counts the workgroup
+    // therefore holds three groups (12 waves, 192 candidates) whose slot orders are permuted so
+    // that the three waves a SIMD gets from it (w, w + 4, w + 8) add up to about the same
+    // number of sweeps on every SIMD, wherever the workgroup lands.
+    b.groups = 1;
+    b.slot_perm = 0xE4E4E4;  // identity three times
+    unsigned gridx = grid;
+    int cus = 256, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        cus = 256;
+    // (with no more groups than compute units every wave has a SIMD of its own anyway)
+    if (S == 0 && nw == 4 && a.nM == 4 && !a.all_xi && grid > (unsigned)cus) {
+        long long wt[4];
+        for (int i = 0; i < 4; ++i) wt[i] = a.Ms[b.order[i]];
+        int perms[24][4], np = 0;
+        for (int p0 = 0; p0 < 4; ++p0) for (int p1 = 0; p1 < 4; ++p1) for (int p2 = 0; p2 < 4; ++p2) {
+            const int p3 = 6 - p0 - p1 - p2;
+            if (p0 == p1 || p0 == p2 || p1 == p2 || p3 < 0 || p3 > 3 || p3 == p0 || p3 == p1 || p3 == p2) continue;
+            perms[np][0] = p0; perms[np][1] = p1; perms[np][2] = p2; perms[np][3] = p3; ++np;
+        }
+        long long best = -1;
+        for (int i1 = 0; i1 < np; ++i1) for (int i2 = 0; i2 < np; ++i2) {
+            long long m = 0;
+            for (int sd = 0; sd < 4; ++sd) {
+                const long long sum = wt[sd] + wt[perms[i1][sd]] + wt[perms[i2][sd]];
+                m = sum > m ? sum : m;
+            }
+            if (best < 0 || m < best) {
+                best = m;
+                unsigned bits = 0xE4;
+                for (int w = 0; w < 4; ++w) bits |= (unsigned)perms[i1][w] << (2 * (4 + w)) | (unsigned)perms[i2][w] << (2 * (8 + w));
+                b.slot_perm = bits;
+            }
+        }
+        b.groups = MK_REGS_GROUPS;
+        gridx = (grid + MK_REGS_GROUPS - 1) / MK_REGS_GROUPS;
+    }
+    const size_t lds_all = lds * b.groups;
     if constexpr (S == 0) {
         if (a.all_xi && a.share[a.S > 2 ? a.S - 2 : 0] > 1)
             hipLaunchKernelGGL(k_makespan_regs8_shared, dim3(grid, (a.nM + nw - 1) / nw, a.S),
                                dim3(64 * nw), lds, st, b);
         else
-            hipLaunchKernelGGL(k_makespan_regs8, dim3(grid, (a.nM + nw - 1) / nw, a.all_xi ? a.S : 1),
-                               dim3(64 * nw), lds, st, b);
+            hipLaunchKernelGGL(k_makespan_regs8, dim3(gridx, (a.nM + nw - 1) / nw, a.all_xi ? a.S : 1),
+                               dim3(64 * nw * b.groups), lds_all, st, b);
     }
     else
         hipLaunchKernelGGL(k_makespan_regs<S>, dim3(grid, (a.nM + nw - 1) / nw), dim3(64 * nw), lds, st, b);

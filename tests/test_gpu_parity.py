@@ -445,6 +445,18 @@ def test_best_plan_multi_list_lengths(ppo, G, Ms):
     check_best_multi(ppo, g, w, Ms, tables)
 
 
+@pytest.mark.parametrize("N", [16384 + 64, 16384 + 337, 3 * 16384 + 129])
+def test_best_plan_multi_many_candidates_four_counts(ppo, G, N):
+    # more groups of 64 candidates than compute units and four counts: workgroups of three
+    # groups, the last one partly or wholly past the end of the list
+    w = workloads.random_small(823, 24, 6, 5, N, zero_frac=0.1, hi_time=9, hi_act=900)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("best_plan_multi many candidates", N)
+    check_best_multi(ppo, g, w, (70, 3, 30, 9), tables)
+
+
 @pytest.mark.parametrize("seed,L,D,S,N", SMALL)
 def test_best_plan_multi_adversarial_small(ppo, G, seed, L, D, S, N):
     w = workloads.random_small(seed, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500)
