@@ -457,6 +457,17 @@ def test_best_plan_multi_many_candidates_four_counts(ppo, G, N):
     check_best_multi(ppo, g, w, (70, 3, 30, 9), tables)
 
 
+@pytest.mark.parametrize("S", [1, 2, 3, 8])
+def test_best_plan_multi_many_candidates_stage_counts(ppo, G, S):
+    N = 16384 + 64 * 7 + 5
+    w = workloads.random_small(830 + S, 20, 8, S, N, zero_frac=0.1, hi_time=9, hi_act=900)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("best_plan_multi many candidates, S", S)
+    check_best_multi(ppo, g, w, (5, 41, 2, 17), tables)
+
+
 @pytest.mark.parametrize("seed,L,D,S,N", SMALL)
 def test_best_plan_multi_adversarial_small(ppo, G, seed, L, D, S, N):
     w = workloads.random_small(seed, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500)
