@@ -17,7 +17,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 # published MI355X figures: 256 compute units x 4 SIMDs x 16 lanes at 2.4 GHz, one 32-bit
 # integer operation per lane per clock
@@ -65,7 +64,7 @@ def main():
         print(json.dumps({"calibrate_copy_MiB": args.calibrate_copy, "copies": 10,
                           "bytes_read_per_copy": n * 8, "bytes_written_per_copy": n * 8}))
         return
-    from gpu_harness import GpuProblem
+    from paper_2204_10562_amd.problem import GpuProblem
     from paper_2204_10562_amd import binding as pp
     from paper_2204_10562_amd import workloads
 

@@ -2,7 +2,7 @@
 import numpy as np
 import torch
 
-from paper_2204_10562_amd import binding as pp
+from . import binding as pp
 
 
 class GpuProblem:

@@ -20,7 +20,7 @@ def say(*a):
 def G():
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
-    from gpu_harness import GpuProblem
+    from paper_2204_10562_amd.problem import GpuProblem
     return GpuProblem
 
 
@@ -129,7 +129,7 @@ def test_replicated_at_full_size(ppo, G):
     st, res, T, W, b, r = g.plan_replicated(M, alpha)
     assert st == 0
     win = res["best_index"]
-    idx = np.unique(np.concatenate([np.arange(0, w.N, 631), [win]]))
+    idx = np.unique(np.concatenate([np.arange(0, w.N, 97), [win]]))
     v = sub_workload(w, idx)
     rc, res0, T0, W0, b0, r0 = ppo.spp_replicated(v.L, v.D, v.N, M, v.fwd, v.bwd, v.actf, v.actb, alpha,
                                                   v.bw, v.orderings)

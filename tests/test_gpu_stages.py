@@ -20,7 +20,7 @@ def say(*a):
 def G():
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
-    from gpu_harness import GpuProblem
+    from paper_2204_10562_amd.problem import GpuProblem
     return GpuProblem
 
 
@@ -144,7 +144,7 @@ def test_stages_bad_orderings_fault(ppo, G):
         np.testing.assert_array_equal(b[keep], b0[keep])
 
 
-@pytest.mark.parametrize("name,stride", [("hetero", 4001)])
+@pytest.mark.parametrize("name,stride", [("hetero", 101), ("stress", 16411)])
 def test_stages_at_full_size(ppo, G, name, stride):
     """Full-size launch: the oracle on every stride-th candidate and on the winner."""
     w = workloads.CONFIGS[name]()

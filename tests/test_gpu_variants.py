@@ -19,7 +19,7 @@ def say(*a):
 def G():
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
-    from gpu_harness import GpuProblem
+    from paper_2204_10562_amd.problem import GpuProblem
     return GpuProblem
 
 
