@@ -64,6 +64,7 @@ def main():
         print(json.dumps({"calibrate_copy_MiB": args.calibrate_copy, "copies": 10,
                           "bytes_read_per_copy": n * 8, "bytes_written_per_copy": n * 8}))
         return
+    from paper_2204_10562_amd import problem
     from paper_2204_10562_amd.problem import GpuProblem
     from paper_2204_10562_amd import binding as pp
     from paper_2204_10562_amd import workloads
@@ -138,15 +139,14 @@ def main():
             rep_winner = pp.read_rep_result(out_rep, D)
             del ws_rep
         # the recursive device ordering (Alg. 2) as one more candidate: where does it rank?
-        rdo = pp.pp_rdo_order(D, w.bw.reshape(-1).tolist())
+        rdo = problem.rdo_row(w).tolist()
         T_all = torch.empty(N * len(Ms), dtype=torch.int64, device=dev)
         pp.pp_best_plan_multi(L, D, S, N, Ms, g.PF, g.PB, g.XF, g.XB, g.orderings, out, T_all, None, ws, g.status)
-        T_all = T_all.reshape(len(Ms), N)
-        o_rdo = torch.tensor(rdo[:S], dtype=torch.int32, device=dev)
+        o_rdo = torch.tensor(rdo, dtype=torch.int32, device=dev)
         out1 = torch.zeros(pp.RESULT_BYTES * len(Ms), dtype=torch.uint8, device=dev)
         T_rdo = torch.empty(len(Ms), dtype=torch.int64, device=dev)
         pp.pp_best_plan_multi(L, D, S, 1, Ms, g.PF, g.PB, g.XF, g.XB, o_rdo, out1, T_rdo, None, ws, g.status)
-        rdo_rank = [(int(T_rdo[q].item()), int((T_all[q] < T_rdo[q]).sum().item()), int(T_all[q].min().item())) for q in range(len(Ms))]
+        rdo_rank = problem.rank_among(T_all.reshape(len(Ms), N), T_rdo)
         del T_all
     assert int(g.status.item()) == 0
     # what the DP really evaluated (rows shared by consecutive candidates are computed once)

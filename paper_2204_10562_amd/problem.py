@@ -154,3 +154,29 @@ class GpuProblem:
         pp.pp_schedule_makespan_variant(variant, w.L, w.D, S, N, M, self.PF, self.PB, self.XF, self.XB, o, b,
                                         T, self.status)
         return self.take_status(), T.cpu().numpy()
+
+
+def rdo_row(w):
+    """The recursive device ordering (Alg. 2) of the workload's cluster, cut to the S devices
+    a candidate row holds: the row Alg. 3 evaluates before anything else."""
+    return np.asarray(pp.pp_rdo_order(w.D, w.bw.reshape(-1).tolist())[:w.S], dtype=np.int32)
+
+
+def with_first_candidate(w, row):
+    """A copy of the workload whose candidate list is `row` followed by the workload's own
+    candidates (explicit list, N + 1 rows), so that index 0 is the extra candidate and ties
+    with a later copy of the same ordering go to it."""
+    import copy
+    v = copy.copy(w)
+    v.orderings = np.ascontiguousarray(np.vstack([np.asarray(row, np.int32)[None, :], w.explicit_orderings()]))
+    v.N = w.N + 1
+    return v
+
+
+def rank_among(T_all, T_one):
+    """How many candidates of T_all ([nM, N] tensor or array) are strictly faster than the
+    candidate with times T_one ([nM]), and the best time, per microbatch count."""
+    T_all = torch.as_tensor(T_all)
+    T_one = torch.as_tensor(T_one).to(T_all.device)
+    faster = (T_all < T_one[:, None]).sum(dim=1)
+    return [(int(T_one[q]), int(faster[q]), int(T_all[q].min())) for q in range(T_all.shape[0])]
