@@ -209,6 +209,31 @@ int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
                  int32_t *status, void *stream);
 
 /*
+ * pp_best_plan for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs, faults and results as
+ * pp_best_plan, minus the workspace: the scratch memory is a device array of
+ * PP_STATIC_WORKSPACE_BYTES that is part of the library's code object (every
+ * GPU the library runs on holds one copy until the process ends).  The call
+ * allocates nothing and frees nothing; the first call on a device looks up
+ * the array's address (no allocation either).
+ *   - Problems whose pp_workspace_bytes(L, D, S, N) exceeds
+ *     PP_STATIC_WORKSPACE_BYTES are rejected with PP_ERR_WORKSPACE and nothing
+ *     is enqueued (the GPT-shaped configuration, L = 128, D = S = 8, all 40320
+ *     orderings, needs 19.4 MiB).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in
+ *     time on one GPU (different streams, different host threads) race.  The
+ *     array keeps the previous call's contents; nothing in it needs to start
+ *     at zero except the work counters, which the call's first kernel clears.
+ *   - Returns PP_ERR_HIP if the array's address cannot be obtained.
+ */
+#define PP_STATIC_WORKSPACE_BYTES (32u << 20)
+int pp_best_plan_static(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                        const int32_t *orderings, pp_result *out, int64_t *T_all,
+                        int64_t *C_all, int32_t *status, void *stream);
+
+/*
  * pp_best_plan for several microbatch counts at once.  The partition (a
  * plan's bounds and C) does not depend on M, because every term of the
  * recursion for W carries the same factor M when nothing is replicated

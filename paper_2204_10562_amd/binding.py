@@ -25,7 +25,7 @@ PP_MAX_STAGES = 64
 
 EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
            "pp_schedule_makespan_variant",
-           "pp_best_plan", "pp_best_plan_multi", "pp_workspace_bytes_stages", "pp_partition_dp_stages",
+           "pp_best_plan", "pp_best_plan_static", "pp_best_plan_multi", "pp_workspace_bytes_stages", "pp_partition_dp_stages",
            "pp_best_plan_stages", "pp_workspace_bytes_replicated", "pp_plan_replicated", "pp_rdo_order",
            "pp_strerror")
 
@@ -85,6 +85,8 @@ def lib():
         L.pp_schedule_makespan_variant.restype = i32
         L.pp_best_plan.argtypes = [i32, i32, i32, i64, i32] + [vp] * 8 + [vp, sz, vp, vp]
         L.pp_best_plan.restype = i32
+        L.pp_best_plan_static.argtypes = [i32, i32, i32, i64, i32] + [vp] * 8 + [vp, vp]
+        L.pp_best_plan_static.restype = i32
         L.pp_best_plan_multi.argtypes = [i32, i32, i32, i64, i32] + [vp] * 9 + [vp, sz, vp, vp]
         L.pp_best_plan_multi.restype = i32
         L.pp_workspace_bytes_stages.argtypes = [i32, i32, i32, i64, i32]
@@ -186,6 +188,21 @@ def pp_best_plan(L, D, S, N, M, PF, PB, XF, XB, orderings, out, T_all, C_all, wo
         _ptr(out, torch.uint8, RESULT_BYTES, "out"),
         _ptr(T_all, i64, N, "T_all", optional=True), _ptr(C_all, i64, N, "C_all", optional=True),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+PP_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def pp_best_plan_static(L, D, S, N, M, PF, PB, XF, XB, orderings, out, T_all, C_all, status):
+    """pp_best_plan with the library's own static device array as workspace."""
+    i64, i32 = torch.int64, torch.int32
+    _check(lib().pp_best_plan_static(
+        L, D, S, N, M, _ptr(PF, i64, L + 1, "PF"), _ptr(PB, i64, L + 1, "PB"),
+        _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(out, torch.uint8, RESULT_BYTES, "out"),
+        _ptr(T_all, i64, N, "T_all", optional=True), _ptr(C_all, i64, N, "C_all", optional=True),
         _ptr(status, i32, 1, "status"), _stream()))
 
 

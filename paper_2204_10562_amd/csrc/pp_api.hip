@@ -1,4 +1,6 @@
 // Entry points of libpp that only check arguments and enqueue kernels.
+#include <atomic>
+
 #include "pp_common.h"
 
 static bool factorial_is(int D, int64_t N) {
@@ -168,6 +170,43 @@ extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t
     if (M < 1) return PP_ERR_INVALID_ARG;
     return pp_best_plan_multi(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, out, T_all, C_all,
                               workspace, workspace_bytes, status, stream);
+}
+
+// ---------------------------------------------------------------- pp_best_plan_static
+//
+// pp_best_plan with the workspace in a device array that is part of the library's code
+// object instead of caller memory, for callers that cannot allocate.  The array's name is
+// only a host-side handle: its device address is looked up once per device (with that device
+// current) and from then on only that address is used.
+static __device__ __align__(256) unsigned char scratch[PP_STATIC_WORKSPACE_BYTES];
+
+#define PP_STATIC_MAX_GPUS 64
+static std::atomic<void *> scratch_at[PP_STATIC_MAX_GPUS];
+
+static void *static_workspace() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= PP_STATIC_MAX_GPUS) return NULL;
+    void *p = scratch_at[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // every thread that gets here asks for the same address; the last store wins
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NULL;
+        scratch_at[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
+extern "C" int pp_best_plan_static(int L, int D, int S, int64_t N, int M, const int64_t *PF,
+                                   const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                                   const int32_t *orderings, pp_result *out, int64_t *T_all,
+                                   int64_t *C_all, int32_t *status, void *stream) {
+    if (M < 1) return PP_ERR_INVALID_ARG;
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (pp_layout(L, D, S, N).total > (size_t)PP_STATIC_WORKSPACE_BYTES) return PP_ERR_WORKSPACE;
+    void *ws = static_workspace();
+    if (!ws) return PP_ERR_HIP;
+    return pp_best_plan_multi(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, out, T_all, C_all, ws,
+                              (size_t)PP_STATIC_WORKSPACE_BYTES, status, stream);
 }
 
 extern "C" const char *pp_strerror(int code) {
