@@ -25,7 +25,10 @@ static inline int pp_index_bits(int L) {
 #define PP_PACK_BLOCKS 64
 struct pp_ws_header {
     unsigned long long pmax[PP_PACK_BLOCKS];  // byte 0
-    unsigned pad0[128];  // byte 512
+    // byte 512: flat[b] != 0 iff, in pack block b's slice of the tables, the channel time
+    // XF + XB of every link is the same at every cut position (all 64 set: it is so everywhere)
+    unsigned flat[PP_PACK_BLOCKS];
+    unsigned pad0[64];  // byte 768
     // byte 1024: work the partition DP actually did in this call, in 64 records of 128 bytes
     // (atomics that hit one cache line are served one after another, so every record has a
     // line of its own): (cell, split) pairs evaluated (rows shared between candidates are
@@ -44,7 +47,7 @@ __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long l
 
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.
 struct pp_ws_layout {
-    size_t hdr, p32, x32, xkt, xct, ord, arg, bounds, C, T, part, total;
+    size_t hdr, p32, x32, xkt, xct, bfl, ord, arg, bounds, C, T, part, total;
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
@@ -61,6 +64,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.x32 = off;    off += pp_align256((size_t)D * D * L * 4);
     w.xkt = off;    off += pp_align256((size_t)D * D * 8 * w.nt * 4);
     w.xct = off;    off += pp_align256((size_t)D * D * 16 * ((w.nt + 1) / 2) * 4);
+    w.bfl = off;    off += pp_align256((size_t)S * (L + 1) * 8);  // channel-free DP table, [S][L+1] int64
     w.ord = off;    off += pp_align256((size_t)N * S * 4);
     w.slots = (int)(N < PP_DP_SLOTS ? N : PP_DP_SLOTS);
     w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 128) * 2);  // rows padded to 128 cells
@@ -152,6 +156,12 @@ __device__ __forceinline__ unsigned long long pp_vmax(const pp_ws_header *hdr) {
         m = o > m ? o : m;
     }
     return m;
+}
+
+// True iff every link's channel time is the same at every cut position (all lanes of a full
+// wave must call; result is uniform).
+__device__ __forceinline__ bool pp_is_flat(const pp_ws_header *hdr) {
+    return __ballot(hdr->flat[threadIdx.x & (PP_PACK_BLOCKS - 1)] != 0) == ~0ull;
 }
 
 __device__ __forceinline__ void pp_raise(int32_t *status, int bit) {

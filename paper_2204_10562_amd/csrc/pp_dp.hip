@@ -30,16 +30,19 @@ struct pack_args {
     const long long *PF, *PB, *XF, *XB;
     pp_ws_header *hdr;
     int *p32, *x32, *xkt, *xct, *ord;  // ord != NULL: write all D! orderings in lexicographic order
+    long long *bfl;                    // [S][L+1] partition DP without channel costs
 };
 
 // x32[link*L + k] = XF + XB at cut position k (k layers before the cut), k = 1..L-1; entry 0
-// is 0.  Returns this thread's largest entry.
-__device__ unsigned long long pack_x(const pack_args &a, size_t first, size_t stride) {
+// is 0.  Returns this thread's largest entry; clears `flat` if an entry differs from the one
+// at the previous cut position of the same link.
+__device__ unsigned long long pack_x(const pack_args &a, size_t first, size_t stride, bool &flat) {
     unsigned long long m = 0;
     for (size_t i = first; i < a.total; i += stride) {
         int k = a.total <= 0xffffffffu ? (int)((unsigned)i % (unsigned)a.L) : (int)(i % (size_t)a.L);
         long long x = 0;
         if (k >= 1) x = a.XF[i - 1] + a.XB[i - 1];
+        if (k >= 2) flat &= (x == a.XF[i - 2] + a.XB[i - 2]);
         a.x32[i] = (int)x;
         unsigned long long ux = x < 0 ? ~0ull : (unsigned long long)x;
         m = ux > m ? ux : m;
@@ -127,11 +130,57 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
     }
 }
 
+// The partition DP with every channel cost taken as zero, which does not depend on the
+// candidate: bfl[0][l] = P[l], bfl[n][l] = min_{n<=k<l} max(bfl[n-1][k], P[l] - P[k]) (infinite
+// for l <= n).  When a link's channel time x_n is the same at every cut position, max with it
+// commutes with the minimum over the split, so the recursion for W(l, xi, r, i) of Sec. IV-B
+// (one replica per stage) gives W[n][l] = max(x_1, ..., x_n, bfl[n][l]) for every ordering;
+// pp_dp_flat.hip builds the plans from that.  Rows are non-decreasing in l and P[l] - P[k]
+// falls as k grows, so a cell is decided at the first split where the two cross (binary
+// search): the value left of the crossing is the difference, right of it the previous row.
+// One workgroup; sh holds P and two rows.
+__device__ void flat_table(const pack_args &a, long long *sh) {
+    const int L = a.L, S = a.S, tid = threadIdx.x;
+    long long *P = sh, *cur = sh + (L + 1), *nxt = cur + (L + 1);
+    for (int l = tid; l <= L; l += 256) {
+        const long long p = a.PF[l] + a.PB[l];
+        P[l] = p;
+        cur[l] = p;
+        a.bfl[l] = p;
+    }
+    __syncthreads();
+    for (int n = 1; n < S; ++n) {
+        for (int l = tid; l <= L; l += 256) {
+            long long best = PP_INF64;
+            if (l >= n + 1) {
+                const long long Pl = P[l];
+                int lo = n, hi = l;  // first split k in [n, l) with row[k] >= P[l] - P[k], or l
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (cur[mid] >= Pl - P[mid]) hi = mid;
+                    else lo = mid + 1;
+                }
+                if (lo <= l - 1) best = cur[lo];
+                if (lo - 1 >= n) {
+                    const long long d = Pl - P[lo - 1];
+                    best = d < best ? d : best;
+                }
+            }
+            nxt[l] = best;
+            a.bfl[(size_t)n * (L + 1) + l] = best;
+        }
+        __syncthreads();
+        long long *t = cur; cur = nxt; nxt = t;
+    }
+}
+
 // Blocks 0..PP_PACK_BLOCKS-1 pack a slice of the tables each and record the largest time of
 // their slice in the header (no atomics, nothing to initialise); further blocks, if any, write
-// the explicit list of all D! orderings.
+// the explicit list of all D! orderings.  Block PP_PACK_BLOCKS builds the channel-free DP table.
 __global__ __launch_bounds__(256) void k_prep(pack_args a) {
+    extern __shared__ __align__(16) long long dyn[];
     __shared__ unsigned long long sh[4];
+    __shared__ int shf[4];
     const int tid = threadIdx.x;
     if (blockIdx.x < PP_PACK_BLOCKS) {
         const unsigned first = blockIdx.x * 256 + tid, stride = PP_PACK_BLOCKS * 256;
@@ -146,7 +195,8 @@ __global__ __launch_bounds__(256) void k_prep(pack_args a) {
             m = pl < 0 ? ~0ull : (unsigned long long)pl;
             if (tid < 64) { a.hdr->work[tid].pairs = 0; a.hdr->work[tid].rows = 0; }
         }
-        unsigned long long mx = pack_x(a, first, stride);
+        bool flat = true;
+        unsigned long long mx = pack_x(a, first, stride, flat);
         m = mx > m ? mx : m;
         pack_xkt(a, first, stride);
         pack_xct(a, first, stride);
@@ -154,15 +204,19 @@ __global__ __launch_bounds__(256) void k_prep(pack_args a) {
             unsigned long long o = __shfl_xor(m, off);
             m = o > m ? o : m;
         }
-        if ((tid & 63) == 0) sh[tid >> 6] = m;
+        const int wflat = __ballot(!flat) == 0;
+        if ((tid & 63) == 0) { sh[tid >> 6] = m; shf[tid >> 6] = wflat; }
         __syncthreads();
         if (tid == 0) {
             for (int w = 1; w < 4; ++w) m = sh[w] > m ? sh[w] : m;
             a.hdr->pmax[blockIdx.x] = m;
+            a.hdr->flat[blockIdx.x] = (unsigned)(shf[0] & shf[1] & shf[2] & shf[3]);
         }
+    } else if (blockIdx.x == PP_PACK_BLOCKS) {
+        flat_table(a, dyn);
     } else {
-        unrank_rows(a, (long long)(blockIdx.x - PP_PACK_BLOCKS) * 256 + tid,
-                    (long long)(gridDim.x - PP_PACK_BLOCKS) * 256);
+        unrank_rows(a, (long long)(blockIdx.x - PP_PACK_BLOCKS - 1) * 256 + tid,
+                    (long long)(gridDim.x - PP_PACK_BLOCKS - 1) * 256);
     }
 }
 
@@ -180,11 +234,12 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
     a.x32 = (int *)(base + lay.x32);
     a.xkt = (int *)(base + lay.xkt);
     a.xct = (int *)(base + lay.xct);
+    a.bfl = (long long *)(base + lay.bfl);
     a.ord = orderings ? NULL : (int *)(base + lay.ord);
     *ord = orderings ? orderings : (const int32_t *)(base + lay.ord);
-    int grid = PP_PACK_BLOCKS;
+    int grid = PP_PACK_BLOCKS + 1;
     if (a.ord) grid += (int)((N + 255) / 256 < 1024 ? (N + 255) / 256 : 1024);
-    hipLaunchKernelGGL(k_prep, dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_prep, dim3(grid), dim3(256), (size_t)3 * (L + 1) * 8, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
@@ -193,6 +248,7 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
 // Both representations in one launch; which one runs depends on the data.
 __global__ __launch_bounds__(256) void k_dp_generic(dp_args a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    if (pp_is_flat(a.hdr)) return;  // k_dp_flat has done the work
     if (pp_vmax(a.hdr) < a.fit_limit) dp_generic_body<false>(a, smem);
     else dp_generic_body<true>(a, smem);
 }
@@ -264,6 +320,12 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     a.bounds_out = bounds_out;
     a.status = status;
     a.nblocks = lay.slots;
+    a.bfl = (const long long *)(base + lay.bfl);
+
+    // channel times that do not depend on the cut position: closed-form plans (the general
+    // kernel enqueued below then returns at once, and the other way round)
+    int rcf = pp_launch_dp_flat(a, st);
+    if (rcf) return rcf;
 
     if (lay.nt) {
         // L <= 128: register-tiled kernel, one wave per candidate (falls back to the generic

@@ -135,6 +135,7 @@ template <int NTL>
 __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     extern __shared__ __align__(16) unsigned char smem[];
     const dp_args &a = b.g;
+    if (pp_is_flat(a.hdr)) return;  // k_dp_flat has done the work
     if (!(pp_vmax(a.hdr) < a.fit_limit)) {
         dp_generic_body<true>(a, smem);  // times too large for 32-bit keys
         return;

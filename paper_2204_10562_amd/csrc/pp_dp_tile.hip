@@ -96,6 +96,7 @@ __device__ __forceinline__ void lds_sync() {
 template <int NT, bool HOIST>
 __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    if (pp_is_flat(a.g.hdr)) return;  // k_dp_flat has done the work
     if (!(pp_vmax(a.g.hdr) < a.g.fit_limit)) {
         dp_generic_body<true>(a.g, smem);  // times too large for 32-bit keys
         return;

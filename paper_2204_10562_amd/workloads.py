@@ -151,10 +151,12 @@ def stress(seed_offset: int = 0, N: int = 1 << 20) -> Workload:
 
 
 def random_small(seed: int, L: int, D: int, S: int, N: int, zero_frac: float = 0.0,
-                 asym: bool = True, hi_time: int = 50, hi_act: int = 4000) -> Workload:
+                 asym: bool = True, hi_time: int = 50, hi_act: int = 4000,
+                 same_act: bool = False) -> Workload:
     """Small adversarial inputs for tests: narrow value ranges (many ties), optional
-    zero durations, asymmetric bandwidth, position-dependent activation sizes,
-    sampled orderings that may use fewer stages than devices."""
+    zero durations, asymmetric bandwidth, position-dependent activation sizes (or, with
+    same_act, one forward and one backward size for every layer boundary, as in a stack of
+    equal blocks), sampled orderings that may use fewer stages than devices."""
     rng = np.random.Generator(np.random.PCG64(seed))
     fwd = rng.integers(0 if zero_frac > 0 else 1, hi_time + 1, size=L).astype(np.int64)
     bwd = rng.integers(0 if zero_frac > 0 else 1, 2 * hi_time + 1, size=L).astype(np.int64)
@@ -168,6 +170,9 @@ def random_small(seed: int, L: int, D: int, S: int, N: int, zero_frac: float = 0
         bw = np.minimum(bw, bw.T)
     np.fill_diagonal(bw, 0)
     orderings = _sample_orderings(rng, N, D)[:, :S].copy()
+    if same_act:
+        actf[:] = actf[0]
+        actb[:] = actb[0]
     return Workload("random_small", L, D, S, N, (1, 2, 3, 5, 8), fwd, bwd, actf, actb, bw, orderings)
 
 

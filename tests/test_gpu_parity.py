@@ -216,6 +216,92 @@ def test_dp_bad_orderings_fault(ppo, G):
         assert st == rc == ppo.FAULT_ORDERING
 
 
+# ---- channel times that do not depend on the cut position (the closed-form kernel)
+
+def ran_closed_form(g):
+    """Which kernel did the last DP call's work: the closed-form one computes no rows."""
+    from paper_2204_10562_amd import binding as pp
+    return pp.read_workspace_stats(g.ws)["rows_executed"] == 0
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL)
+def test_dp_equal_activations_small(ppo, G, seed, L, D, S, N):
+    # ties everywhere, zero-length layers (P not strictly increasing), asymmetric links, S < D
+    w = workloads.random_small(seed + 1000, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500, same_act=True)
+    say("partition_dp equal activations", seed, L, D, S, N)
+    g = G(w)
+    check_dp(ppo, g, w)
+    assert ran_closed_form(g)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", [(1201, 60, 6, 6, 90), (1202, 128, 8, 8, 200), (1203, 300, 9, 9, 64),
+                                           (1204, 2048, 20, 20, 10), (1205, 90, 40, 40, 30), (1206, 700, 70, 64, 9)])
+def test_dp_equal_activations_wider_times(ppo, G, seed, L, D, S, N):
+    # realistic spreads: few ties, long stages, S up to 64 (one wave per workgroup), D > 64
+    w = workloads.random_small(seed, L, D, S, N, hi_time=3000, hi_act=10 ** 7, same_act=True)
+    say("partition_dp equal activations wide spread", seed, L, D, S, N)
+    g = G(w)
+    check_dp(ppo, g, w)
+    assert ran_closed_form(g)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N,shift", [(1211, 40, 4, 4, 50, 26), (1212, 130, 5, 5, 40, 40), (1213, 300, 6, 3, 30, 50)])
+def test_dp_equal_activations_times_beyond_32_bits(ppo, G, seed, L, D, S, N, shift):
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1, hi_time=9, hi_act=300, same_act=True)
+    w.fwd = w.fwd << shift
+    w.bwd = w.bwd << shift
+    w.actf = w.actf << (shift - 3)
+    w.actb = w.actb << (shift - 3)
+    say("partition_dp equal activations wide", seed, L, D, S, N, shift)
+    g = G(w)
+    check_dp(ppo, g, w)
+    assert ran_closed_form(g)
+
+
+def test_dp_equal_activations_detection(ppo, G):
+    # the size after the last layer is not a boundary: it may differ; any other entry decides
+    base = workloads.random_small(1221, 50, 5, 5, 80, hi_time=40, hi_act=900, same_act=True)
+    import copy
+    for where, flat in ((None, True), (49, True), (48, False), (0, False), (17, False)):
+        for arr in ("actf", "actb"):
+            w = copy.copy(base)
+            a = getattr(base, arr).copy()
+            if where is not None:
+                a[where] += 777
+            setattr(w, arr, a)
+            say("partition_dp detection", where, arr, flat)
+            g = G(w)
+            check_dp(ppo, g, w)
+            assert ran_closed_form(g) == flat, (where, arr)
+
+
+def test_dp_equal_activations_all_orderings_and_faults(ppo, G):
+    import math
+    w = workloads.random_small(1231, 30, 7, 7, 1, hi_time=60, hi_act=5000, same_act=True)
+    w.orderings = None
+    w.N = math.factorial(7)
+    say("partition_dp equal activations, all 7! orderings")
+    g = G(w)
+    check_dp(ppo, g, w)
+    assert ran_closed_form(g)
+    # bad rows in a caller's list raise the fault and leave the other candidates alone
+    w = workloads.random_small(1232, 25, 6, 5, 200, hi_time=60, hi_act=5000, same_act=True)
+    tables = oracle_tables(ppo, w)
+    good = ppo.partition_dp(w.L, w.D, w.S, w.N, *tables, w.orderings)
+    v = sub_workload(w, np.arange(w.N))
+    v.orderings[13, 2] = v.orderings[13, 0]
+    v.orderings[63, 4] = 6
+    v.orderings[199, 0] = -1
+    say("partition_dp equal activations, faults")
+    g = G(v)
+    g.set_tables(*tables)
+    st, C, b = g.dp()
+    assert st == ppo.FAULT_ORDERING == ppo.partition_dp(v.L, v.D, v.S, v.N, *tables, v.orderings)[0]
+    keep = np.array([c for c in range(w.N) if c not in (13, 63, 199)])
+    np.testing.assert_array_equal(C[keep], good[1][keep])
+    np.testing.assert_array_equal(b[keep], good[2][keep])
+
+
 def test_dp_work_counters(ppo, G):
     from paper_2204_10562_amd import binding as pp
     # generic kernel (L > 128): every row of every candidate is computed
@@ -230,7 +316,11 @@ def test_dp_work_counters(ppo, G):
     assert st["pairs_executed"] == N * per and st["rows_executed"] == N * (S - 1)
     # tiled kernel, all orderings in lexicographic order: shared rows are computed once,
     # so the count lies between one row per distinct ordering prefix and the full count
+    # (one activation size changed, so that the transfer times depend on the cut position
+    # and the general kernel runs)
     w = workloads.transformer()
+    w.actf = w.actf.copy()
+    w.actf[7] += 1 << 20
     g = G(w)
     assert g.prefix() == 0
     say("work counters tiled")

@@ -65,6 +65,19 @@ def test_stages_adversarial_small(ppo, G, seed, L, D, S, N):
     check_stages(ppo, g, w, (1, 5, 40), tables)
 
 
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL)
+def test_stages_equal_activations_small(ppo, G, seed, L, D, S, N):
+    # transfer times that do not depend on the cut position: the closed-form DP kernel
+    w = workloads.random_small(seed + 2000, L, D, S, N, zero_frac=0.15, hi_time=7, hi_act=500, same_act=True)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("stages equal activations", seed, L, D, S, N)
+    check_stages(ppo, g, w, (1, 5, 40), tables)
+    from paper_2204_10562_amd import binding as pp
+    assert pp.read_workspace_stats(g.ws)["rows_executed"] == 0
+
+
 @pytest.mark.parametrize("seed,L,D,S,N,shift", [(211, 40, 4, 4, 50, 26), (212, 130, 5, 5, 40, 40)])
 def test_stages_wide_values(ppo, G, seed, L, D, S, N, shift):
     # times too large for 32-bit keys: the int64 representation
