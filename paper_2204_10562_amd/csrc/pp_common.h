@@ -64,7 +64,8 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.x32 = off;    off += pp_align256((size_t)D * D * L * 4);
     w.xkt = off;    off += pp_align256((size_t)D * D * 8 * w.nt * 4);
     w.xct = off;    off += pp_align256((size_t)D * D * 16 * ((w.nt + 1) / 2) * 4);
-    w.bfl = off;    off += pp_align256((size_t)S * (L + 1) * 8);  // channel-free DP table, [S][L+1] int64
+    // channel-free DP table: values [S][L+1] int64, then lowest minimising splits [S][L+1] int32
+    w.bfl = off;    off += pp_align256((size_t)S * (L + 1) * 12);
     w.ord = off;    off += pp_align256((size_t)N * S * 4);
     w.slots = (int)(N < PP_DP_SLOTS ? N : PP_DP_SLOTS);
     w.arg = off;    off += pp_align256((size_t)w.slots * S * (L + 128) * 2);  // rows padded to 128 cells

@@ -9,14 +9,11 @@
 // cell is a 32-bit key (time << K) | k: the max of two keys whose low bits both equal k keeps
 // k, so a plain integer min over k yields the smallest time and, among equal times, the
 // lowest k - the required tie-break - at three integer operations per (cell, split) pair.
-// Otherwise cells are int64 with an explicit strict-less update.  Which one applies depends
-// on the data, which the host cannot see without synchronising, so both kernels are enqueued
-// and the one whose turn it is not returns at once.
-#include <stdlib.h>
-
-#include <type_traits>
-
-#include <stdio.h>
+// Otherwise cells are int64 with an explicit strict-less update.  And when no link's channel
+// time depends on the cut position the whole program has a closed form (pp_dp_flat.h).  Which
+// of the three applies depends on the data, which the host cannot see without synchronising:
+// the pack kernel leaves what is needed to tell in the workspace header, and the one kernel
+// enqueued after it branches on that.
 #include "pp_common.h"
 #include "pp_dp_generic.h"
 #include "pp_dp_tile.h"
@@ -131,27 +128,31 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
 }
 
 // The partition DP with every channel cost taken as zero, which does not depend on the
-// candidate: bfl[0][l] = P[l], bfl[n][l] = min_{n<=k<l} max(bfl[n-1][k], P[l] - P[k]) (infinite
-// for l <= n).  When a link's channel time x_n is the same at every cut position, max with it
-// commutes with the minimum over the split, so the recursion for W(l, xi, r, i) of Sec. IV-B
-// (one replica per stage) gives W[n][l] = max(x_1, ..., x_n, bfl[n][l]) for every ordering;
-// pp_dp_flat.hip builds the plans from that.  Rows are non-decreasing in l and P[l] - P[k]
-// falls as k grows, so a cell is decided at the first split where the two cross (binary
-// search): the value left of the crossing is the difference, right of it the previous row.
-// One workgroup; sh holds P and two rows.
+// candidate: B[0][l] = P[l], B[n][l] = min_{n<=k<l} max(B[n-1][k], P[l] - P[k]) (infinite for
+// l <= n), and A[n][l] = the lowest minimising k.  pp_dp_flat.h builds every candidate's plan
+// from these two tables when no link's channel time depends on the cut position.  Rows are
+// non-decreasing in l and P[l] - P[k] falls as k grows, so a cell is decided at the first
+// split k* where the two cross (binary search): left of it the difference is the larger term,
+// from it on the previous row.  If the difference just left of the crossing is no larger than
+// the row value at it, the minimum sits there, at the lowest split with that same prefix sum
+// (zero-length layers make equal neighbours); otherwise at k*.
+// One workgroup; sh holds P and two rows.  a.bfl: B [S][L+1] int64, then A [S][L+1] int32.
 __device__ void flat_table(const pack_args &a, long long *sh) {
     const int L = a.L, S = a.S, tid = threadIdx.x;
     long long *P = sh, *cur = sh + (L + 1), *nxt = cur + (L + 1);
+    int *A = (int *)(a.bfl + (size_t)S * (L + 1));
     for (int l = tid; l <= L; l += 256) {
         const long long p = a.PF[l] + a.PB[l];
         P[l] = p;
         cur[l] = p;
         a.bfl[l] = p;
+        A[l] = 0;
     }
     __syncthreads();
     for (int n = 1; n < S; ++n) {
         for (int l = tid; l <= L; l += 256) {
             long long best = PP_INF64;
+            int arg = 0;
             if (l >= n + 1) {
                 const long long Pl = P[l];
                 int lo = n, hi = l;  // first split k in [n, l) with row[k] >= P[l] - P[k], or l
@@ -160,14 +161,21 @@ __device__ void flat_table(const pack_args &a, long long *sh) {
                     if (cur[mid] >= Pl - P[mid]) hi = mid;
                     else lo = mid + 1;
                 }
+                arg = lo;
                 if (lo <= l - 1) best = cur[lo];
                 if (lo - 1 >= n) {
                     const long long d = Pl - P[lo - 1];
-                    best = d < best ? d : best;
+                    if (d <= best) {
+                        best = d;
+                        int k = lo - 1;
+                        while (k > n && P[k - 1] == P[k]) --k;
+                        arg = k;
+                    }
                 }
             }
             nxt[l] = best;
             a.bfl[(size_t)n * (L + 1) + l] = best;
+            A[(size_t)n * (L + 1) + l] = arg;
         }
         __syncthreads();
         long long *t = cur; cur = nxt; nxt = t;
@@ -243,15 +251,7 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
-// ---------------------------------------------------------------- generic kernel
-
-// Both representations in one launch; which one runs depends on the data.
-__global__ __launch_bounds__(256) void k_dp_generic(dp_args a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    if (pp_is_flat(a.hdr)) return;  // k_dp_flat has done the work
-    if (pp_vmax(a.hdr) < a.fit_limit) dp_generic_body<false>(a, smem);
-    else dp_generic_body<true>(a, smem);
-}
+// ---------------------------------------------------------------- launch policy
 
 // Consecutive candidates one wave of the tiled kernel walks.
 //
@@ -322,11 +322,6 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     a.nblocks = lay.slots;
     a.bfl = (const long long *)(base + lay.bfl);
 
-    // channel times that do not depend on the cut position: closed-form plans (the general
-    // kernel enqueued below then returns at once, and the other way round)
-    int rcf = pp_launch_dp_flat(a, st);
-    if (rcf) return rcf;
-
     if (lay.nt) {
         // L <= 128: register-tiled kernel, one wave per candidate (falls back to the generic
         // int64 body inside the same launch when the times do not fit 32-bit keys)
@@ -344,35 +339,17 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         int wpb = 4;  // waves per workgroup, limited by 64 KiB of LDS
         while (wpb > 1 && lds_wave * wpb > 64 * 1024) wpb >>= 1;
         if (lds_wave * wpb > 64 * 1024) return PP_ERR_INVALID_ARG;  // cannot happen for S <= 64
-        t.hoist = 1;
-        if (const char *e = getenv("PP_DP_HOIST")) t.hoist = atoi(e) != 0;
-        t.prio = 1;
-        if (const char *e = getenv("PP_DP_PRIO")) t.prio = atoi(e) != 0;
-        int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
-        if (!t.hoist) waves_per_simd = 4;
-        if (const char *e = getenv("PP_DP_WPS")) { int v = atoi(e); if (v >= 1 && v <= 8) waves_per_simd = v; }
+        const int waves_per_simd = lay.nt >= 14 ? 2 : (lay.nt >= 12 ? 3 : 4);
         t.chunk = choose_chunk(N, D, lex_ord != NULL, (long long)cus * 4, waves_per_simd);
-        // tuning overrides for experiments: PP_DP_CHUNK (candidates per wave), PP_DP_WPB (waves
-        // per workgroup); the results do not depend on either
-        if (const char *e = getenv("PP_DP_CHUNK")) { long long v = atoll(e); if (v >= 1) t.chunk = v; }
-        if (const char *e = getenv("PP_DP_WPB")) {
-            int v = atoi(e);
-            if (v >= 1 && v <= 4 && lds_wave * v <= 64 * 1024) wpb = v;
-        }
         {
             // Priority levels end when a tenth, a quarter and half of the chunk are left: the
             // two waves of a SIMD drift apart while they are on the same level and are pulled
             // together at each boundary, so the levels get shorter towards the end (measured at
-            // GPT size against equal quarters: 65.8 against 67.1 us).  Experiment knob:
-            // PP_DP_PRIO_LEFT=a,b,c.
+            // GPT size against equal quarters: 65.8 against 67.1 us).
             const long long frac[3] = {10, 4, 2};
             for (int k = 0; k < 3; ++k) {
                 long long v = t.chunk / frac[k];
                 t.prio_left[k] = (int)(v > 0x3fffffff ? 0x3fffffff : v);
-            }
-            if (const char *e = getenv("PP_DP_PRIO_LEFT")) {
-                int x, y, z;
-                if (sscanf(e, "%d,%d,%d", &x, &y, &z) == 3) { t.prio_left[0] = x; t.prio_left[1] = y; t.prio_left[2] = z; }
             }
         }
         const long long nchunks = (N + t.chunk - 1) / t.chunk;
@@ -381,19 +358,12 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         t.g = a;
         return pp_launch_dp_tile(t, lay.nt, grid, wpb, st);
     }
-    // L > 128: super-tiled kernel, one persistent wave per candidate slot.  PP_DP_GENERIC=1
-    // selects the plain one-workgroup-per-candidate kernel instead (for comparison).
-    const char *e = getenv("PP_DP_GENERIC");
-    if (!(e && atoi(e) == 1)) {
-        int cus = 256;
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            cus = 256;
-        long long waves = lay.slots < N ? lay.slots : N;
-        return pp_launch_dp_big(a, (int)waves, cus, st);
-    }
-    int block = 256;
-    hipLaunchKernelGGL(k_dp_generic, dim3(a.nblocks), dim3(block), (size_t)3 * (L + 1) * 8, st, a);
-    return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
+    // L > 128: super-tiled kernel, one persistent wave per candidate slot
+    int cus = 256;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        cus = 256;
+    long long waves = lay.slots < N ? lay.slots : N;
+    return pp_launch_dp_big(a, (int)waves, cus, st);
 }

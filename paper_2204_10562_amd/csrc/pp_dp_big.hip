@@ -20,6 +20,7 @@
 // g is built (one coalesced pass), and the plan is read back from there with cache-bypassing
 // loads.  Waves are persistent and walk candidates wave, wave + nwaves, ...
 #include "pp_common.h"
+#include "pp_dp_flat.h"
 #include "pp_dp_generic.h"
 
 #define DPP_QUAD_XOR1 0xB1     // quad_perm:[1,0,3,2]
@@ -135,7 +136,10 @@ template <int NTL>
 __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     extern __shared__ __align__(16) unsigned char smem[];
     const dp_args &a = b.g;
-    if (pp_is_flat(a.hdr)) return;  // k_dp_flat has done the work
+    if (pp_is_flat(a.hdr)) {
+        dp_flat_body(a, smem, a.lds_bytes);  // no channel time depends on the cut position
+        return;
+    }
     if (!(pp_vmax(a.hdr) < a.fit_limit)) {
         dp_generic_body<true>(a, smem);  // times too large for 32-bit keys
         return;
@@ -292,7 +296,10 @@ int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, hipStream_t st) {
     size_t lds = (size_t)(1 + 2 * wpb) * RS * 4;
     const size_t generic = (size_t)3 * (g.L + 1) * 8;  // the int64 fallback's rows
     if (lds < generic) lds = generic;
+    const size_t flat = pp_flat_lds_wanted(g.L, g.D, g.S, wpb);  // the closed-form body's tables
+    if (lds < flat) lds = flat;
     if (lds > 64 * 1024) return PP_ERR_INVALID_ARG;
+    b.g.lds_bytes = lds;
     // resident waves: 4 per SIMD by registers, and what 160 KiB of LDS per CU allow
     long long per_cu = (long long)(160 * 1024 / lds) * wpb;
     if (per_cu > 16) per_cu = 16;

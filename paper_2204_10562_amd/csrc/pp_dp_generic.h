@@ -19,7 +19,8 @@ struct dp_args {
     int validate;    // the list came from the caller: check every row
     pp_ws_header *hdr;
     const int *p32, *x32;
-    const long long *bfl;  // [S][L+1] the partition DP with no channel cost (row 0 = P), see pp_dp_flat.hip
+    const long long *bfl;  // the partition DP with no channel cost (values, then splits), see pp_dp_flat.h
+    size_t lds_bytes;      // dynamic LDS of the launch
     unsigned short *arg;  // [nblocks][S][L+1] backtrack tables, one per working workgroup
     int nblocks;          // workgroups that take part (the rest of the grid returns)
     // stages == 0: C_out [N], bounds_out [N][S]: the plan with S stages.
@@ -31,11 +32,6 @@ struct dp_args {
     int *bounds_out;
     int32_t *status;
 };
-
-// Closed-form path for channel times that do not depend on the cut position (pp_dp_flat.hip):
-// enqueued before the general kernel; exactly one of the two does the work, decided on the
-// device from the workspace header.
-int pp_launch_dp_flat(const dp_args &g, hipStream_t st);
 
 // Kernel for 128 < L with 32-bit keys (pp_dp_big.hip): persistent waves, as many as fit the
 // GPU (cus compute units) but at most max_waves (the backtrack tables the workspace holds).

@@ -12,8 +12,6 @@ struct dp_tile_args {
     long long N;
     long long chunk;  // consecutive candidates walked by one wave
     int validate;     // orderings came from the caller: check them
-    int hoist;        // keep the candidate-independent difference keys in registers
-    int prio;         // waves raise their issue priority with the share of their chunk still to do
     int prio_left[3]; // priority k+1 while more than prio_left[k] candidates of the chunk are left
     const int *xkt;   // [link][b][j] keys ((XF+XB) << K) | k for k = 8j+b, infinite if k == 0 or k >= L
     const int *xct;   // [link][a][h][r] the same keys for the cells l = 8(hH+r)+a+1, H = ceil(nt/2)

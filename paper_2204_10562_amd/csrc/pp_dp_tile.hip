@@ -26,6 +26,7 @@
 // arena rows make up its path, and the plans of up to 64 finished candidates are read back
 // together, one candidate per lane.
 #include "pp_common.h"
+#include "pp_dp_flat.h"
 #include "pp_dp_tile.h"
 
 #define DPP_QUAD_XOR1 0xB1     // quad_perm:[1,0,3,2]
@@ -93,10 +94,13 @@ __device__ __forceinline__ void lds_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int NT, bool HOIST>
+template <int NT>
 __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    if (pp_is_flat(a.g.hdr)) return;  // k_dp_flat has done the work
+    if (pp_is_flat(a.g.hdr)) {
+        dp_flat_body(a.g, smem, a.g.lds_bytes);  // no channel time depends on the cut position
+        return;
+    }
     if (!(pp_vmax(a.g.hdr) < a.g.fit_limit)) {
         dp_generic_body<true>(a.g, smem);  // times too large for 32-bit keys
         return;
@@ -126,9 +130,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     if (c0 >= c1) return;
 
     // candidate-independent part: Dp[i][j] = ((P[l] - P[k]) << K) | k, or infinite if k >= l
-    // (HOIST = false keeps only P[l] << K and (P[k] << K) - k and subtracts in the loop:
-    // more arithmetic per pair, far fewer registers, more resident waves)
-    int Dp[HOIST ? NT * (NT + 1) / 2 : 1];
+    int Dp[NT * (NT + 1) / 2];
     int Pl[NT], Pk[NT];
     {
 #pragma unroll
@@ -136,16 +138,14 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
             Pl[i] = a.g.p32[8 * i + la + 1] << K;
             Pk[i] = (a.g.p32[8 * i + lb] << K) - (8 * i + lb);
         }
-        if (HOIST) {
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+        for (int i = 0; i < NT; ++i)
 #pragma unroll
-                for (int j = 0; j <= i; ++j) {
-                    int d = (j < i || lb <= la) ? Pl[i] - Pk[j] : PP_INF32;
-                    asm volatile("" : "+v"(d));  // keep the masked value, not the mask, in the loop
-                    Dp[i * (i + 1) / 2 + j] = d;
-                }
-        }
+            for (int j = 0; j <= i; ++j) {
+                int d = (j < i || lb <= la) ? Pl[i] - Pk[j] : PP_INF32;
+                asm volatile("" : "+v"(d));  // keep the masked value, not the mask, in the loop
+                Dp[i * (i + 1) / 2 + j] = d;
+            }
         // row 0: one stage holding the first l layers (same for every candidate)
         if (lb == 0) {
 #pragma unroll
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     // reduction a lane holds the cells l = 8 (h H + r) + a + 1 (h = b / 4, r = 0..H-1), and
     // DL[r] = ((P[L] - P[l]) << K) | l (infinite for l >= L) is the difference key of cell L
     // against the split after l layers.
-    constexpr bool FUSE = HOIST;
+    constexpr bool FUSE = true;
     constexpr int HC = (NT + 1) / 2;
     int DL[FUSE ? HC : 1];
     if (FUSE) {
@@ -178,9 +178,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
 
     // the difference key of block (i, j)
     auto dkey = [&](int i, int j) __attribute__((always_inline)) -> int {
-        if (HOIST) return Dp[i * (i + 1) / 2 + j];
-        int d = Pl[i] - Pk[j];
-        return (j < i || lb <= la) ? d : PP_INF32;
+        return Dp[i * (i + 1) / 2 + j];
     };
     const unsigned long long smask = S >= 64 ? ~0ull : ((1ull << S) - 1);
     const int top_lane = ((L - 1) & 7) * 8;  // a lane that owns cell L (in tile NT-1)
@@ -305,15 +303,13 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
         // c is a valid candidate whose rows first..S-1 are to be computed; xk holds (or is
         // about to receive) the channel keys of row `first`
         fresh = false;
-        if (a.prio) {
-            // Of the waves that share a SIMD the one with more of its chunk still to do issues
-            // first, so that they finish together and none runs alone at the end (levels from
-            // thresholds worked out once: a division here costs as much as a tenth of a row).
-            if (c <= prio_until[2]) __builtin_amdgcn_s_setprio(3);
-            else if (c <= prio_until[1]) __builtin_amdgcn_s_setprio(2);
-            else if (c <= prio_until[0]) __builtin_amdgcn_s_setprio(1);
-            else __builtin_amdgcn_s_setprio(0);
-        }
+        // Of the waves that share a SIMD the one with more of its chunk still to do issues
+        // first, so that they finish together and none runs alone at the end (levels from
+        // thresholds worked out once: a division here costs as much as a tenth of a row).
+        if (c <= prio_until[2]) __builtin_amdgcn_s_setprio(3);
+        else if (c <= prio_until[1]) __builtin_amdgcn_s_setprio(2);
+        else if (c <= prio_until[0]) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
         const bool more = c + 1 < c1;
         int v_on = (more && lane < S) ? ord[(c + 1) * S + lane] : 0;
         int first_n = -2, v_link_n = 0;  // next candidate: -2 none, -1 bad ordering
@@ -361,11 +357,6 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
             }
             fetch_x(xf, next_link);
 
-            if (!HOIST) {
-                // the differences are formed per row; do not let them be hoisted out again
-#pragma unroll
-                for (int j = 0; j < NT; ++j) asm volatile("" : "+v"(Pk[j]));
-            }
             int *nrow = rows + n * RS;
             // the previous row is read through an index of its own, so that the NT reads are
             // one address and NT immediate offsets (seen as nrow minus a constant the offsets
@@ -490,8 +481,7 @@ __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
 
 template <int NT>
 static int launch_nt(const dp_tile_args &a, int grid, int wpb, size_t lds, hipStream_t st) {
-    if (a.hoist) hipLaunchKernelGGL((k_dp_tile<NT, true>), dim3(grid), dim3(64 * wpb), lds, st, a);
-    else hipLaunchKernelGGL((k_dp_tile<NT, false>), dim3(grid), dim3(64 * wpb), lds, st, a);
+    hipLaunchKernelGGL(k_dp_tile<NT>, dim3(grid), dim3(64 * wpb), lds, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
@@ -499,8 +489,12 @@ int pp_launch_dp_tile(const dp_tile_args &a, int nt, int grid, int wpb, hipStrea
     size_t lds = (size_t)wpb * pp_dp_tile_lds_per_wave(a.S, nt);
     const size_t generic = (size_t)3 * (a.L + 1) * 8;  // the int64 fallback's rows
     if (lds < generic) lds = generic;
+    const size_t flat = pp_flat_lds_wanted(a.L, a.D, a.S, wpb);  // the closed-form body's tables
+    if (lds < flat) lds = flat;
+    dp_tile_args b = a;
+    b.g.lds_bytes = lds;
     switch (nt) {
-#define CASE(n) case n: return launch_nt<n>(a, grid, wpb, lds, st);
+#define CASE(n) case n: return launch_nt<n>(b, grid, wpb, lds, st);
         CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
         CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
 #undef CASE
