@@ -154,6 +154,22 @@ int pp_schedule_makespan(int L, int D, int S, int64_t N, int M,
                          int64_t *T_out, int32_t *status, void *stream);
 
 /*
+ * pp_schedule_makespan for several microbatch counts in one launch (Alg. 1 once
+ * per count on the same plans): the plans' block durations are gathered once
+ * and the counts are scheduled side by side.
+ *   nM      number of microbatch counts, 1..PP_MAX_M_LIST
+ *   M_list  [nM] HOST array, every entry >= 1
+ *   T_out   [nM*N], T of candidate c for M_list[q] at q*N + c
+ * Same faults as pp_schedule_makespan.
+ */
+int pp_schedule_makespan_multi(int L, int D, int S, int64_t N, int nM,
+                               const int32_t *M_list, const int64_t *PF,
+                               const int64_t *PB, const int64_t *XF,
+                               const int64_t *XB, const int32_t *orderings,
+                               const int32_t *bounds, int64_t *T_out,
+                               int32_t *status, void *stream);
+
+/*
  * pp_schedule_makespan under a comparison schedule.  The timing rule is that of
  * Alg. 1's scheduling phase in every case (an item starts when its microbatch
  * has left the preceding block and its resource is idle; resources follow their

@@ -24,7 +24,7 @@ PP_FAULT_OVERFLOW = 16
 PP_MAX_STAGES = 64
 
 EXPORTS = ("pp_prefix_costs", "pp_workspace_bytes", "pp_partition_dp", "pp_schedule_makespan",
-           "pp_schedule_makespan_variant",
+           "pp_schedule_makespan_multi", "pp_schedule_makespan_variant",
            "pp_best_plan", "pp_best_plan_static", "pp_best_plan_multi", "pp_workspace_bytes_stages", "pp_partition_dp_stages",
            "pp_best_plan_stages", "pp_workspace_bytes_replicated", "pp_plan_replicated", "pp_rdo_order",
            "pp_strerror")
@@ -81,6 +81,8 @@ def lib():
         L.pp_partition_dp.restype = i32
         L.pp_schedule_makespan.argtypes = [i32, i32, i32, i64, i32] + [vp] * 7 + [vp, vp]
         L.pp_schedule_makespan.restype = i32
+        L.pp_schedule_makespan_multi.argtypes = [i32, i32, i32, i64, i32] + [vp] * 8 + [vp, vp]
+        L.pp_schedule_makespan_multi.restype = i32
         L.pp_schedule_makespan_variant.argtypes = [i32, i32, i32, i32, i64, i32] + [vp] * 7 + [vp, vp]
         L.pp_schedule_makespan_variant.restype = i32
         L.pp_best_plan.argtypes = [i32, i32, i32, i64, i32] + [vp] * 8 + [vp, sz, vp, vp]
@@ -163,6 +165,19 @@ def pp_schedule_makespan(L, D, S, N, M, PF, PB, XF, XB, orderings, bounds, T_out
         _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
         _ptr(orderings, i32, N * S, "orderings", optional=True),
         _ptr(bounds, i32, N * S, "bounds"), _ptr(T_out, i64, N, "T_out"),
+        _ptr(status, i32, 1, "status"), _stream()))
+
+
+def pp_schedule_makespan_multi(L, D, S, N, M_list, PF, PB, XF, XB, orderings, bounds, T_out, status):
+    """M_list is a host sequence of ints; T_out holds len(M_list) * N values."""
+    i64, i32 = torch.int64, torch.int32
+    nM = len(M_list)
+    Ms = (ctypes.c_int32 * nM)(*[int(m) for m in M_list])
+    _check(lib().pp_schedule_makespan_multi(
+        L, D, S, N, nM, ctypes.cast(Ms, ctypes.c_void_p), _ptr(PF, i64, L + 1, "PF"),
+        _ptr(PB, i64, L + 1, "PB"), _ptr(XF, i64, D * D * L, "XF"), _ptr(XB, i64, D * D * L, "XB"),
+        _ptr(orderings, i32, N * S, "orderings", optional=True),
+        _ptr(bounds, i32, N * S, "bounds"), _ptr(T_out, i64, N * nM, "T_out"),
         _ptr(status, i32, 1, "status"), _stream()))
 
 

@@ -58,6 +58,18 @@ def build_libpp(verbose=False, incremental=False):
     return LIB_PATH
 
 
+CALIB_PATH = os.path.join(_PKG, "libpp_calib.so")
+
+
+def build_calib(verbose=False):
+    """Compile the benchmark's calibration kernels (csrc/calib/) into libpp_calib.so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(_PKG, "csrc", "calib", "pp_calib.hip")
+    _run([hipcc, "-shared"] + HIPCC_FLAGS + [src, "-o", CALIB_PATH], verbose)
+    return CALIB_PATH
+
+
 if __name__ == "__main__":
     import sys
     print(build_libpp(verbose=True, incremental="--incremental" in sys.argv))
+    print(build_calib(verbose=True))

@@ -115,6 +115,21 @@ extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const
                               status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
+extern "C" int pp_schedule_makespan_multi(int L, int D, int S, int64_t N, int nM,
+                                          const int32_t *M_list, const int64_t *PF,
+                                          const int64_t *PB, const int64_t *XF, const int64_t *XB,
+                                          const int32_t *orderings, const int32_t *bounds,
+                                          int64_t *T_out, int32_t *status, void *stream) {
+    int rc = pp_check_sizes(L, D, S, N, orderings);
+    if (rc) return rc;
+    if (nM < 1 || nM > PP_MAX_M_LIST || !M_list || !PF || !PB || !XF || !XB || !bounds || !T_out)
+        return PP_ERR_INVALID_ARG;
+    for (int q = 0; q < nM; ++q)
+        if (M_list[q] < 1) return PP_ERR_INVALID_ARG;
+    return pp_launch_makespan(L, D, S, N, nM, M_list, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
+                              status, NULL, NULL, NULL, NULL, (hipStream_t)stream);
+}
+
 extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
                                             const int64_t *PF, const int64_t *PB, const int64_t *XF,
                                             const int64_t *XB, const int32_t *orderings,

@@ -66,6 +66,16 @@ class GpuProblem:
                                 self.status)
         return self.take_status(), T.cpu().numpy()
 
+    def makespan_multi(self, Ms, bounds, orderings="default", N=None, S=None):
+        w = self.w
+        N, S = N or w.N, S or w.S
+        o = self.orderings if isinstance(orderings, str) else orderings
+        b = torch.from_numpy(np.ascontiguousarray(bounds, dtype=np.int32).reshape(-1)).to(self.dev)
+        T = torch.empty(N * len(Ms), dtype=torch.int64, device=self.dev)
+        pp.pp_schedule_makespan_multi(w.L, w.D, S, N, list(Ms), self.PF, self.PB, self.XF, self.XB, o, b, T,
+                                      self.status)
+        return self.take_status(), T.cpu().numpy().reshape(len(Ms), N)
+
     def best(self, M, orderings="default", N=None, S=None, want_all=True):
         w = self.w
         N, S = N or w.N, S or w.S

@@ -120,6 +120,17 @@ def gpt(seed_offset: int = 0) -> Workload:
     return Workload("gpt", L, D, D, math.factorial(D), (8, 16, 32, 64), fwd, bwd, act, act.copy(), bw)
 
 
+def gpt_varied(seed_offset: int = 0) -> Workload:
+    """The GPT-shaped configuration with activation sizes that differ from boundary to boundary
+    (16 MiB x U[0.5, 2), from a generator of its own so that every other draw is config 3's):
+    same L, D, N and value ranges, but the transfer times depend on the cut position, which is
+    the case the general partition-DP kernel exists for."""
+    w = gpt(seed_offset)
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 3 + 1009 + seed_offset))
+    act = _rint(16 * MIB * rng.uniform(0.5, 2.0, size=w.L))
+    return Workload("gpt_varied", w.L, w.D, w.S, w.N, w.Ms, w.fwd, w.bwd, act, act.copy(), w.bw)
+
+
 def hetero(seed_offset: int = 0, N: int = 10 ** 6) -> Workload:
     """Config 4: L=300 conv-net-shaped, D=16, N seed-sampled orderings, M in {16, 32}."""
     rng = _rng(4, seed_offset)
@@ -177,6 +188,8 @@ def random_small(seed: int, L: int, D: int, S: int, N: int, zero_frac: float = 0
 
 
 CONFIGS = {"tiny": tiny, "transformer": transformer, "gpt": gpt, "hetero": hetero, "stress": stress}
+# the five configurations plus variants used by the benchmark and the tests
+WORKLOADS = dict(CONFIGS, gpt_varied=gpt_varied)
 
 
 def pair_evals_per_candidate(L: int, S: int) -> int:

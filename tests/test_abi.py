@@ -75,6 +75,12 @@ def test_host_side_argument_errors_enqueue_nothing(libpp):
     assert libpp.pp_best_plan_multi(16, 4, 4, 24, 2, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1  # M = 0
     assert libpp.pp_best_plan_multi(16, 4, 4, 24, 17, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1
     assert libpp.pp_best_plan_multi(16, 4, 4, 24, 0, mp, one, one, one, one, z, one, z, z, one, 1 << 30, z, z) == -1
+    assert libpp.pp_schedule_makespan_multi(16, 4, 4, 24, 2, mp, one, one, one, one, z, one, one, z, z) == -1  # M = 0
+    assert libpp.pp_schedule_makespan_multi(16, 4, 4, 24, 17, mp, one, one, one, one, z, one, one, z, z) == -1
+    assert libpp.pp_schedule_makespan_multi(16, 4, 4, 24, 1, mp, one, one, one, one, z, z, one, z, z) == -1   # no bounds
+    # the entry point without a workspace argument: sizes beyond its array are refused
+    assert libpp.pp_best_plan_static(300, 16, 16, 200000, 4, one, one, one, one, one, one, z, z, z, z) == -2
+    assert libpp.pp_best_plan_static(16, 4, 4, 24, 0, one, one, one, one, z, one, z, z, z, z) == -1
 
 
 def test_stage_search_and_replicated_argument_errors(libpp):

@@ -345,6 +345,45 @@ def random_bounds(rng, N, S, L):
 
 
 @pytest.mark.parametrize("name", ["tiny", "transformer", "gpt"])
+def test_makespan_multi_full_configs(ppo, G, name):
+    # several microbatch counts in one launch, on the DP's plans of every candidate
+    w = workloads.CONFIGS[name]()
+    g = G(w)
+    assert g.prefix() == 0
+    tables = oracle_tables(ppo, w)
+    rc, C0, b0 = ppo.partition_dp(w.L, w.D, w.S, w.N, *tables, w.orderings)
+    assert rc == 0
+    Ms = tuple(w.Ms) + (1, 3, 29)
+    say("makespan_multi", name, Ms)
+    st, T = g.makespan_multi(Ms, b0)
+    assert st == 0
+    for q, M in enumerate(Ms):
+        rc, T0 = ppo.schedule_makespan(w.L, w.D, w.S, w.N, M, *tables, w.orderings, b0)
+        assert rc == 0
+        np.testing.assert_array_equal(T[q], T0)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N", [(1301, 40, 5, 5, 130), (1302, 90, 12, 12, 70), (1303, 300, 20, 20, 65),
+                                           (1304, 200, 40, 33, 40), (1305, 9, 3, 1, 5)])
+def test_makespan_multi_arbitrary_plans(ppo, G, seed, L, D, S, N):
+    # any valid plan, every kernel family (registers, 17..32 stages, LDS columns), 1..16 counts
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1, hi_time=30, hi_act=3000)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bounds = random_bounds(rng, N, S, L)
+    for Ms in ((7,), (2, 50), (1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 100)):
+        say("makespan_multi arbitrary", seed, L, D, S, N, Ms)
+        st, T = g.makespan_multi(Ms, bounds)
+        assert st == 0
+        for q, M in enumerate(Ms):
+            rc, T0 = ppo.schedule_makespan(L, D, S, N, M, *tables, w.orderings, bounds)
+            assert rc == 0
+            np.testing.assert_array_equal(T[q], T0)
+
+
+@pytest.mark.parametrize("name", ["tiny", "transformer", "gpt"])
 def test_makespan_full_configs(ppo, G, name):
     w = workloads.CONFIGS[name]()
     g = G(w)
