@@ -107,21 +107,39 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
 // stages == 0: C_out [N], bounds_out [N][S].  stages == 1: the plans for every stage count
 // xi = 1..S on the first xi devices: C_out [N][S], bounds_out [N][S(S+1)/2], the xi bounds of
 // stage count xi at offset xi(xi-1)/2.
+// defer_mmax > 0: see pp_fuse_info (the plans are left to the makespan kernel that follows when
+// the closed form applies and the times for defer_mmax microbatches fit 32 bits).
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
-                 const int32_t *user_ord, int stages, int64_t *C_out, int32_t *bounds_out,
-                 void *ws, const pp_ws_layout &lay, int32_t *status, hipStream_t st);
+                 const int32_t *user_ord, int stages, int defer_mmax, int64_t *C_out,
+                 int32_t *bounds_out, void *ws, const pp_ws_layout &lay, int32_t *status,
+                 hipStream_t st);
 // Makespan of every candidate's plan for each of the nM microbatch counts in Ms (host array).
 // With part/C/out non-NULL the launch also finds, per microbatch count, the candidate
 // with the smallest T (lowest index on ties) and fills out[q] (one pair of int64 per wave of
 // 64 candidates and microbatch count in part).  T_out ([nM][N]) may then be NULL; T_scratch
 // ([N]) is needed for S > 16 in that case.  hdr: the workspace header the pack kernel has filled
 // for these tables (its largest time decides between 32-bit and 64-bit kernels), or NULL.
+// fuse != NULL (pp_best_plan only, needs hdr): the partition DP kernel was told (defer_mmax of
+// pp_launch_dp) to leave the plans to the makespan kernel whenever no link's channel time
+// depends on the cut position and all finish times for fuse->mmax microbatches fit 32 bits;
+// the makespan kernel then builds them from the channel-free tables fuse->bfl and writes
+// fuse->C [N] and fuse->bounds [N][S] (the arrays `C` and `bounds` point at as well).  Only
+// where pp_makespan_can_fuse(L, D, S) holds.
+struct pp_fuse_info {
+    int mmax;            // largest microbatch count of the call
+    int validate;        // the ordering list came from the caller
+    const int64_t *bfl;  // the channel-free tables in the workspace
+    int64_t *C;
+    int32_t *bounds;
+};
+bool pp_makespan_can_fuse(int L, int D, int S);
 int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
-                       pp_result *out, const pp_ws_header *hdr, hipStream_t st);
+                       pp_result *out, const pp_ws_header *hdr, const pp_fuse_info *fuse,
+                       hipStream_t st);
 // Stage-count search: makespan of the plan with xi stages of every candidate for xi = 1..S
 // (bounds [N][S(S+1)/2] and C [N][S] as pp_launch_dp leaves them with stages == 1), written to
 // T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest

@@ -301,8 +301,9 @@ static long long choose_chunk(int64_t N, int D, bool lex, long long simds, int w
 
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
-                 const int32_t *user_ord, int stages, int64_t *C_out, int32_t *bounds_out,
-                 void *ws, const pp_ws_layout &lay, int32_t *status, hipStream_t st) {
+                 const int32_t *user_ord, int stages, int defer_mmax, int64_t *C_out,
+                 int32_t *bounds_out, void *ws, const pp_ws_layout &lay, int32_t *status,
+                 hipStream_t st) {
     char *base = (char *)ws;
     dp_args a;
     a.stages = stages;
@@ -321,6 +322,7 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     a.status = status;
     a.nblocks = lay.slots;
     a.bfl = (const long long *)(base + lay.bfl);
+    a.defer_mmax = defer_mmax;
 
     if (lay.nt) {
         // L <= 128: register-tiled kernel, one wave per candidate (falls back to the generic

@@ -137,7 +137,8 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     extern __shared__ __align__(16) unsigned char smem[];
     const dp_args &a = b.g;
     if (pp_is_flat(a.hdr)) {
-        dp_flat_body(a, smem, a.lds_bytes);  // no channel time depends on the cut position
+        // no channel time depends on the cut position: closed form, here or in the makespan kernel
+        if (!dp_flat_deferred(a)) dp_flat_body(a, smem, a.lds_bytes);
         return;
     }
     if (!(pp_vmax(a.hdr) < a.fit_limit)) {

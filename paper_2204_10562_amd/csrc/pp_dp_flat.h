@@ -275,6 +275,13 @@ __device__ __forceinline__ void dp_flat_run8(const dp_args &a, const flat_view &
     if (lane == 0) pp_count_work(a.hdr, total, 0, blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
 }
 
+// True (uniformly) if the plans of this call are built by the makespan kernel that follows
+// (same test as there: pp_makespan.hip, fused_gather).  All lanes of a full wave must call.
+__device__ __forceinline__ bool dp_flat_deferred(const dp_args &a) {
+    if (!a.defer_mmax) return false;
+    return pp_vmax(a.hdr) <= 0x7fffffffull / (unsigned long long)(a.defer_mmax + 4 * a.S - 4);
+}
+
 // Must be entered by whole workgroups of full waves; lds_bytes = dynamic LDS of the launch
 // (at least pp_flat_col_bytes(S)).
 __device__ inline void dp_flat_body(const dp_args &a, unsigned char *smem, size_t lds_bytes) {

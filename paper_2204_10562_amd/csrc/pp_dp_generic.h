@@ -21,6 +21,9 @@ struct dp_args {
     const int *p32, *x32;
     const long long *bfl;  // the partition DP with no channel cost (values, then splits), see pp_dp_flat.h
     size_t lds_bytes;      // dynamic LDS of the launch
+    // > 0: when the closed form applies and the finish times of a schedule of defer_mmax
+    // microbatches fit 32 bits, leave the plans to the makespan kernel that follows
+    int defer_mmax;
     unsigned short *arg;  // [nblocks][S][L+1] backtrack tables, one per working workgroup
     int nblocks;          // workgroups that take part (the rest of the grid returns)
     // stages == 0: C_out [N], bounds_out [N][S]: the plan with S stages.

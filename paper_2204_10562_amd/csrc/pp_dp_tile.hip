@@ -98,7 +98,8 @@ template <int NT>
 __global__ __launch_bounds__(256) void k_dp_tile(dp_tile_args a) {
     extern __shared__ __align__(16) unsigned char smem[];
     if (pp_is_flat(a.g.hdr)) {
-        dp_flat_body(a.g, smem, a.g.lds_bytes);  // no channel time depends on the cut position
+        // no channel time depends on the cut position: closed form, here or in the makespan kernel
+        if (!dp_flat_deferred(a.g)) dp_flat_body(a.g, smem, a.g.lds_bytes);
         return;
     }
     if (!(pp_vmax(a.g.hdr) < a.g.fit_limit)) {

@@ -23,6 +23,7 @@
 // When asked to, each wave also reduces (T, candidate) to its minimum, and a one-workgroup
 // kernel launched next reduces the per-wave minima to the winner record.
 #include "pp_common.h"
+#include "pp_dp_flat.h"
 
 struct tc_pair { long long T, c; };
 
@@ -63,6 +64,15 @@ struct mk_args {
     // workspace header with the largest time of the tables (NULL if there is none): lets every
     // wave of a launch take the same decision between 32-bit and 64-bit finish times
     const pp_ws_header *hdr;
+    // k_makespan_regs8 inside pp_best_plan: nonzero = when no link's channel time depends on the
+    // cut position and every finish time of the launch fits 32 bits (both read from hdr), the
+    // partition DP kernel has left the plans to this kernel, which builds them in closed form
+    // from the channel-free tables bfl (pp_dp_flat.h) and writes C_w [N] and bounds_w [N][S].
+    // fuse_mmax: the largest microbatch count of the call (the DP kernel tests the same bound).
+    int fuse, fuse_mmax, fuse_validate;
+    const long long *bfl;
+    long long *C_w;
+    int *bounds_w;
     int32_t *status;
     // replicated stages (k_rep_makespan and the record of its arg-min; NULL otherwise): replica
     // counts laid out like bounds, prefix sums of the parameter sizes, activation sizes, the
@@ -466,6 +476,177 @@ __device__ __forceinline__ long long sweep_regs(const long long (&dur64)[4 * S -
 #define MK_REGS_WAVES 4
 #define MK_REGS_GROUPS 3
 
+// LDS the fused gather needs: per group, J rows of 64 int32 durations and one row of 64 int64
+// per wave (only when a group has several waves), then the tables: B and A of the channel-free
+// program, PF, PB, and the forward and backward channel time of every link.
+__host__ __device__ static inline size_t mk_fuse_exchange_bytes(int S, int nw, int G) {
+    return nw > 1 ? (size_t)G * ((size_t)(4 * S - 3) * 64 * 4 + (size_t)nw * 64 * 8) : 0;
+}
+__host__ __device__ static inline size_t mk_fuse_lds_bytes(int L, int D, int S, int nw, int G) {
+    return mk_fuse_exchange_bytes(S, nw, G) + pp_flat_table_bytes(L, S) + (size_t)2 * (L + 1) * 8 +
+           (size_t)2 * D * D * 8;
+}
+
+// The gather of regs_body when the plans are not in memory yet (a.fuse): if the tables say so
+// (see mk_args), every lane builds its candidate's plan in closed form from tables staged in
+// LDS - W[n][l] = max(largest channel time so far, channel-free cell), lowest split from the
+// channel-free split table or by a search in the prefix sums - and takes the block durations
+// from LDS as well, so that the whole gather costs one trip to memory.  Returns false (nothing
+// done) if this launch reads its plans from memory.  Must be entered by whole workgroups.
+template <int S>
+__device__ __forceinline__ bool fused_gather(const mk_args &a, long long c, bool live, int g, int w,
+                                             int nw, int G, long long (&dur)[4 * S - 3 + 1],
+                                             long long &worst, int &fault) {
+    constexpr int R = 2 * S - 1, J = 4 * S - 3;
+    extern __shared__ __align__(16) unsigned char fsm[];
+    const int L = a.L, D = a.D, nP = L + 1, tid = threadIdx.x, lane = tid & 63;
+    // requests first: header, this lane's row, the tables (8 pieces of 16 bytes per thread and
+    // pass; contiguous in the workspace as B then A), PF, PB, and the links' channel times
+    const unsigned flat_w = a.hdr->flat[lane];
+    unsigned long long vmax = a.hdr->pmax[lane];
+    int row[S];
+#pragma unroll
+    for (int n = 0; n < S; ++n) row[n] = live ? a.orderings[c * a.ord_stride + n] : 0;
+    const size_t tab = pp_flat_table_bytes(L, S);
+    unsigned char *tbase = fsm + mk_fuse_exchange_bytes(S, nw, G);
+    long long *sB = (long long *)tbase;
+    int *sA = (int *)(sB + (size_t)S * nP);
+    long long *sPF = (long long *)(tbase + tab), *sPB = sPF + nP, *sxf = sPB + nP, *sxb = sxf + D * D;
+    const int n16 = (int)(tab / 16), T = blockDim.x;
+    int4 first[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) first[u] = tid + u * T < n16 ? ((const int4 *)a.bfl)[tid + u * T] : make_int4(0, 0, 0, 0);
+    // (what the first pass of the loops below stores)
+    long long pf0 = tid <= L ? a.PF[tid] : 0, pb0 = tid <= L ? a.PB[tid] : 0;
+    long long xf0 = (tid < D * D && L > 1) ? a.XF[(size_t)tid * L] : 0, xb0 = (tid < D * D && L > 1) ? a.XB[(size_t)tid * L] : 0;
+    for (int off = 32; off; off >>= 1) {
+        const unsigned long long o = __shfl_xor(vmax, off);
+        vmax = o > vmax ? o : vmax;
+    }
+    const bool fused = __ballot(flat_w != 0) == ~0ull &&
+                       vmax <= 0x7fffffffull / (unsigned long long)(a.fuse_mmax + 4 * S - 4);
+    if (!fused) return false;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        if (tid + u * T < n16) ((int4 *)sB)[tid + u * T] = first[u];
+    for (int base = 8 * T; base < n16; base += 8 * T) {  // (narrow workgroups: further passes)
+        int4 more[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            more[u] = base + tid + u * T < n16 ? ((const int4 *)a.bfl)[base + tid + u * T] : make_int4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (base + tid + u * T < n16) ((int4 *)sB)[base + tid + u * T] = more[u];
+    }
+    for (int i = tid; i <= L; i += T) {
+        sPF[i] = i == tid ? pf0 : a.PF[i];
+        sPB[i] = i == tid ? pb0 : a.PB[i];
+    }
+    for (int i = tid; i < D * D; i += T) {
+        sxf[i] = i == tid ? xf0 : (L > 1 ? a.XF[(size_t)i * L] : 0);
+        sxb[i] = i == tid ? xb0 : (L > 1 ? a.XB[(size_t)i * L] : 0);
+    }
+    __syncthreads();
+
+    // a caller's row is checked here (the DP kernel has not looked at it)
+    bool bad = false;
+    if (a.fuse_validate && live) {
+#pragma unroll
+        for (int n = 0; n < S; ++n) {
+            bad |= row[n] < 0 || row[n] >= D;
+#pragma unroll
+            for (int q = 0; q < n; ++q) bad |= row[q] == row[n];
+        }
+    }
+    fault = bad ? PP_FAULT_ORDERING : 0;
+    if (bad) {
+#pragma unroll
+        for (int n = 0; n < S; ++n) row[n] = 0;
+    }
+    // prefix maxima of the channel times, then the plan from (S-1, L) downwards
+    long long m[S];
+    int link[S];
+    m[0] = 0;
+    link[0] = 0;
+#pragma unroll
+    for (int n = 1; n < S; ++n) {
+        link[n] = row[n - 1] * D + row[n];
+        m[n] = sxf[link[n]] + sxb[link[n]];
+    }
+#pragma unroll
+    for (int n = 1; n < S; ++n) m[n] = m[n] > m[n - 1] ? m[n] : m[n - 1];
+    int e[S];
+    long long Cval = sB[L];  // S == 1: P[L]
+    e[S - 1] = L;
+    const int steps = pp_flat_steps(L);
+#pragma unroll
+    for (int n = S - 1; n >= 1; --n) {
+        const long long bn = sB[(size_t)n * nP + e[n]];
+        int r = sA[(size_t)n * nP + e[n]];
+        if (n == S - 1) Cval = m[n] > bn ? m[n] : bn;
+        if (m[n] > bn) {  // the channels bind: the longest last stage that fits in m_n
+            const long long t = sB[e[n]] - m[n];
+            int pos = 0;
+            for (int st = 1 << (steps - 1); st; st >>= 1) {
+                const int idx = pos + st - 1;
+                pos += sB[idx <= L ? idx : L] < t ? st : 0;
+            }
+            r = pos < L ? pos : L;
+            r = r > n ? r : n;
+        }
+        e[n - 1] = r;
+    }
+    // the plan goes to memory once per candidate (the winner's record is read from there)
+    if (w == 0 && live) {
+        a.C_w[c] = bad ? PP_INF64 : Cval;
+        int *bo = a.bounds_w + c * S;
+        if (S == 8) {
+            *(int4 *)bo = bad ? make_int4(0, 0, 0, 0) : make_int4(e[0], e[1], e[2], e[3]);
+            *(int4 *)(bo + 4) = bad ? make_int4(0, 0, 0, 0) : make_int4(e[4], e[5], e[6], e[7]);
+        } else {
+#pragma unroll
+            for (int n = 0; n < S; ++n) bo[n] = bad ? 0 : e[n];
+        }
+    }
+    // block durations of this wave's share of the stages (all of them for a single wave)
+    int *xd = (int *)fsm + (size_t)g * ((size_t)J * 64 + (size_t)nw * 128) + lane;  // [J][64] int32, then [nw][64] int64
+    long long mine = 0;
+    const bool use = live && !bad;
+#pragma unroll
+    for (int n = 0; n < S; ++n) {
+        if (nw > 1 && n % nw != w) continue;
+        const int e0 = n ? e[n - 1] : 0;
+        long long F = sPF[e[n]] - sPF[e0], Bk = sPB[e[n]] - sPB[e0], cf = 0, cb = 0;
+        if (n) { cf = sxf[link[n]]; cb = sxb[link[n]]; }
+        if (!use) F = Bk = cf = cb = 0;
+        const long long wn = F + Bk > cf + cb ? F + Bk : cf + cb;
+        mine = wn > mine ? wn : mine;
+        const int r = 2 * n + 1;
+        auto put = [&](int j, long long d) {
+            if (nw > 1) xd[(j - 1) * 64] = (int)d;
+            else dur[j] = d;
+        };
+        if (n == S - 1) put(R, F + Bk);
+        else { put(r, F); put(2 * R - r, Bk); }
+        if (n) { put(r - 1, cf); put(2 * R - (r - 1), cb); }
+    }
+    worst = mine;
+    if (nw > 1) {
+        long long *xw = (long long *)((int *)fsm + (size_t)g * ((size_t)J * 64 + (size_t)nw * 128) + (size_t)J * 64);
+        xw[w * 64 + lane] = mine;
+        __syncthreads();
+#pragma unroll
+        for (int j = 1; j <= J; ++j) dur[j] = xd[(j - 1) * 64];
+        worst = 0;
+        for (int v = 0; v < nw; ++v) {
+            const long long o = xw[v * 64 + lane];
+            worst = o > worst ? o : worst;
+        }
+    }
+    dur[0] = 0;
+    return true;
+}
+
 // One wave per (64 candidates, microbatch count).  The waves of a workgroup serve the same 64
 // candidates for up to MK_REGS_WAVES counts: the scattered table lookups of the gather, which
 // cost more than the schedule itself for small M, are split between them by stage and
@@ -490,7 +671,13 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
     long long dur[J + 1];
     long long worst;
     int fault;
-    if (nw == 1) {
+    bool gathered = false;
+    if constexpr (!SHARE && S >= 2 && S <= 8) {
+        if (a.fuse) gathered = fused_gather<S>(a, c, live, g, w, nw, G, dur, worst, fault);
+    }
+    if (gathered) {
+        // durations, worst and fault are set
+    } else if (nw == 1) {
         fault = gather_durations<S>(a, c, live, worst, [&](int j, long long d) { dur[j] = d; });
     } else {
         long long mine;
@@ -856,7 +1043,11 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
         b.groups = MK_REGS_GROUPS;
         gridx = (grid + MK_REGS_GROUPS - 1) / MK_REGS_GROUPS;
     }
-    const size_t lds_all = lds * b.groups;
+    size_t lds_all = lds * b.groups;
+    if (b.fuse) {
+        const size_t need = mk_fuse_lds_bytes(a.L, a.D, a.S, nw, b.groups);
+        lds_all = need > lds_all ? need : lds_all;
+    }
     if constexpr (S == 0) {
         if (a.all_xi && a.share[a.S > 2 ? a.S - 2 : 0] > 1)
             hipLaunchKernelGGL(k_makespan_regs8_shared, dim3(grid, (a.nM + nw - 1) / nw, a.S),
@@ -919,11 +1110,19 @@ static int launch_makespan(const mk_args &a, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
+// The makespan kernel can build the plans itself (closed form, tables staged in LDS) for 2..8
+// stages when its tables fit beside the exchange area of the largest workgroup it may use.
+bool pp_makespan_can_fuse(int L, int D, int S) {
+    return S >= 2 && S <= 8 && D <= 32 &&
+           mk_fuse_lds_bytes(L, D, S, MK_REGS_WAVES, MK_REGS_GROUPS) <= 64 * 1024;
+}
+
 int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
-                       pp_result *out, const pp_ws_header *hdr, hipStream_t st) {
+                       pp_result *out, const pp_ws_header *hdr, const pp_fuse_info *fuse,
+                       hipStream_t st) {
     mk_args a = {};
     a.L = L; a.D = D; a.S = S; a.N = N;
     a.nM = nM;
@@ -935,6 +1134,14 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
     a.T_out = (long long *)T_out; a.status = status;
     a.part = (tc_pair *)part; a.C = (const long long *)C; a.out = out;
     a.hdr = hdr;
+    if (fuse && hdr && pp_makespan_can_fuse(L, D, S)) {
+        a.fuse = 1;
+        a.fuse_mmax = fuse->mmax;
+        a.fuse_validate = fuse->validate;
+        a.bfl = (const long long *)fuse->bfl;
+        a.C_w = (long long *)fuse->C;
+        a.bounds_w = fuse->bounds;
+    }
     if (S > 16 && lds_lanes(S) != 64 && part) {
         // narrow workgroups: per microbatch count, T goes to memory and a separate pass finds
         // the minimum

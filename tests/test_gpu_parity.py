@@ -512,6 +512,69 @@ def test_best_plan_adversarial_small(ppo, G, seed, L, D, S, N):
         check_best(ppo, g, w, M, tables)
 
 
+@pytest.mark.parametrize("seed,L,D,S,N", SMALL + [(1401, 128, 8, 8, 300), (1402, 100, 30, 7, 200), (1403, 64, 32, 8, 150),
+                                                    (1404, 400, 6, 6, 130), (1405, 50, 40, 8, 70), (1406, 20, 9, 2, 65)])
+def test_best_plan_equal_activations(ppo, G, seed, L, D, S, N):
+    # transfer times that do not depend on the cut position: for 2..8 stages the makespan kernel
+    # builds the plans itself from tables in LDS (where they fit), otherwise the DP kernel does
+    w = workloads.random_small(seed + 3000, L, D, S, N, zero_frac=0.15 if seed % 2 else 0.0,
+                               hi_time=7 if seed < 1400 else 900, hi_act=500 if seed < 1400 else 10 ** 6, same_act=True)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    for M in (1, 4, 37):
+        say("best_plan equal activations", seed, L, D, S, N, "M", M)
+        check_best(ppo, g, w, M, tables)
+    check_best_multi(ppo, g, w, (2, 9, 33, 70), tables)
+    check_best_multi(ppo, g, w, (5, 6), tables)
+
+
+def test_best_plan_equal_activations_wide_and_faults(ppo, G):
+    # times beyond 32 bits: the plans come from the DP kernel (int64), the schedule runs in int64
+    w = workloads.random_small(1411, 60, 6, 6, 90, zero_frac=0.1, hi_time=9, hi_act=300, same_act=True)
+    w.fwd = w.fwd << 30
+    w.bwd = w.bwd << 30
+    w.actf = w.actf << 27
+    w.actb = w.actb << 27
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("best_plan equal activations, wide")
+    check_best(ppo, g, w, 5, tables)
+    check_best_multi(ppo, g, w, (3, 20), tables)
+    # times that fit for few microbatches but not for many: the two kernels must agree on who
+    # builds the plans, for every count of the list
+    w = workloads.random_small(1412, 40, 5, 5, 70, hi_time=9, hi_act=300, same_act=True)
+    w.fwd = w.fwd << 18
+    w.bwd = w.bwd << 18
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("best_plan equal activations, near the 32-bit bound")
+    for Ms in ((1,), (2, 3), (40, 1), (3000,)):
+        check_best_multi(ppo, g, w, Ms, tables)
+    # bad rows in a caller's list: the fault is raised, the other candidates are right
+    w = workloads.random_small(1413, 25, 6, 5, 200, hi_time=60, hi_act=5000, same_act=True)
+    tables = oracle_tables(ppo, w)
+    rc, res0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, 6, *tables, w.orderings)
+    v = sub_workload(w, np.arange(w.N))
+    v.orderings[13, 2] = v.orderings[13, 0]
+    v.orderings[63, 4] = 6
+    v.orderings[199, 0] = -1
+    g = G(v)
+    g.set_tables(*tables)
+    say("best_plan equal activations, faults")
+    st, res, T, C = g.best(6)
+    assert st & ppo.FAULT_ORDERING
+    keep = np.array([c for c in range(w.N) if c not in (13, 63, 199)])
+    np.testing.assert_array_equal(T[keep], T0[keep])
+    np.testing.assert_array_equal(C[keep], C0[keep])
+    big = np.iinfo(np.int64).max
+    assert (T[[13, 63, 199]] == big).all() and (C[[13, 63, 199]] == big).all()
+    if res0["best_index"] in keep:
+        assert res == res0
+
+
 def test_best_plan_ties_lowest_index(ppo, G):
     w = workloads.tiny()
     w.bw = np.full((4, 4), 16000, np.int64)
