@@ -4,59 +4,68 @@
 // of C); transfer time over a link is size / bandwidth (Sec. III-B, c^f and c^b with one GPU
 // per stage), rounded up to whole microseconds per direction.
 //
-// Both parts are bandwidth-trivial: 4L int64 in, 2(L+1) + 2 D^2 L int64 out.  The table
-// part gives every thread one (link, boundary) entry, so a wave reads consecutive
-// activation sizes and writes 64 consecutive int64 results (512-byte coalesced segments).
+// Both parts are bandwidth-trivial: 4L int64 in, 2(L+1) + 2 D^2 L int64 out.  The scan reads
+// and writes consecutive int64 per consecutive lane and does its chunked work in LDS; the table
+// part gives every thread one (link, boundary) entry, so a wave reads consecutive activation
+// sizes and writes 64 consecutive int64 results (512-byte coalesced segments).
 #include "pp_common.h"
 
 #define SCAN_THREADS 256
 
-// One workgroup scans both arrays.  Each thread owns a contiguous chunk; chunk totals are
-// scanned through LDS; a value that reaches 2^62 (also by wrap-around: each addend is below
-// 2^62, so a running sum cannot skip the interval [2^62, 2^64)) raises the overflow fault.
+// One workgroup scans both arrays.  The inputs are read lane-interleaved (consecutive lanes,
+// consecutive int64: coalesced) into LDS, every thread then scans a contiguous chunk there,
+// the chunk totals are scanned with wave shuffles and one exchange between the four waves,
+// and the results leave LDS lane-interleaved again.  A value that reaches 2^62 (also by
+// wrap-around: each addend is below 2^62, so a running sum cannot skip the interval
+// [2^62, 2^64)) raises the overflow fault.
 __device__ __forceinline__ void prefix_scan(
     int L, const long long *__restrict__ fwd, const long long *__restrict__ bwd,
     const long long *__restrict__ actf, const long long *__restrict__ actb,
     long long *__restrict__ PF, long long *__restrict__ PB, int32_t *status) {
-    __shared__ unsigned long long totF[SCAN_THREADS], totB[SCAN_THREADS];
-    const int tid = threadIdx.x;
-    const int chunk = (L + SCAN_THREADS - 1) / SCAN_THREADS;
-    const int lo = tid * chunk, hi = min(L, lo + chunk);
+    __shared__ unsigned long long sF[PP_MAX_LAYERS], sB[PP_MAX_LAYERS];
+    __shared__ unsigned long long wF[SCAN_THREADS / 64], wB[SCAN_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int fault = 0;
-    unsigned long long sf = 0, sb = 0;
-    for (int l = lo; l < hi; ++l) {
-        long long f = fwd[l], b = bwd[l];
+    for (int l = tid; l < L; l += SCAN_THREADS) {
+        const long long f = fwd[l], b = bwd[l];
         if (f < 0 || b < 0) fault |= PP_FAULT_NEGATIVE;
         if (f >= PP_CAP62 || b >= PP_CAP62) fault |= PP_FAULT_OVERFLOW;
         if (l + 1 < L && (actf[l] < 0 || (actb && actb[l] < 0))) fault |= PP_FAULT_NEGATIVE;
-        sf += (unsigned long long)f;
-        sb += (unsigned long long)b;
+        sF[l] = (unsigned long long)f;
+        sB[l] = (unsigned long long)b;
     }
-    totF[tid] = sf;
-    totB[tid] = sb;
     __syncthreads();
-    // inclusive Hillis-Steele scan of the chunk totals
-    for (int d = 1; d < SCAN_THREADS; d <<= 1) {
-        unsigned long long af = 0, ab = 0;
-        if (tid >= d) { af = totF[tid - d]; ab = totB[tid - d]; }
-        __syncthreads();
-        totF[tid] += af;
-        totB[tid] += ab;
-        __syncthreads();
+    const int chunk = (L + SCAN_THREADS - 1) / SCAN_THREADS;
+    const int lo = tid * chunk, hi = min(L, lo + chunk);
+    unsigned long long tf = 0, tb = 0;
+    for (int l = lo; l < hi; ++l) { tf += sF[l]; tb += sB[l]; }
+    // inclusive scan of the chunk totals: within the wave, then across the four waves
+    unsigned long long inf = tf, inb = tb;
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long of = __shfl_up(inf, d), ob = __shfl_up(inb, d);
+        if (lane >= d) { inf += of; inb += ob; }
     }
-    unsigned long long rf = tid ? totF[tid - 1] : 0, rb = tid ? totB[tid - 1] : 0;
-    if (tid == 0) { PF[0] = 0; PB[0] = 0; }
+    if (lane == 63) { wF[wave] = inf; wB[wave] = inb; }
+    __syncthreads();
+    unsigned long long rf = inf - tf, rb = inb - tb;  // exclusive: the sum before this chunk
+    for (int v = 0; v < wave; ++v) { rf += wF[v]; rb += wB[v]; }
+    // a partial total that wrapped shows up here or in some later chunk's running value
+    if (rf + tf >= (unsigned long long)PP_CAP62 || rb + tb >= (unsigned long long)PP_CAP62)
+        fault |= PP_FAULT_OVERFLOW;
     for (int l = lo; l < hi; ++l) {
-        rf += (unsigned long long)fwd[l];
-        rb += (unsigned long long)bwd[l];
+        rf += sF[l];
+        rb += sB[l];
         if (rf >= (unsigned long long)PP_CAP62 || rb >= (unsigned long long)PP_CAP62)
             fault |= PP_FAULT_OVERFLOW;
-        PF[l + 1] = (long long)rf;
-        PB[l + 1] = (long long)rb;
+        sF[l] = rf;
+        sB[l] = rb;
     }
-    // a partial total that wrapped shows up in some later chunk's running value or here
-    if (totF[tid] >= (unsigned long long)PP_CAP62 || totB[tid] >= (unsigned long long)PP_CAP62)
-        fault |= PP_FAULT_OVERFLOW;
+    __syncthreads();
+    if (tid == 0) { PF[0] = 0; PB[0] = 0; }
+    for (int l = tid; l < L; l += SCAN_THREADS) {
+        PF[l + 1] = (long long)sF[l];
+        PB[l + 1] = (long long)sB[l];
+    }
     if (fault) pp_raise(status, fault);
 }
 
