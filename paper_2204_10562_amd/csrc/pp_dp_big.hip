@@ -9,11 +9,11 @@
 // 128I + 8i + a + 1 and splits 128J + 8j + b; a cell is (time << K) | k, so max keeps the
 // split index and min returns the smallest time with the lowest split), but the difference
 // term ((P[l] - P[k]) << K) | k is too large to keep in registers for the whole plane, so it
-// is formed on the fly: subtract, max and half a three-operand min per pair.  Only super-tiles
-// on or below the diagonal are visited, from the diagonal leftwards, and the scan of a super-row
-// stops as soon as the difference term alone rules out everything further left; the last
-// super-row has NTL <= 16 cell tiles, fixed at compile time, so a model of 300 layers does not
-// pay for 384.
+// is formed on the fly: subtract, max and half a three-operand min per pair.  The cells are
+// taken in groups of 32 (four tiles); a group visits the blocks of 32 splits on or below the
+// diagonal, from the diagonal leftwards, and stops as soon as the difference term alone rules
+// out everything further left for its cells; the last super-row has NTL <= 16 cell tiles,
+// fixed at compile time, so a model of 300 layers does not pay for 384.
 //
 // Per wave in LDS: two rows of keys (the row being read, rewritten in place as g, and the row
 // being produced).  Split indices go to a per-wave table in global memory while the next row's
@@ -55,73 +55,34 @@ __device__ __forceinline__ void big_lds_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-// One super-tile: NTI cell tiles x NTJ split tiles.  G and Pk point at split 128J of the g
-// row and of the table (P[k] << K) - k.  DIAG: the super-tile lies on the diagonal (I == J):
-// blocks above the block diagonal are skipped, blocks on it are valid for lanes with b <= a.
-template <int NTI, int NTJ, bool DIAG>
-__device__ __forceinline__ void big_tile(int (&acc)[16], const int (&Pl)[16], const int *G,
-                                         const int *Pk, int la, int lb) {
-    int g[NTJ], pk[NTJ];
+// The g row and the table (P[k] << K) - k at the 4 split tiles of one block, as lane (a, b)
+// needs them: splits 8 j + b.
+struct big_splits {
+    int g[4], pk[4];
+};
+
+__device__ __forceinline__ void big_load(big_splits &s, const int *G, const int *Pk, int lb) {
 #pragma unroll
-    for (int j = 0; j < NTJ; ++j) { g[j] = G[8 * j + lb]; pk[j] = Pk[8 * j + lb]; }
+    for (int j = 0; j < 4; ++j) { s.g[j] = G[8 * j + lb]; s.pk[j] = Pk[8 * j + lb]; }
+}
+
+// One block: NI4 (<= 4) cell tiles against 4 split tiles.  DIAG: the split tiles are the cell
+// tiles' own: tiles above the diagonal are skipped, those on it are valid for lanes with b <= a.
+template <int NI4, bool DIAG>
+__device__ __forceinline__ void big_block(int (&acc)[4], const int (&Pl)[4], const big_splits &s,
+                                          int la, int lb) {
 #pragma unroll
-    for (int j = 0; j < NTJ; ++j) asm volatile("" : "+v"(g[j]), "+v"(pk[j]));  // all reads in flight
-#pragma unroll
-    for (int i = 0; i < NTI; ++i) {
+    for (int i = 0; i < NI4; ++i) {
         int v = acc[i];
 #pragma unroll
-        for (int j = 0; j < NTJ; ++j) {
+        for (int j = 0; j < 4; ++j) {
             if (DIAG && j > i) continue;
-            int d = Pl[i] - pk[j];
+            int d = Pl[i] - s.pk[j];
             if (DIAG && j == i) d = lb <= la ? d : PP_INF32;
-            v = bmin(v, bmax(g[j], d));
+            v = bmin(v, bmax(s.g[j], d));
         }
         acc[i] = v;
     }
-}
-
-// One super-row of NTI cell tiles: the diagonal super-tile, then the super-tiles to its left
-// from the nearest on, then the reduction over the 8 lanes that share a cell, then the cells go
-// to the next row.  P[l] - P[k] grows as k falls, so once the smallest difference of a
-// super-tile (first cell of the row against the super-tile's last split) exceeds the largest
-// value any lane still holds, neither that super-tile nor any further left can lower or tie a
-// cell: the scan stops there.  Returns the first super-tile visited (for the work counter).
-template <int NTI>
-__device__ __forceinline__ int big_super_row(int I, const int *G, const int *sPk, int *nxt,
-                                             int la, int lb, int K) {
-    int acc[16], Pl[16];
-#pragma unroll
-    for (int i = 0; i < NTI; ++i) {
-        const int l = 128 * I + 8 * i + la + 1;
-        Pl[i] = sPk[l] + l;  // P[l] << K
-        acc[i] = PP_INF32;
-    }
-    big_tile<NTI, NTI, true>(acc, Pl, G + 128 * I, sPk + 128 * I, la, lb);
-    int J = I - 1;
-    for (; J >= 0; --J) {
-        if (J < I - 1) {
-            // largest value held by any lane for any cell of this super-row (as a time)
-            int ub = acc[0];
-#pragma unroll
-            for (int i = 1; i < NTI; ++i) ub = bmax(ub, acc[i]);
-            for (int off = 32; off; off >>= 1) ub = bmax(ub, __shfl_xor(ub, off));
-            const int first_l = 128 * I + 1, last_k = 128 * J + 127;
-            // (P[l] << K) - (P[k] << K) compared with the time part of the bound
-            const int dmin = (sPk[first_l] + first_l) - (sPk[last_k] + last_k);
-            if ((dmin >> K) > (ub >> K)) break;
-        }
-        big_tile<NTI, 16, false>(acc, Pl, G + 128 * J, sPk + 128 * J, la, lb);
-    }
-#pragma unroll
-    for (int i = 0; i < NTI; ++i) {
-        acc[i] = big_min_over_b(acc[i]);
-        asm volatile("" : "+v"(acc[i]));
-    }
-    if (lb == 0) {
-#pragma unroll
-        for (int i = 0; i < NTI; ++i) nxt[128 * I + 8 * i + la + 1] = acc[i];
-    }
-    return J + 1;
 }
 
 // (cell, split) pairs with cell in [a, b], split in [klo, cell - 1]
@@ -130,6 +91,73 @@ __device__ __forceinline__ unsigned long long big_pairs(int a, int b, int klo) {
     if (b < a) return 0;
     const unsigned long long lo = (unsigned long long)(a - klo), hi = (unsigned long long)(b - klo);
     return (lo + hi) * (hi - lo + 1) / 2;
+}
+
+// A group of NI4 cell tiles (cells c0+1 .. c0+8 NI4, c0 a multiple of 32) of row n: the block on
+// the diagonal, then the blocks of 32 splits to its left from the nearest on, then the
+// reduction over the 8 lanes that share a cell, then the cells go to the next row.
+// P[l] - P[k] grows as k falls, so once the smallest difference of the next block (first cell
+// of the group against the block's last split) exceeds every value a lane still holds for a
+// cell of the group, neither that block nor any further left can lower or tie one of them:
+// the scan stops there.  The test costs a scalar subtraction, two maxima and one compare:
+// pend holds (P[32 s + 31] << K) in lane s.  Returns the pairs evaluated (for the work counter).
+template <int NI4>
+__device__ __forceinline__ unsigned long long big_cell_group(int c0, int n, int L, const int *G,
+                                                             const int *sPk, int *nxt, int la,
+                                                             int lb, int pend) {
+    int acc[4], Pl[4];
+#pragma unroll
+    for (int i = 0; i < NI4; ++i) {
+        const int l = c0 + 8 * i + la + 1;
+        Pl[i] = sPk[l] + l;  // P[l] << K
+        acc[i] = PP_INF32;
+    }
+    big_splits s;
+    big_load(s, G + c0, sPk + c0, lb);
+    big_block<NI4, true>(acc, Pl, s, la, lb);
+    const int first = __builtin_amdgcn_readlane(Pl[0], 0);  // lane 0 holds cell c0 + 1
+    const int sg_lo = n >> 5;  // blocks wholly below split n hold nothing feasible
+    int sg = (c0 >> 5) - 1;
+    for (; sg >= sg_lo; --sg) {
+        // ((P[c0 + 1] - P[32 sg + 31]) << K) is the smallest difference key of block sg: it can
+        // still lower or tie a cell of the group only if some lane holds a key that is not below it
+        // (fetching the next block's splits ahead of this test was measured: no gain)
+        const int dkey = first - __builtin_amdgcn_readlane(pend, sg);
+        int m = acc[0];
+#pragma unroll
+        for (int i = 1; i < NI4; ++i) m = bmax(m, acc[i]);
+        if (!__ballot(m >= dkey)) break;
+        big_load(s, G + 32 * sg, sPk + 32 * sg, lb);
+        big_block<NI4, false>(acc, Pl, s, la, lb);
+    }
+#pragma unroll
+    for (int i = 0; i < NI4; ++i) {
+        acc[i] = big_min_over_b(acc[i]);
+        asm volatile("" : "+v"(acc[i]));
+    }
+    if (lb == 0) {
+#pragma unroll
+        for (int i = 0; i < NI4; ++i) nxt[c0 + 8 * i + la + 1] = acc[i];
+    }
+    const int a0 = c0 + 1 > n + 1 ? c0 + 1 : n + 1, b0 = c0 + 8 * NI4 < L ? c0 + 8 * NI4 : L;
+    const int klo = 32 * (sg + 1) > n ? 32 * (sg + 1) : n;
+    return big_pairs(a0, b0, klo);
+}
+
+// One super-row of NTI cell tiles of row n, in groups of four.
+template <int NTI>
+__device__ __forceinline__ unsigned long long big_super_row(int I, int n, int L, const int *G,
+                                                            const int *sPk, int *nxt, int la,
+                                                            int lb, int pend) {
+    unsigned long long pairs = 0;
+    constexpr int REST = (NTI & 3) ? (NTI & 3) : 4;
+#pragma unroll
+    for (int cg = 0; cg < (NTI + 3) / 4; ++cg) {
+        const int c0 = 128 * I + 32 * cg;
+        if (NTI - 4 * cg >= 4) pairs += big_cell_group<4>(c0, n, L, G, sPk, nxt, la, lb, pend);
+        else pairs += big_cell_group<REST>(c0, n, L, G, sPk, nxt, la, lb, pend);
+    }
+    return pairs;
 }
 
 template <int NTL>
@@ -160,6 +188,8 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     for (int k = threadIdx.x; k <= Lp; k += blockDim.x) sPk[k] = (a.p32[k < L ? k : L] << K) - k;
     __syncthreads();
     if (wave >= b.waves) return;
+    // lane s: (P[32 s + 31] << K), the last split of block s (for the early exit's test)
+    const int pend = 32 * lane + 31 <= Lp ? sPk[32 * lane + 31] + 32 * lane + 31 : 0;
     unsigned short *arg = a.arg + (size_t)wave * b.arg_stride;
     unsigned long long pairs = 0, nrows = 0;
     const int tri = S * (S + 1) / 2;
@@ -210,13 +240,9 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
             }
             big_lds_sync();
             if (n < S - 1) {
-                for (int I = 0; I < NI; ++I) {
-                    const int J0 = I + 1 < NI ? big_super_row<16>(I, cur, sPk, nxt, la, lb, K)
-                                              : big_super_row<NTL>(I, cur, sPk, nxt, la, lb, K);
-                    const int a0 = 128 * I + 1 > n + 1 ? 128 * I + 1 : n + 1;
-                    const int b0 = 128 * I + 128 < L ? 128 * I + 128 : L;
-                    pairs += big_pairs(a0, b0, 128 * J0 > n ? 128 * J0 : n);
-                }
+                for (int I = 0; I < NI; ++I)
+                    pairs += I + 1 < NI ? big_super_row<16>(I, n, L, cur, sPk, nxt, la, lb, pend)
+                                        : big_super_row<NTL>(I, n, L, cur, sPk, nxt, la, lb, pend);
                 if (lane == 0) nxt[0] = PP_INF32;
                 big_lds_sync();
                 int *t = cur; cur = nxt; nxt = t;
