@@ -115,6 +115,8 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
             }
         }
         unsigned used = 0;
+        int row[4];
+        const bool vec = (D & 3) == 0;  // rows are 16-byte aligned pieces: store four devices at a time
         for (int n = 0; n < D; ++n) {
             int digit = (int)(((n < 12 ? digits >> (5 * n) : digits_hi >> (5 * (n - 12)))) & 31);
             // digit-th zero bit of `used`
@@ -122,7 +124,12 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
             for (int k = 0; k < digit; ++k) freeb &= freeb - 1;
             int dev = __builtin_ctz(freeb);
             used |= 1u << dev;
-            a.ord[c * D + n] = dev;
+            if (vec) {
+                row[n & 3] = dev;
+                if ((n & 3) == 3) *(int4 *)(a.ord + c * D + n - 3) = make_int4(row[0], row[1], row[2], row[3]);
+            } else {
+                a.ord[c * D + n] = dev;
+            }
         }
     }
 }
@@ -177,7 +184,10 @@ __device__ void flat_table(const pack_args &a, long long *sh) {
             a.bfl[(size_t)n * (L + 1) + l] = best;
             A[(size_t)n * (L + 1) + l] = arg;
         }
-        __syncthreads();
+        // The next row reads this one from LDS only, so the barrier waits for the LDS writes and
+        // lets the stores to global memory drain behind it (__syncthreads would wait for them
+        // too: a trip to memory per row).
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         long long *t = cur; cur = nxt; nxt = t;
     }
 }

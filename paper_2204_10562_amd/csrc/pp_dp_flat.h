@@ -279,7 +279,9 @@ __device__ __forceinline__ void dp_flat_run8(const dp_args &a, const flat_view &
 // (same test as there: pp_makespan.hip, fused_gather).  All lanes of a full wave must call.
 __device__ __forceinline__ bool dp_flat_deferred(const dp_args &a) {
     if (!a.defer_mmax) return false;
-    return pp_vmax(a.hdr) <= 0x7fffffffull / (unsigned long long)(a.defer_mmax + 4 * a.S - 4);
+    // (lane b looks at the largest time of pack block b: all below the limit = their maximum is)
+    const unsigned long long limit = 0x7fffffffull / (unsigned long long)(a.defer_mmax + 4 * a.S - 4);
+    return !__ballot(a.hdr->pmax[threadIdx.x & (PP_PACK_BLOCKS - 1)] > limit);
 }
 
 // Must be entered by whole workgroups of full waves; lds_bytes = dynamic LDS of the launch

@@ -519,12 +519,9 @@ __device__ __forceinline__ bool fused_gather(const mk_args &a, long long c, bool
     // (what the first pass of the loops below stores)
     long long pf0 = tid <= L ? a.PF[tid] : 0, pb0 = tid <= L ? a.PB[tid] : 0;
     long long xf0 = (tid < D * D && L > 1) ? a.XF[(size_t)tid * L] : 0, xb0 = (tid < D * D && L > 1) ? a.XB[(size_t)tid * L] : 0;
-    for (int off = 32; off; off >>= 1) {
-        const unsigned long long o = __shfl_xor(vmax, off);
-        vmax = o > vmax ? o : vmax;
-    }
+    // (lane b holds the largest time of pack block b: all below the limit = their maximum is)
     const bool fused = __ballot(flat_w != 0) == ~0ull &&
-                       vmax <= 0x7fffffffull / (unsigned long long)(a.fuse_mmax + 4 * S - 4);
+                       !__ballot(vmax > 0x7fffffffull / (unsigned long long)(a.fuse_mmax + 4 * S - 4));
     if (!fused) return false;
 #pragma unroll
     for (int u = 0; u < 8; ++u)
