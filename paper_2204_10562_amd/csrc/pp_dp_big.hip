@@ -85,11 +85,11 @@ __device__ __forceinline__ void big_block(int (&acc)[4], const int (&Pl)[4], con
     }
 }
 
-// (cell, split) pairs with cell in [a, b], split in [klo, cell - 1]
-__device__ __forceinline__ unsigned long long big_pairs(int a, int b, int klo) {
+// (cell, split) pairs with cell in [a, b], split in [klo, cell - 1] (at most L^2 / 2 < 2^22)
+__device__ __forceinline__ unsigned big_pairs(int a, int b, int klo) {
     if (a <= klo) a = klo + 1;
     if (b < a) return 0;
-    const unsigned long long lo = (unsigned long long)(a - klo), hi = (unsigned long long)(b - klo);
+    const unsigned lo = (unsigned)(a - klo), hi = (unsigned)(b - klo);
     return (lo + hi) * (hi - lo + 1) / 2;
 }
 
@@ -102,7 +102,7 @@ __device__ __forceinline__ unsigned long long big_pairs(int a, int b, int klo) {
 // the scan stops there.  The test costs a scalar subtraction, two maxima and one compare:
 // pend holds (P[32 s + 31] << K) in lane s.  Returns the pairs evaluated (for the work counter).
 template <int NI4>
-__device__ __forceinline__ unsigned long long big_cell_group(int c0, int n, int L, const int *G,
+__device__ __forceinline__ unsigned big_cell_group(int c0, int n, int L, const int *G,
                                                              const int *sPk, int *nxt, int la,
                                                              int lb, int pend) {
     int acc[4], Pl[4];
@@ -146,10 +146,10 @@ __device__ __forceinline__ unsigned long long big_cell_group(int c0, int n, int 
 
 // One super-row of NTI cell tiles of row n, in groups of four.
 template <int NTI>
-__device__ __forceinline__ unsigned long long big_super_row(int I, int n, int L, const int *G,
+__device__ __forceinline__ unsigned big_super_row(int I, int n, int L, const int *G,
                                                             const int *sPk, int *nxt, int la,
                                                             int lb, int pend) {
-    unsigned long long pairs = 0;
+    unsigned pairs = 0;
     constexpr int REST = (NTI & 3) ? (NTI & 3) : 4;
 #pragma unroll
     for (int cg = 0; cg < (NTI + 3) / 4; ++cg) {
