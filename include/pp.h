@@ -105,9 +105,18 @@ int pp_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
  * consecutive candidates share (equal ordering prefixes) are computed and
  * counted once, and the kernel for L > 128 skips splits that cannot matter, so
  * these can be far below N * pairs-per-candidate.
+ *
+ * For L > 128 and D <= 64 the dynamic program is computed once for every
+ * group of candidates whose links have the same transfer times at every cut
+ * position (the rows of XF and XB of link (o[n-1], o[n]) equal, n = 1..S-1)
+ * whenever (number of distinct link rows)^(S-1) <= 2^20; the four uint32 at
+ * byte PP_WS_SHARE then hold: 1 (0 if every candidate was computed on its
+ * own), the number of distinct link rows, that power, and the number of
+ * candidates computed.
  */
 #define PP_WS_WORK 1024
 #define PP_WS_WORK_STRIDE 128
+#define PP_WS_SHARE 768
 size_t pp_workspace_bytes(int L, int D, int S, int64_t N);
 
 /*

@@ -45,7 +45,7 @@ extern "C" int pp_partition_dp(int L, int D, int S, int64_t N, const int64_t *PF
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 0, 0, C_out,
+    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 0, 0, 0, C_out,
                         bounds_out, workspace, lay, status, st);
 }
 
@@ -69,7 +69,7 @@ extern "C" int pp_partition_dp_stages(int L, int D, int S, int64_t N, const int6
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, 0, C_out,
+    return pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, 0, 0, C_out,
                         bounds_out, workspace, lay, status, st);
 }
 
@@ -96,7 +96,7 @@ extern "C" int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM, const
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, 0, C, bounds,
+    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, 0, 0, C, bounds,
                       workspace, lay, status, st);
     if (rc) return rc;
     return pp_launch_makespan_stages(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, C, T,
@@ -112,7 +112,7 @@ extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const
     if (rc) return rc;
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
     return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
-                              status, NULL, NULL, NULL, NULL, NULL, (hipStream_t)stream);
+                              status, NULL, NULL, NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
 extern "C" int pp_schedule_makespan_multi(int L, int D, int S, int64_t N, int nM,
@@ -127,7 +127,7 @@ extern "C" int pp_schedule_makespan_multi(int L, int D, int S, int64_t N, int nM
     for (int q = 0; q < nM; ++q)
         if (M_list[q] < 1) return PP_ERR_INVALID_ARG;
     return pp_launch_makespan(L, D, S, N, nM, M_list, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
-                              status, NULL, NULL, NULL, NULL, NULL, (hipStream_t)stream);
+                              status, NULL, NULL, NULL, NULL, NULL, NULL, (hipStream_t)stream);
 }
 
 extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, int64_t N, int M,
@@ -140,7 +140,7 @@ extern "C" int pp_schedule_makespan_variant(int variant, int L, int D, int S, in
     if (M < 1 || !PF || !PB || !XF || !XB || !bounds || !T_out) return PP_ERR_INVALID_ARG;
     if (variant == PP_SCHED_PE)
         return pp_launch_makespan(L, D, S, N, 1, &M, PF, PB, XF, XB, orderings, bounds, T_out, NULL,
-                                  status, NULL, NULL, NULL, NULL, NULL, (hipStream_t)stream);
+                                  status, NULL, NULL, NULL, NULL, NULL, NULL, (hipStream_t)stream);
     if (variant != PP_SCHED_DUPLEX && variant != PP_SCHED_GPIPE && variant != PP_SCHED_ADDITIVE &&
         variant != PP_SCHED_FIFO)
         return PP_ERR_INVALID_ARG;
@@ -180,12 +180,21 @@ extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const 
     fuse.C = C;
     fuse.bounds = bounds;
     const bool can_fuse = pp_makespan_can_fuse(L, D, S);
+    // Where candidates share their partition DP (L > 128, few distinct link times) the schedule
+    // is shared too: only the representatives are evaluated, the arg-min runs over them (a
+    // representative is the lowest candidate of its group, so ties still go to the lowest
+    // index), and T and C reach the other candidates only if the caller wants the arrays.
+    const bool listed = lay.sh_table != 0 && pp_makespan_takes_list(S);
     rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 0,
-                      can_fuse ? fuse.mmax : 0, C, bounds, workspace, lay, status, st);
+                      can_fuse ? fuse.mmax : 0, listed, C, bounds, workspace, lay, status, st);
     if (rc) return rc;
-    return pp_launch_makespan(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, T_all,
-                              (int64_t *)(base + lay.T), status, C, base + lay.part, out,
-                              (const pp_ws_header *)(base + lay.hdr), can_fuse ? &fuse : NULL, st);
+    rc = pp_launch_makespan(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, T_all,
+                            (int64_t *)(base + lay.T), status, C, base + lay.part, out,
+                            (const pp_ws_header *)(base + lay.hdr), can_fuse ? &fuse : NULL,
+                            listed ? (const int32_t *)(base + lay.sh_reps) : NULL, st);
+    if (rc || !listed || (!T_all && !C_all)) return rc;
+    return pp_launch_share_scatter(N, C_all ? 1 : 0, 0, T_all ? nM : 0, C_all, NULL, T_all, workspace,
+                                   lay, st);
 }
 
 extern "C" int pp_best_plan(int L, int D, int S, int64_t N, int M, const int64_t *PF,

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "pp.h"
@@ -28,7 +29,12 @@ struct pp_ws_header {
     // byte 512: flat[b] != 0 iff, in pack block b's slice of the tables, the channel time
     // XF + XB of every link is the same at every cut position (all 64 set: it is so everywhere)
     unsigned flat[PP_PACK_BLOCKS];
-    unsigned pad0[64];  // byte 768
+    // byte 768: candidates that share a partition DP (pp_share.hip).  share_active != 0: the
+    // links fall into share_nc classes of equal channel-time rows and the share_tsize =
+    // share_nc^(S-1) sequences of classes index a table; share_nreps candidates (one per
+    // sequence that occurs, plus every candidate with a bad ordering) stand for all of them.
+    unsigned share_active, share_nc, share_tsize, share_nreps;
+    unsigned pad0[60];
     // byte 1024: work the partition DP actually did in this call, in 64 records of 128 bytes
     // (atomics that hit one cache line are served one after another, so every record has a
     // line of its own): (cell, split) pairs evaluated (rows shared between candidates are
@@ -39,6 +45,9 @@ struct pp_ws_header {
     } work[64];
 };
 
+static_assert(offsetof(pp_ws_header, share_active) == PP_WS_SHARE, "header layout");
+static_assert(offsetof(pp_ws_header, work) == PP_WS_WORK, "header layout");
+
 __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long long pairs,
                                               unsigned long long rows, unsigned who) {
     atomicAdd(&hdr->work[who & 63].pairs, pairs);
@@ -48,12 +57,21 @@ __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long l
 // Workspace carving, identical for pp_partition_dp and pp_best_plan.
 struct pp_ws_layout {
     size_t hdr, p32, x32, xkt, xct, bfl, ord, arg, bounds, C, T, part, total;
+    // candidates that share a DP (0 = not carved: see pp_share_possible)
+    size_t sh_hash, sh_rep, sh_table, sh_keys, sh_reps;
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
 
 #define PP_TILE_MAX_L 128
 #define PP_DP_SLOTS 4096
+// Sharing of one partition DP between the candidates whose links have the same channel times
+// (pp_share.hip): table entries, and the sizes it is built for.
+#define PP_SHARE_TABLE (1 << 20)
+#define PP_SHARE_MAX_D 64
+static inline bool pp_share_possible(int L, int D, int64_t N) {
+    return L > PP_TILE_MAX_L && D <= PP_SHARE_MAX_D && N < 0x7fffffff;
+}
 
 static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     pp_ws_layout w;
@@ -73,6 +91,14 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.C = off;      off += pp_align256((size_t)N * 8);
     w.T = off;      off += pp_align256((size_t)N * 8);
     w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16 * PP_MAX_M_LIST);
+    w.sh_hash = w.sh_rep = w.sh_table = w.sh_keys = w.sh_reps = 0;
+    if (pp_share_possible(L, D, N)) {
+        w.sh_hash = off;  off += pp_align256((size_t)D * D * 8);
+        w.sh_rep = off;   off += pp_align256((size_t)D * D * 4);
+        w.sh_table = off; off += pp_align256((size_t)PP_SHARE_TABLE * 4);
+        w.sh_keys = off;  off += pp_align256((size_t)N * 4);
+        w.sh_reps = off;  off += pp_align256((size_t)N * 4);
+    }
     w.total = off;
     return w;
 }
@@ -109,11 +135,30 @@ int pp_launch_pack(int L, int D, int S, int64_t N, const int64_t *PF, const int6
 // stage count xi at offset xi(xi-1)/2.
 // defer_mmax > 0: see pp_fuse_info (the plans are left to the makespan kernel that follows when
 // the closed form applies and the times for defer_mmax microbatches fit 32 bits).
+// keep_list != 0 (only where lay.sh_table != 0): where candidates share their DP, leave the
+// results with the representatives - the caller schedules the list (rlist of
+// pp_launch_makespan) and calls pp_launch_share_scatter itself - and set every partial of the
+// arg-min in the workspace to "none".
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
-                 const int32_t *user_ord, int stages, int defer_mmax, int64_t *C_out,
-                 int32_t *bounds_out, void *ws, const pp_ws_layout &lay, int32_t *status,
-                 hipStream_t st);
+                 const int32_t *user_ord, int stages, int defer_mmax, int keep_list,
+                 int64_t *C_out, int32_t *bounds_out, void *ws, const pp_ws_layout &lay,
+                 int32_t *status, hipStream_t st);
+// Candidates whose links have equal channel-time rows, position by position, have the same
+// partition DP (pp_share.hip).  pp_launch_share_prepare finds, on the device, one
+// representative per sequence of link classes (the lowest candidate index) and leaves the list
+// in the workspace (header fields share_*); the DP kernel for L > 128 then walks that list
+// only, and pp_launch_share_scatter copies every representative's results (nC entries of C_out
+// and nB of bounds_out per candidate) to the candidates it stands for.  Both do nothing when
+// the class sequences do not fit the table.  Only where lay.sh_table != 0.
+// fill_part != 0: also set the arg-min partials of the workspace (lay.part) to "none".
+int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, const int64_t *XB,
+                            const int32_t *ord, int validate, int fill_part, void *ws,
+                            const pp_ws_layout &lay, hipStream_t st);
+// With nT > 0 also T_out [nT][N] (the makespan kernel ran over the representatives as well).
+int pp_launch_share_scatter(int64_t N, int nC, int nB, int nT, int64_t *C_out, int32_t *bounds_out,
+                            int64_t *T_out, void *ws, const pp_ws_layout &lay, hipStream_t st);
+
 // Makespan of every candidate's plan for each of the nM microbatch counts in Ms (host array).
 // With part/C/out non-NULL the launch also finds, per microbatch count, the candidate
 // with the smallest T (lowest index on ties) and fills out[q] (one pair of int64 per wave of
@@ -134,12 +179,14 @@ struct pp_fuse_info {
     int32_t *bounds;
 };
 bool pp_makespan_can_fuse(int L, int D, int S);
+// rlist != NULL (needs hdr and part, and pp_makespan_takes_list(S)): see mk_args.
+bool pp_makespan_takes_list(int S);
 int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, const int64_t *PF,
                        const int64_t *PB, const int64_t *XF, const int64_t *XB,
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
                        pp_result *out, const pp_ws_header *hdr, const pp_fuse_info *fuse,
-                       hipStream_t st);
+                       const int32_t *rlist, hipStream_t st);
 // Stage-count search: makespan of the plan with xi stages of every candidate for xi = 1..S
 // (bounds [N][S(S+1)/2] and C [N][S] as pp_launch_dp leaves them with stages == 1), written to
 // T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest

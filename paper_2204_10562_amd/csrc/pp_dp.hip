@@ -311,9 +311,10 @@ static long long choose_chunk(int64_t N, int D, bool lex, long long simds, int w
 
 int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_t *PB,
                  const int64_t *XF, const int64_t *XB, const int32_t *lex_ord,
-                 const int32_t *user_ord, int stages, int defer_mmax, int64_t *C_out,
-                 int32_t *bounds_out, void *ws, const pp_ws_layout &lay, int32_t *status,
-                 hipStream_t st) {
+                 const int32_t *user_ord, int stages, int defer_mmax, int keep_list,
+                 int64_t *C_out, int32_t *bounds_out, void *ws, const pp_ws_layout &lay,
+                 int32_t *status, hipStream_t st) {
+    if (keep_list && !lay.sh_table) return PP_ERR_INVALID_ARG;
     char *base = (char *)ws;
     dp_args a;
     a.stages = stages;
@@ -377,5 +378,13 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         cus = 256;
     long long waves = lay.slots < N ? lay.slots : N;
-    return pp_launch_dp_big(a, (int)waves, cus, st);
+    if (!lay.sh_table) return pp_launch_dp_big(a, (int)waves, cus, NULL, st);
+    // candidates whose links have the same channel times share one DP: the kernel walks the
+    // representatives the preparation finds, and their results are copied to the others
+    int rc = pp_launch_share_prepare(L, D, S, N, XF, XB, a.ord, a.validate, keep_list, ws, lay, st);
+    if (rc) return rc;
+    rc = pp_launch_dp_big(a, (int)waves, cus, (const int *)(base + lay.sh_reps), st);
+    if (rc || keep_list) return rc;
+    return pp_launch_share_scatter(N, stages ? S : 1, stages ? S * (S + 1) / 2 : S, 0, C_out,
+                                   bounds_out, NULL, ws, lay, st);
 }

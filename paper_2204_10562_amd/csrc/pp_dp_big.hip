@@ -18,7 +18,8 @@
 // Per wave in LDS: two rows of keys (the row being read, rewritten in place as g, and the row
 // being produced).  Split indices go to a per-wave table in global memory while the next row's
 // g is built (one coalesced pass), and the plan is read back from there with cache-bypassing
-// loads.  Waves are persistent and walk candidates wave, wave + nwaves, ...
+// loads.  Waves are persistent and walk candidates wave, wave + nwaves, ... - all of them, or
+// the one representative of every group of candidates that are the same problem.
 #include "pp_common.h"
 #include "pp_dp_flat.h"
 #include "pp_dp_generic.h"
@@ -31,6 +32,9 @@ struct dp_big_args {
     int NI;      // super-rows: ceil(L / 128)
     int waves;   // working waves (each owns one backtrack table)
     size_t arg_stride;  // entries of one wave's backtrack table: S * Lp
+    // non-NULL: if the workspace header says so, walk this list of representatives (one per
+    // group of candidates with the same DP, see pp_share.hip) instead of all candidates
+    const int *reps;
     dp_args g;
 };
 
@@ -194,7 +198,10 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     unsigned long long pairs = 0, nrows = 0;
     const int tri = S * (S + 1) / 2;
 
-    for (long long c = wave; c < a.N; c += b.waves) {
+    const bool listed = b.reps != NULL && a.hdr->share_active != 0;
+    const long long todo = listed ? (long long)a.hdr->share_nreps : a.N;
+    for (long long r = wave; r < todo; r += b.waves) {
+        const long long c = listed ? (long long)b.reps[r] : r;
         // ordering: lane n holds device o[n]
         const int v_o = lane < S ? a.ord[c * S + lane] : 0;
         bool bad = false;
@@ -311,9 +318,10 @@ static int launch_big(const dp_big_args &b, int grid, int wpb, size_t lds, hipSt
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
-int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, hipStream_t st) {
+int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const int *reps, hipStream_t st) {
     dp_big_args b;
     b.g = g;
+    b.reps = reps;
     b.NI = (g.L + 127) / 128;
     const int Lp = 128 * b.NI, RS = Lp + 4;
     b.arg_stride = (size_t)g.S * Lp;

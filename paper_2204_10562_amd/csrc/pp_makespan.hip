@@ -79,6 +79,11 @@ struct mk_args {
     // bandwidth matrix, and W per (candidate, stage count) (PP_INF64 = no such plan)
     const int *reps;
     const long long *PA, *actf, *actb, *bw, *W;
+    // k_makespan_regs<S> inside pp_best_plan: non-NULL = if the workspace header says that
+    // candidates share their partition DP (pp_share.hip), this is the list of the candidates
+    // that stand for all others; only they are scheduled (entry i by lane i of the launch), and
+    // the slots of the partials no wave writes hold "none" already
+    const int *rlist;
     pp_rep_result *rout;   // [nM] winner records with replica counts (instead of out)
     // arg-min (all NULL when not wanted)
     tc_pair *part;         // [nM][waves]: every wave's minimum, reduced by k_pick
@@ -648,7 +653,7 @@ __device__ __forceinline__ bool fused_gather(const mk_args &a, long long c, bool
 // candidates for up to MK_REGS_WAVES counts: the scattered table lookups of the gather, which
 // cost more than the schedule itself for small M, are split between them by stage and
 // exchanged through LDS (dynamic, (J + 1 + waves) * 64 * 8 bytes; none for a single wave).
-template <int S, bool SHARE = false>
+template <int S, bool SHARE = false, bool LISTED = false>
 __device__ __forceinline__ void regs_body(const mk_args &a) {
     constexpr int R = 2 * S - 1, J = 4 * S - 3;
     extern __shared__ __align__(16) long long sh_all[];  // per group: [J+1][64] durations, [nw][64] worst
@@ -662,8 +667,16 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
     // one lane per candidate, or per block of `f` candidates that share this plan
     const long long f = SHARE ? a.share[S <= 8 ? S : 0] : 1;
     if (SHARE && (long long)blockIdx.x * 64 * f >= a.N) return;  // (the whole workgroup; G = 1)
-    const long long c = (group * 64 + lane) * f;
-    const bool live = c < a.N;
+    long long c = (group * 64 + lane) * f;
+    bool live = c < a.N;
+    if constexpr (LISTED) {
+        if (a.rlist && a.hdr->share_active) {
+            const long long todo = a.hdr->share_nreps;
+            if (group * 64 >= todo) return;  // (the whole workgroup: G = 1)
+            live = group * 64 + lane < todo;
+            c = live ? (long long)a.rlist[group * 64 + lane] : 0;
+        }
+    }
     sh_dur += (size_t)g * (J + 1 + nw) * 64;
     long long dur[J + 1];
     long long worst;
@@ -725,7 +738,7 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
 // 9 <= S <= 16: one kernel per S.
 template <int S>
 __global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs(mk_args a) {
-    regs_body<S>(a);
+    regs_body<S, false, true>(a);
 }
 
 // S <= 8: one kernel for all of them, so that the stage-count search can evaluate the plans of
@@ -1107,6 +1120,9 @@ static int launch_makespan(const mk_args &a, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
+// The kernels that can schedule a list of representatives instead of all candidates.
+bool pp_makespan_takes_list(int S) { return S >= 9 && S <= 16; }
+
 // The makespan kernel can build the plans itself (closed form, tables staged in LDS) for 2..8
 // stages when its tables fit beside the exchange area of the largest workgroup it may use.
 bool pp_makespan_can_fuse(int L, int D, int S) {
@@ -1119,8 +1135,10 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
                        const int32_t *orderings, const int32_t *bounds, int64_t *T_out,
                        int64_t *T_scratch, int32_t *status, const int64_t *C, void *part,
                        pp_result *out, const pp_ws_header *hdr, const pp_fuse_info *fuse,
-                       hipStream_t st) {
+                       const int32_t *rlist, hipStream_t st) {
+    if (rlist && (!pp_makespan_takes_list(S) || !hdr || !part)) return PP_ERR_INVALID_ARG;
     mk_args a = {};
+    a.rlist = rlist;
     a.L = L; a.D = D; a.S = S; a.N = N;
     a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
