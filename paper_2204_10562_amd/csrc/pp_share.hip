@@ -2,10 +2,11 @@
 //
 // Row n of the recursion for W(l, xi, r, i) (Sec. IV-B with one replica per stage) sees a
 // candidate's devices only through X_n[k], the time link (o[n-1], o[n]) needs for the
-// activations at cut position k.  Real clusters have few distinct bandwidths (Sec. V-A: NVLink,
-// PCIe, one network), so many links carry the same row X[.], and two candidates whose links
-// have equal rows position by position get the same table, bottleneck and plan.  This file
-// finds those groups on the device:
+// activations at cut position k.  Real clusters have few distinct bandwidths (Sec. III-A: PCIe
+// or NVLink inside a server, RDMA or TCP between servers; the testbeds of Sec. V-A have one of
+// each), so many links carry the same row X[.], and two candidates whose links have equal rows
+// position by position get the same table, bottleneck and plan.  This file finds those groups
+// on the device:
 //   1. k_share_hash     a hash of every link's forward and backward row (one wave per link),
 //                       and the table of representatives set to "none";
 //   2. k_share_classes  link i joins the class of the lowest link with the same hash whose rows
