@@ -34,7 +34,11 @@ struct pp_ws_header {
     // share_nc^(S-1) sequences of classes index a table; share_nreps candidates (one per
     // sequence that occurs, plus every candidate with a bad ordering) stand for all of them.
     unsigned share_active, share_nc, share_tsize, share_nreps;
-    unsigned pad0[60];
+    // the first share_nsorted entries of the list are the representatives in the order of their
+    // keys (first link most significant); the share_nbad candidates with a bad ordering follow,
+    // stored from the end of the array backwards (pp_share_at)
+    unsigned share_nsorted, share_nbad;
+    unsigned pad0[58];
     // byte 1024: work the partition DP actually did in this call, in 64 records of 128 bytes
     // (atomics that hit one cache line are served one after another, so every record has a
     // line of its own): (cell, split) pairs evaluated (rows shared between candidates are
@@ -58,7 +62,8 @@ __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long l
 struct pp_ws_layout {
     size_t hdr, p32, x32, xkt, xct, bfl, ord, arg, bounds, C, T, part, total;
     // candidates that share a DP (0 = not carved: see pp_share_possible)
-    size_t sh_hash, sh_rep, sh_table, sh_keys, sh_reps;
+    size_t sh_hash, sh_rep, sh_table, sh_keys, sh_reps, sh_cnt, sh_rows;
+    int sh_row_waves;  // waves that have a slice of sh_rows (saved DP rows, S rows of L + 132 keys)
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
@@ -71,6 +76,23 @@ struct pp_ws_layout {
 #define PP_SHARE_MAX_D 64
 static inline bool pp_share_possible(int L, int D, int64_t N) {
     return L > PP_TILE_MAX_L && D <= PP_SHARE_MAX_D && N < 0x7fffffff;
+}
+// Saved DP rows (see pp_dp_big.hip): waves that walk the list, bytes in all, keys per row.
+#ifndef PP_SHARE_ROW_WAVES
+#define PP_SHARE_ROW_WAVES 2048
+#endif
+#ifndef PP_SHARE_ROW_BYTES
+#define PP_SHARE_ROW_BYTES ((size_t)64 << 20)
+#endif
+#ifndef PP_SHARE_MIN_CHUNK
+#define PP_SHARE_MIN_CHUNK 8
+#endif
+__host__ __device__ static inline int pp_share_row_stride(int L) { return 128 * ((L + 127) / 128) + 4; }
+// Entry r of the list of representatives (hdr as the share kernels left it).
+__device__ __forceinline__ long long pp_share_at(const pp_ws_header *hdr, const int *reps, long long N,
+                                                 long long r) {
+    const long long ns = hdr->share_nsorted;
+    return r < ns ? reps[r] : reps[N - 1 - (r - ns)];
 }
 
 static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
@@ -91,13 +113,22 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.C = off;      off += pp_align256((size_t)N * 8);
     w.T = off;      off += pp_align256((size_t)N * 8);
     w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16 * PP_MAX_M_LIST);
-    w.sh_hash = w.sh_rep = w.sh_table = w.sh_keys = w.sh_reps = 0;
+    w.sh_hash = w.sh_rep = w.sh_table = w.sh_keys = w.sh_reps = w.sh_cnt = w.sh_rows = 0;
+    w.sh_row_waves = 0;
     if (pp_share_possible(L, D, N)) {
         w.sh_hash = off;  off += pp_align256((size_t)D * D * 8);
         w.sh_rep = off;   off += pp_align256((size_t)D * D * 4);
         w.sh_table = off; off += pp_align256((size_t)PP_SHARE_TABLE * 4);
         w.sh_keys = off;  off += pp_align256((size_t)N * 4);
         w.sh_reps = off;  off += pp_align256((size_t)N * 4);
+        w.sh_cnt = off;   off += pp_align256((size_t)(PP_SHARE_TABLE / 256) * 4);
+        // DP rows a wave keeps for the next representative of its chunk: at most 64 MiB
+        const size_t per_wave = (size_t)S * pp_share_row_stride(L) * 4;
+        size_t nw = PP_SHARE_ROW_BYTES / per_wave;
+        if (nw > PP_SHARE_ROW_WAVES) nw = PP_SHARE_ROW_WAVES;
+        if (nw > (size_t)w.slots) nw = (size_t)w.slots;
+        w.sh_row_waves = (int)nw;
+        w.sh_rows = off;  off += pp_align256(nw * per_wave);
     }
     w.total = off;
     return w;

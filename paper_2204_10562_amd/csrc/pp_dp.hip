@@ -383,7 +383,12 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     // representatives the preparation finds, and their results are copied to the others
     int rc = pp_launch_share_prepare(L, D, S, N, XF, XB, a.ord, a.validate, keep_list, ws, lay, st);
     if (rc) return rc;
-    rc = pp_launch_dp_big(a, (int)waves, cus, (const int *)(base + lay.sh_reps), st);
+    pp_share_list list;
+    list.reps = (const int *)(base + lay.sh_reps);
+    list.keys = (const int *)(base + lay.sh_keys);
+    list.rows = (int *)(base + lay.sh_rows);
+    list.row_waves = lay.sh_row_waves;
+    rc = pp_launch_dp_big(a, (int)waves, cus, &list, st);
     if (rc || keep_list) return rc;
     return pp_launch_share_scatter(N, stages ? S : 1, stages ? S * (S + 1) / 2 : S, 0, C_out,
                                    bounds_out, NULL, ws, lay, st);

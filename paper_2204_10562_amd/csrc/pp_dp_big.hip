@@ -33,8 +33,12 @@ struct dp_big_args {
     int waves;   // working waves (each owns one backtrack table)
     size_t arg_stride;  // entries of one wave's backtrack table: S * Lp
     // non-NULL: if the workspace header says so, walk this list of representatives (one per
-    // group of candidates with the same DP, see pp_share.hip) instead of all candidates
-    const int *reps;
+    // group of candidates with the same DP, see pp_share.hip) instead of all candidates: every
+    // wave a run of neighbours, which share their first links and so their first rows (keys:
+    // the key of every candidate; rows: row_waves slices of S saved rows of Lp + 4 keys)
+    const int *reps, *keys;
+    int *rows;
+    int row_waves;
     dp_args g;
 };
 
@@ -198,10 +202,43 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     unsigned long long pairs = 0, nrows = 0;
     const int tri = S * (S + 1) / 2;
 
+    // Which candidates this wave takes: every waves-th one, or, where candidates share their
+    // DP, a run of consecutive entries of the sorted list of representatives.
     const bool listed = b.reps != NULL && a.hdr->share_active != 0;
-    const long long todo = listed ? (long long)a.hdr->share_nreps : a.N;
-    for (long long r = wave; r < todo; r += b.waves) {
-        const long long c = listed ? (long long)b.reps[r] : r;
+    long long r_begin = wave, r_end = a.N, r_step = b.waves, nsorted = 0;
+    unsigned pw = 1;  // lane n = 1..S-1: (classes)^(S-1-n), the weight of the key's digit n
+    if (listed) {
+        const long long total = a.hdr->share_nreps;
+        nsorted = a.hdr->share_nsorted;
+        const long long nw = b.waves < b.row_waves ? b.waves : b.row_waves;
+        long long chunk = (total + nw - 1) / nw;
+        if (chunk < PP_SHARE_MIN_CHUNK) chunk = PP_SHARE_MIN_CHUNK;
+        r_begin = wave * chunk;
+        r_end = r_begin + chunk < total ? r_begin + chunk : total;
+        r_step = 1;
+        const unsigned nc = a.hdr->share_nc;
+        for (int n = lane + 1; n < S; ++n) pw *= nc;
+    }
+    int *save = b.rows + (size_t)(listed ? wave : 0) * S * RS;
+    int prev_key = -1;
+    int v_tops = 0;  // lane n keeps W[n][L] (with its split index) for the stage-count search
+    int *cur = bufA, *nxt = bufB;
+    for (long long r = r_begin; r < r_end; r += r_step) {
+        const long long c = listed ? pp_share_at(a.hdr, b.reps, a.N, r) : r;
+        // rows 1..p of the previous representative are this one's too: its key has the same
+        // first p digits (equal links give equal rows)
+        int p = 0, key = -1;
+        if (listed && r < nsorted) {
+            key = b.keys[c];
+            if (prev_key >= 0) {
+                const bool differ = lane >= 1 && lane < S && (unsigned)key / pw != (unsigned)prev_key / pw;
+                const unsigned long long m = __ballot(differ);
+                p = m ? __builtin_ctzll(m) - 1 : S - 2;
+                p = p < S - 2 ? p : S - 2;
+                p = p > 0 ? p : 0;
+            }
+        }
+        prev_key = key;
         // ordering: lane n holds device o[n]
         const int v_o = lane < S ? a.ord[c * S + lane] : 0;
         bool bad = false;
@@ -221,18 +258,29 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
                 if (lane == 0) a.C_out[c] = PP_INF64;
                 if (lane < S) a.bounds_out[c * S + lane] = 0;
             }
+            prev_key = -1;  // (the next candidate starts from row 0)
             continue;
         }
         const int v_link = __shfl_up(v_o, 1) * D + v_o;
 
-        // row 0: one stage holding the first l layers
-        int *cur = bufA, *nxt = bufB;
-        for (int l = lane; l <= Lp; l += 64) cur[l] = l ? sPk[l] + l : PP_INF32;
-        big_lds_sync();
-        int top = cur[L];  // S == 1: C = P[L]
-        int v_tops = top;  // lane n keeps W[n][L] (with its split index) for the stage-count search
+        int top = 0;
+        if (p == 0) {
+            // row 0: one stage holding the first l layers
+            for (int l = lane; l <= Lp; l += 64) cur[l] = l ? sPk[l] + l : PP_INF32;
+            big_lds_sync();
+            top = cur[L];  // S == 1: C = P[L]
+            v_tops = top;
+        } else {
+            // row p as this wave left it (stored by other lanes of the wave: wait for the
+            // stores, then read past the L1 cache)
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+            const int *from = save + (size_t)p * RS;
+            for (int l = lane; l <= Lp; l += 64)
+                cur[l] = __hip_atomic_load(from + l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            big_lds_sync();
+        }
 
-        for (int n = 1; n < S; ++n) {
+        for (int n = p + 1; n < S; ++n) {
             const int *xrow = a.x32 + (size_t)__builtin_amdgcn_readlane(v_link, n) * L;
             // Rewrite the previous row in place as g; on the way its split indices (the low
             // key bits) go to the backtrack table.
@@ -255,6 +303,11 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
                 int *t = cur; cur = nxt; nxt = t;
                 const int top_n = cur[L];
                 if (lane == n) v_tops = top_n;
+                if (listed) {
+                    // kept for the next representative of the run
+                    int *to = save + (size_t)n * RS;
+                    for (int l = lane; l <= Lp; l += 64) to[l] = cur[l];
+                }
             } else {
                 // only W[S-1][L] is needed of the last row
                 const int PL = sPk[L] + L;
@@ -318,10 +371,14 @@ static int launch_big(const dp_big_args &b, int grid, int wpb, size_t lds, hipSt
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
-int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const int *reps, hipStream_t st) {
+int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_list *list,
+                     hipStream_t st) {
     dp_big_args b;
     b.g = g;
-    b.reps = reps;
+    b.reps = list ? list->reps : NULL;
+    b.keys = list ? list->keys : NULL;
+    b.rows = list ? list->rows : NULL;
+    b.row_waves = list ? list->row_waves : 0;
     b.NI = (g.L + 127) / 128;
     const int Lp = 128 * b.NI, RS = Lp + 4;
     b.arg_stride = (size_t)g.S * Lp;

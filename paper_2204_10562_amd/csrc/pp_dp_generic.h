@@ -38,8 +38,15 @@ struct dp_args {
 
 // Kernel for 128 < L with 32-bit keys (pp_dp_big.hip): persistent waves, as many as fit the
 // GPU (cus compute units) but at most max_waves (the backtrack tables the workspace holds).
-// reps: the list pp_launch_share_prepare leaves in the workspace, or NULL.
-int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const int *reps, hipStream_t st);
+// list: what pp_launch_share_prepare leaves in the workspace (representatives, every
+// candidate's key, room for saved rows), or NULL.
+struct pp_share_list {
+    const int *reps, *keys;
+    int *rows;
+    int row_waves;
+};
+int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_list *list,
+                     hipStream_t st);
 
 // Loads candidate c's ordering into s_o[0..S-1]; returns false (uniformly) if it is not a
 // list of distinct devices below D.  Must be called by the whole workgroup.

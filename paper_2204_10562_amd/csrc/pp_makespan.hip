@@ -674,7 +674,7 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
             const long long todo = a.hdr->share_nreps;
             if (group * 64 >= todo) return;  // (the whole workgroup: G = 1)
             live = group * 64 + lane < todo;
-            c = live ? (long long)a.rlist[group * 64 + lane] : 0;
+            c = live ? pp_share_at(a.hdr, a.rlist, a.N, group * 64 + lane) : 0;
         }
     }
     sh_dur += (size_t)g * (J + 1 + nw) * 64;

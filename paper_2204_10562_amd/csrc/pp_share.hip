@@ -12,12 +12,15 @@
 //   2. k_share_classes  link i joins the class of the lowest link with the same hash whose rows
 //                       are equal entry by entry (one wave per link);
 //   3. k_share_keys     classes numbered 0..nc-1; a candidate's key is its sequence of S-1
-//                       class numbers read as a number in base nc, and the lowest candidate of
-//                       every key is kept with an atomic min (only if nc^(S-1) fits the table);
-//   4. k_share_reps     the table compacted into the list of representatives.
-// The DP kernel walks the list, and k_share_scatter hands every representative's results to the
-// candidates of its key.  Candidates with a bad ordering are representatives of themselves, so
-// the DP kernel reports them as it always does.  All decisions are taken on the device; when
+//                       class numbers read as a number in base nc (first link most
+//                       significant), and the lowest candidate of every key is kept with an
+//                       atomic min (only if nc^(S-1) fits the table);
+//   4. k_share_count, k_share_reps   the table compacted, in the order of the keys, into the
+//                       list of representatives.
+// The DP kernel walks the list - neighbours in it share their first links and with them the
+// first rows of the table - and k_share_scatter hands every representative's results to the
+// candidates of its key.  Candidates with a bad ordering are representatives of themselves
+// (kept after the sorted ones), so the DP kernel reports them as it always does.  All decisions are taken on the device; when
 // the keys do not fit the table the kernels return at once and the DP runs over all candidates.
 #include "pp_common.h"
 
@@ -31,7 +34,8 @@ struct share_args {
     int *lrep;                  // [D*D] lowest link with equal rows (-1 on the diagonal)
     int *table;                 // [PP_SHARE_TABLE] lowest candidate of every key
     int *keys;                  // [N] key of every candidate (-1: bad ordering)
-    int *reps;                  // [N] representatives, in no particular order
+    int *reps;                  // [N] representatives (see pp_share_at)
+    int *cnt;                   // [PP_SHARE_TABLE / 256] keys in use per 256 table entries
     // arg-min partials to preset (pairs of int64), or NULL
     long long *part;
     long long n_part;
@@ -67,6 +71,8 @@ __global__ __launch_bounds__(256) void k_share_hash(share_args a) {
         a.hdr->share_nc = 0;
         a.hdr->share_tsize = 0;
         a.hdr->share_nreps = 0;
+        a.hdr->share_nsorted = 0;
+        a.hdr->share_nbad = 0;
     }
     const int i = blockIdx.x * 4 + (tid >> 6);
     if (i >= nl) return;
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(256) void k_share_keys(share_args a) {
     for (long long c = (long long)blockIdx.x * 256 + tid; c < a.N; c += (long long)gridDim.x * 256) {
         const int *row = a.ord + c * S;
         unsigned long long used = 0;
-        unsigned key = 0, mul = 1;
+        unsigned key = 0;
         bool bad = false;
         int prev = 0;
         auto step = [&](int n, int d) {
@@ -168,10 +174,7 @@ __global__ __launch_bounds__(256) void k_share_keys(share_args a) {
                 bad |= (used >> d) & 1;
                 used |= 1ull << d;
             }
-            if (n) {
-                key += (unsigned)s_cls[prev * D + d] * mul;
-                mul *= (unsigned)nc;
-            }
+            if (n) key = key * (unsigned)nc + (unsigned)s_cls[prev * D + d];
             prev = d;
         };
         if (vec) {
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(256) void k_share_keys(share_args a) {
         }
         if (bad) {
             a.keys[c] = -1;
-            a.reps[atomicAdd(&a.hdr->share_nreps, 1u)] = (int)c;
+            a.reps[a.N - 1 - atomicAdd(&a.hdr->share_nbad, 1u)] = (int)c;
         } else {
             a.keys[c] = (int)key;
             // (most candidates of a common key arrive after a lower one: a look first spares
@@ -196,25 +199,53 @@ __global__ __launch_bounds__(256) void k_share_keys(share_args a) {
     }
 }
 
+// Keys in use in every block of 256 table entries.
+__global__ __launch_bounds__(256) void k_share_count(share_args a) {
+    __shared__ int sh[4];
+    const unsigned tsize = a.hdr->share_tsize;
+    const unsigned key = blockIdx.x * 256u + threadIdx.x;
+    const bool has = key < tsize && a.table[key] != SHARE_NONE;
+    const unsigned long long mask = __ballot(has);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = __builtin_popcountll(mask);
+    __syncthreads();
+    if (threadIdx.x == 0) a.cnt[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
 __global__ __launch_bounds__(256) void k_share_reps(share_args a) {
+    __shared__ int sh[4], shw[4];
+    const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
     // (T, candidate) = "none" in every slot of the arg-min's partials: the makespan kernel that
     // walks the list writes only the slots of the waves that have a representative
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < a.n_part; i += (long long)gridDim.x * 256) {
+    for (long long i = (long long)blockIdx.x * 256 + tid; i < a.n_part; i += (long long)gridDim.x * 256) {
         a.part[2 * i] = PP_INF64;
         a.part[2 * i + 1] = INT64_MAX;
     }
     const unsigned tsize = a.hdr->share_tsize;
-    if (blockIdx.x * 256u >= tsize) return;
-    const unsigned key = blockIdx.x * 256u + threadIdx.x;
+    if (blockIdx.x * 256u >= tsize && blockIdx.x) return;
+    // keys in use before this block's (block 0: in all blocks, for the header)
+    const int upto = blockIdx.x ? (int)blockIdx.x : PP_SHARE_TABLE / 256;
+    int sum = 0;
+    for (int i = tid; i < upto; i += 256) sum += a.cnt[i];
+    for (int off = 32; off; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) sh[wib] = sum;
+    __syncthreads();
+    const int before = sh[0] + sh[1] + sh[2] + sh[3];
+    if (blockIdx.x == 0) {
+        if (tid == 0) {
+            a.hdr->share_nsorted = (unsigned)before;
+            a.hdr->share_nreps = (unsigned)before + a.hdr->share_nbad;
+        }
+    }
+    const int base = blockIdx.x ? before : 0;
+    const unsigned key = blockIdx.x * 256u + tid;
     const int c = key < tsize ? a.table[key] : SHARE_NONE;
     const bool has = c != SHARE_NONE;
     const unsigned long long mask = __ballot(has);
-    if (!mask) return;
-    const int lane = threadIdx.x & 63;
-    unsigned base = 0;
-    if (lane == 0) base = atomicAdd(&a.hdr->share_nreps, (unsigned)__builtin_popcountll(mask));
-    base = __builtin_amdgcn_readfirstlane(base);
-    if (has) a.reps[base + __builtin_popcountll(mask & ((1ull << lane) - 1))] = c;
+    if (lane == 0) shw[wib] = __builtin_popcountll(mask);
+    __syncthreads();
+    int at = base + __builtin_popcountll(mask & ((1ull << lane) - 1));
+    for (int w = 0; w < wib; ++w) at += shw[w];
+    if (has) a.reps[at] = c;
 }
 
 // Every candidate that is not the representative of its key takes the representative's
@@ -247,6 +278,7 @@ static share_args share_base(void *ws, const pp_ws_layout &lay) {
     a.table = (int *)(base + lay.sh_table);
     a.keys = (int *)(base + lay.sh_keys);
     a.reps = (int *)(base + lay.sh_reps);
+    a.cnt = (int *)(base + lay.sh_cnt);
     return a;
 }
 
@@ -271,6 +303,7 @@ int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, c
     hipLaunchKernelGGL(k_share_hash, dim3(link_blocks + SHARE_FILL_BLOCKS), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_classes, dim3(link_blocks), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_keys, dim3((unsigned)share_grid(N)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_share_count, dim3(PP_SHARE_TABLE / 256), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_reps, dim3(PP_SHARE_TABLE / 256), dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
