@@ -130,13 +130,15 @@ __device__ __forceinline__ int gather_durations(const mk_args &a, long long c, b
                 if (bad) fault |= PP_FAULT_ORDERING;
             }
         }
-        int prev = 0;
+        // (a bad ordering is reported alone: its plan is not looked at)
+        int prev = 0, fb = 0;
         for (int n = 0; n < S; ++n) {
             int e = a.bounds[c * a.bnd_stride + bnd_off + n];
-            if (e <= prev || e > L) fault |= PP_FAULT_BOUNDS;
+            if (e <= prev || e > L) fb = PP_FAULT_BOUNDS;
             prev = e;
         }
-        if (prev != L) fault |= PP_FAULT_BOUNDS;
+        if (prev != L) fb = PP_FAULT_BOUNDS;
+        fault = fault ? fault : fb;
     }
     worst = 0;
     unsigned long long rem = (unsigned long long)(live ? c : 0);

@@ -573,7 +573,7 @@ def test_best_plan_equal_activations_wide_and_faults(ppo, G):
     g.set_tables(*tables)
     say("best_plan equal activations, faults")
     st, res, T, C = g.best(6)
-    assert st & ppo.FAULT_ORDERING
+    assert st == ppo.FAULT_ORDERING
     keep = np.array([c for c in range(w.N) if c not in (13, 63, 199)])
     np.testing.assert_array_equal(T[keep], T0[keep])
     np.testing.assert_array_equal(C[keep], C0[keep])

@@ -227,7 +227,7 @@ def test_shared_schedule(ppo, G, seed, L, D, S, N, size):
     say("shared schedule", seed, L, D, S, N)
     for want_all in (True, False):
         st, res, T, C = g.best_multi(Ms, want_all=want_all)
-        assert st & ppo.FAULT_ORDERING
+        assert st == ppo.FAULT_ORDERING
         for q, M in enumerate(Ms):
             assert res[q] == want[q][1]
             if want_all:
@@ -240,7 +240,7 @@ def test_shared_schedule(ppo, G, seed, L, D, S, N, size):
     assert stats["share_active"] == 1 and stats["share_computed"] == len(set(keys)) + len(bad)
     # a single count through pp_best_plan
     st, r1, T1, C1 = g.best(Ms[1])
-    assert st & ppo.FAULT_ORDERING and r1 == want[1][1]
+    assert st == ppo.FAULT_ORDERING and r1 == want[1][1]
     np.testing.assert_array_equal(T1, want[1][0])
     np.testing.assert_array_equal(C1, C0)
     # and without bad rows the whole search against the oracle's
