@@ -184,6 +184,9 @@ def main():
         % (t_dp["mean"] * 1e6, t_dp["median"] * 1e6, t_dp["min"] * 1e6, pairs / t_dp["mean"], N * S * L / t_dp["mean"],
            "   [closed form: transfer times do not depend on the cut position]" if closed_form else ""))
     log("     executed %d of %d nominal pair-evals (%d rows)" % (stats["pairs_executed"], pairs, stats["rows_executed"]))
+    if L > 128 and stats["share_active"]:
+        log("     %d link classes: %d of the %d candidates computed, the others share their results"
+            % (stats["share_classes"], stats["share_computed"], N))
     for M in Ms:
         log("  pp_schedule_makespan M=%-3d %7.1f us   %.3e block-ops/s" % (M, t_mk[M]["mean"] * 1e6, N * M * (4 * S - 3) / t_mk[M]["mean"]))
     log("  pp_schedule_makespan_multi %6.1f us (median %.1f, min %.1f)   %.3e block-ops/s = %.1f%% of int32 VALU peak at %d ops/block-op"
@@ -372,7 +375,10 @@ def main():
         "dp": {"entry_point": "pp_partition_dp", "closed_form": closed_form, "call": us(t_dp),
                "dp_cells_per_s": N * S * L / t_dp["mean"], "dp_nominal_pair_evals_per_s": pairs / t_dp["mean"],
                "pair_evals_executed_per_launch": stats["pairs_executed"], "pair_evals_nominal_per_launch": pairs,
-               "rows_executed_per_launch": stats["rows_executed"]},
+               "rows_executed_per_launch": stats["rows_executed"],
+               # candidates whose links have the same transfer times share one DP (L > 128)
+               "shared": ({"link_classes": stats["share_classes"], "candidates_computed": stats["share_computed"]}
+                          if L > 128 and stats["share_active"] else None)},
         "dp_cells_per_s": N * S * L / t_dp["mean"],
         "prefix": {"entry_point": "pp_prefix_costs", "call": us(t_prefix), "algorithmic_bytes": prefix_bytes,
                    "GB_per_s": prefix_bytes / t_prefix["mean"] / 1e9, "hbm_peak_GB_per_s": 8000},
