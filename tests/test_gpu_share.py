@@ -253,3 +253,59 @@ def test_shared_schedule(ppo, G, seed, L, D, S, N, size):
         assert rc == 0 and res[q] == r0
         np.testing.assert_array_equal(T[q], T0)
         np.testing.assert_array_equal(C, C1)
+
+
+def test_shared_corner_shapes(ppo, G):
+    # a single stage (one key for everybody), and a list in which every row is bad
+    w = islands(workloads.random_small(4801, 140, 4, 1, 50, hi_time=60, hi_act=50000), 2, 100, 10)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("shared dp, one stage")
+    check_shared(ppo, g, w, tables)
+    w = islands(workloads.random_small(4802, 150, 5, 4, 40, hi_time=60, hi_act=50000), 2, 100, 10)
+    w.orderings = w.orderings.copy()
+    w.orderings[:, 2] = w.orderings[:, 0]
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("shared dp, every row bad")
+    st, C, b = g.dp()
+    assert st == ppo.FAULT_ORDERING
+    assert (C == np.iinfo(np.int64).max).all() and (b == 0).all()
+    st, res, T, C = g.best(3)
+    assert st == ppo.FAULT_ORDERING and res["best_index"] == -1
+    assert (T == np.iinfo(np.int64).max).all()
+
+
+@pytest.mark.parametrize("kind", ["equal_activations", "wide_times"])
+def test_shared_schedule_other_dp_paths(ppo, G, kind):
+    # 9..16 stages on more than 128 layers where the DP itself takes another path: the closed
+    # form (transfer times that do not depend on the cut position) and the 64-bit fallback
+    # (times beyond the 32-bit keys); the schedule still runs over the representatives
+    w = workloads.random_small(4901, 180, 12, 10, 1200, hi_time=40, hi_act=30000, same_act=kind == "equal_activations")
+    w = islands(w, 4, 160, 21)
+    if kind == "wide_times":
+        w.fwd = w.fwd << 34
+        w.bwd = w.bwd << 34
+        w.actf = w.actf << 30
+        w.actb = w.actb << 30
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("shared schedule,", kind)
+    Ms = (2, 37)
+    st, res, T, C = g.best_multi(Ms)
+    assert st == 0
+    for q, M in enumerate(Ms):
+        rc, r0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, M, *tables, w.orderings)
+        assert rc == 0 and res[q] == r0
+        np.testing.assert_array_equal(T[q], T0)
+        np.testing.assert_array_equal(C, C0)
+    st, res2, _, _ = g.best_multi(Ms, want_all=False)
+    assert st == 0 and res2 == res
+    from paper_2204_10562_amd import binding as pp
+    stats = pp.read_workspace_stats(g.ws)
+    assert stats["share_active"] == 1 and stats["share_computed"] < w.N
+    if kind == "equal_activations":
+        assert stats["rows_executed"] == 0
