@@ -1,6 +1,6 @@
-// Partition DP for 128 < L <= 2048 with 32-bit keys: one wavefront per candidate, the
-// (cell, split) plane tiled in 128 x 128 super-tiles, each of them spread over the 64 lanes as
-// 16 x 16 blocks of 8 x 8.
+// Partition DP for 128 < L <= 2048 with 32-bit keys: one wavefront per candidate, the cells of
+// a row in super-rows of 128, the (cell, split) plane in blocks of 32 x 32 that the 64 lanes
+// cover as 4 x 4 tiles of 8 x 8.
 //
 // Recursion for W(l, xi, r, i) of Sec. IV-B / the PRM listing with one replica per stage:
 //   W[n][l] = min_{n<=k<l} max(g_n[k], P[l] - P[k]),   g_n[k] = max(W[n-1][k], X_n[k]).
@@ -18,8 +18,10 @@
 // Per wave in LDS: two rows of keys (the row being read, rewritten in place as g, and the row
 // being produced).  Split indices go to a per-wave table in global memory while the next row's
 // g is built (one coalesced pass), and the plan is read back from there with cache-bypassing
-// loads.  Waves are persistent and walk candidates wave, wave + nwaves, ... - all of them, or
-// the one representative of every group of candidates that are the same problem.
+// loads.  Waves are persistent and walk candidates wave, wave + nwaves, ...; where groups of
+// candidates are the same problem (pp_share.hip) a wave instead takes a run of consecutive
+// entries of the sorted list of representatives, keeps every row it computes in the workspace
+// and starts each representative at the first row its predecessor does not share.
 #include "pp_common.h"
 #include "pp_dp_flat.h"
 #include "pp_dp_generic.h"
