@@ -96,12 +96,19 @@ extern "C" int pp_best_plan_stages(int L, int D, int S, int64_t N, int nM, const
     const int32_t *ord = NULL;
     rc = pp_launch_pack(L, D, S, N, PF, PB, XF, XB, orderings, workspace, lay, &ord, st);
     if (rc) return rc;
-    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, 0, 0, C, bounds,
-                      workspace, lay, status, st);
+    // (where candidates share their DP the plans of the representatives are scheduled and
+    // compared, and the others get T and C only if the caller wants the arrays)
+    const bool listed = lay.sh_table != 0 && pp_makespan_takes_list(S);
+    rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 1, 0, listed, C,
+                      bounds, workspace, lay, status, st);
     if (rc) return rc;
-    return pp_launch_makespan_stages(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, C, T,
-                                     status, base + sl.part, out, (const pp_ws_header *)(base + lay.hdr),
-                                     orderings == NULL, st);
+    rc = pp_launch_makespan_stages(L, D, S, N, nM, M_list, PF, PB, XF, XB, ord, bounds, C, T,
+                                   status, base + sl.part, out, (const pp_ws_header *)(base + lay.hdr),
+                                   orderings == NULL, listed ? (const int32_t *)(base + lay.sh_reps) : NULL,
+                                   st);
+    if (rc || !listed || (!T_all && !C_all)) return rc;
+    return pp_launch_share_scatter(N, C_all ? S : 0, 0, T_all ? nM : 0, S, C_all, NULL, T_all, workspace,
+                                   lay, st);
 }
 
 extern "C" int pp_schedule_makespan(int L, int D, int S, int64_t N, int M, const int64_t *PF,
@@ -179,12 +186,12 @@ extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const 
     fuse.bfl = (const int64_t *)(base + lay.bfl);
     fuse.C = C;
     fuse.bounds = bounds;
-    const bool can_fuse = pp_makespan_can_fuse(L, D, S);
     // Where candidates share their partition DP (L > 128, few distinct link times) the schedule
     // is shared too: only the representatives are evaluated, the arg-min runs over them (a
     // representative is the lowest candidate of its group, so ties still go to the lowest
     // index), and T and C reach the other candidates only if the caller wants the arrays.
     const bool listed = lay.sh_table != 0 && pp_makespan_takes_list(S);
+    const bool can_fuse = !listed && pp_makespan_can_fuse(L, D, S);
     rc = pp_launch_dp(L, D, S, N, PF, PB, XF, XB, orderings ? NULL : ord, orderings, 0,
                       can_fuse ? fuse.mmax : 0, listed, C, bounds, workspace, lay, status, st);
     if (rc) return rc;
@@ -193,7 +200,7 @@ extern "C" int pp_best_plan_multi(int L, int D, int S, int64_t N, int nM, const 
                             (const pp_ws_header *)(base + lay.hdr), can_fuse ? &fuse : NULL,
                             listed ? (const int32_t *)(base + lay.sh_reps) : NULL, st);
     if (rc || !listed || (!T_all && !C_all)) return rc;
-    return pp_launch_share_scatter(N, C_all ? 1 : 0, 0, T_all ? nM : 0, C_all, NULL, T_all, workspace,
+    return pp_launch_share_scatter(N, C_all ? 1 : 0, 0, T_all ? nM : 0, 1, C_all, NULL, T_all, workspace,
                                    lay, st);
 }
 

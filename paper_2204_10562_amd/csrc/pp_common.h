@@ -186,9 +186,10 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
 int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, const int64_t *XB,
                             const int32_t *ord, int validate, int fill_part, void *ws,
                             const pp_ws_layout &lay, hipStream_t st);
-// With nT > 0 also T_out [nT][N] (the makespan kernel ran over the representatives as well).
-int pp_launch_share_scatter(int64_t N, int nC, int nB, int nT, int64_t *C_out, int32_t *bounds_out,
-                            int64_t *T_out, void *ws, const pp_ws_layout &lay, hipStream_t st);
+// With nT > 0 also T_out [nT][N][tw] (the makespan kernel ran over the representatives as well).
+int pp_launch_share_scatter(int64_t N, int nC, int nB, int nT, int tw, int64_t *C_out,
+                            int32_t *bounds_out, int64_t *T_out, void *ws, const pp_ws_layout &lay,
+                            hipStream_t st);
 
 // Makespan of every candidate's plan for each of the nM microbatch counts in Ms (host array).
 // With part/C/out non-NULL the launch also finds, per microbatch count, the candidate
@@ -223,11 +224,13 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
 // T_st [nM][N][S], then per microbatch count the smallest T over all (candidate, xi), lowest
 // candidate and then lowest xi on ties, into out[q].  part must hold 1024 * nM pairs of int64.
 // lex: `orderings` is the library's own list of all D! orderings in lexicographic order.
+// rlist != NULL (S <= 16, needs hdr): only the representatives are scheduled (see mk_args).
 int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int *Ms,
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              pp_result *out, const pp_ws_header *hdr, int lex, hipStream_t st);
+                              pp_result *out, const pp_ws_header *hdr, int lex,
+                              const int32_t *rlist, hipStream_t st);
 // Makespan (Eq. 2) of the plans with replicated stages of every (candidate, stage count) and
 // the keep-the-minimum over them; arrays laid out as pp_plan_replicated documents; part holds
 // 1024 pairs of int64.

@@ -390,6 +390,6 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     list.row_waves = lay.sh_row_waves;
     rc = pp_launch_dp_big(a, (int)waves, cus, &list, st);
     if (rc || keep_list) return rc;
-    return pp_launch_share_scatter(N, stages ? S : 1, stages ? S * (S + 1) / 2 : S, 0, C_out,
+    return pp_launch_share_scatter(N, stages ? S : 1, stages ? S * (S + 1) / 2 : S, 0, 1, C_out,
                                    bounds_out, NULL, ws, lay, st);
 }

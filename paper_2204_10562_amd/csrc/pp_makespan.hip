@@ -684,7 +684,7 @@ __device__ __forceinline__ void regs_body(const mk_args &a) {
     long long worst;
     int fault;
     bool gathered = false;
-    if constexpr (!SHARE && S >= 2 && S <= 8) {
+    if constexpr (!SHARE && !(LISTED && S <= 8) && S >= 2 && S <= 8) {
         if (a.fuse) gathered = fused_gather<S>(a, c, live, g, w, nw, G, dur, worst, fault);
     }
     if (gathered) {
@@ -757,6 +757,21 @@ __global__ __launch_bounds__(64 * MK_REGS_WAVES * MK_REGS_GROUPS) void k_makespa
         case 6: regs_body<6>(a); break;
         case 7: regs_body<7>(a); break;
         case 8: regs_body<8>(a); break;
+    }
+}
+
+// The same over the list of representatives (see mk_args::rlist; always one group per
+// workgroup).  A kernel of its own so that the plain one stays as lean as it is.
+__global__ __launch_bounds__(64 * MK_REGS_WAVES) void k_makespan_regs8_listed(mk_args a) {
+    switch (a.all_xi ? (int)blockIdx.z + 1 : a.S) {
+        case 1: regs_body<1, false, true>(a); break;
+        case 2: regs_body<2, false, true>(a); break;
+        case 3: regs_body<3, false, true>(a); break;
+        case 4: regs_body<4, false, true>(a); break;
+        case 5: regs_body<5, false, true>(a); break;
+        case 6: regs_body<6, false, true>(a); break;
+        case 7: regs_body<7, false, true>(a); break;
+        case 8: regs_body<8, false, true>(a); break;
     }
 }
 
@@ -1029,7 +1044,7 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         cus = 256;
     // (with no more groups than compute units every wave has a SIMD of its own anyway)
-    if (S == 0 && nw == 4 && a.nM == 4 && !a.all_xi && grid > (unsigned)cus) {
+    if (S == 0 && nw == 4 && a.nM == 4 && !a.all_xi && !a.rlist && grid > (unsigned)cus) {
         long long wt[4];
         for (int i = 0; i < 4; ++i) wt[i] = a.Ms[b.order[i]];
         int perms[24][4], np = 0;
@@ -1061,7 +1076,10 @@ static int launch_regs(const mk_args &a, hipStream_t st) {
         lds_all = need > lds_all ? need : lds_all;
     }
     if constexpr (S == 0) {
-        if (a.all_xi && a.share[a.S > 2 ? a.S - 2 : 0] > 1)
+        if (a.rlist)
+            hipLaunchKernelGGL(k_makespan_regs8_listed, dim3(grid, (a.nM + nw - 1) / nw, a.all_xi ? a.S : 1),
+                               dim3(64 * nw), lds, st, b);
+        else if (a.all_xi && a.share[a.S > 2 ? a.S - 2 : 0] > 1)
             hipLaunchKernelGGL(k_makespan_regs8_shared, dim3(grid, (a.nM + nw - 1) / nw, a.S),
                                dim3(64 * nw), lds, st, b);
         else
@@ -1123,7 +1141,7 @@ static int launch_makespan(const mk_args &a, hipStream_t st) {
 }
 
 // The kernels that can schedule a list of representatives instead of all candidates.
-bool pp_makespan_takes_list(int S) { return S >= 9 && S <= 16; }
+bool pp_makespan_takes_list(int S) { return S >= 1 && S <= 16; }
 
 // The makespan kernel can build the plans itself (closed form, tables staged in LDS) for 2..8
 // stages when its tables fit beside the exchange area of the largest workgroup it may use.
@@ -1151,7 +1169,7 @@ int pp_launch_makespan(int L, int D, int S, int64_t N, int nM, const int *Ms, co
     a.T_out = (long long *)T_out; a.status = status;
     a.part = (tc_pair *)part; a.C = (const long long *)C; a.out = out;
     a.hdr = hdr;
-    if (fuse && hdr && pp_makespan_can_fuse(L, D, S)) {
+    if (fuse && hdr && !rlist && pp_makespan_can_fuse(L, D, S)) {
         a.fuse = 1;
         a.fuse_mmax = fuse->mmax;
         a.fuse_validate = fuse->validate;
@@ -1190,9 +1208,20 @@ __global__ __launch_bounds__(64) void k_argmin(mk_args a) {
     const int lane = threadIdx.x, q = blockIdx.y;
     const long long *T = a.T_out + (long long)q * a.N;
     tc_pair v = {PP_INF64, INT64_MAX};
-    for (long long c = (long long)blockIdx.x * 64 + lane; c < a.N; c += (long long)gridDim.x * 64) {
-        tc_pair o = {T[c], c};
-        v = tc_min(v, o);
+    if (a.rlist && a.hdr->share_active) {
+        // only the rows of the representatives hold values: entry (r, x) of the list is entry
+        // rep(r) * w + x of T (w entries per candidate: the stage counts of the search)
+        const long long w = a.search ? a.search : 1, todo = (long long)a.hdr->share_nreps * w;
+        for (long long i = (long long)blockIdx.x * 64 + lane; i < todo; i += (long long)gridDim.x * 64) {
+            const long long r = i / w, c = pp_share_at(a.hdr, a.rlist, a.N / w, r) * w + (i - r * w);
+            tc_pair o = {T[c], c};
+            v = tc_min(v, o);
+        }
+    } else {
+        for (long long c = (long long)blockIdx.x * 64 + lane; c < a.N; c += (long long)gridDim.x * 64) {
+            tc_pair o = {T[c], c};
+            v = tc_min(v, o);
+        }
     }
     // emit() reduces over the wave: hand it this lane's minimum as if it were the lane's own
     // candidate; T_out must not be rewritten
@@ -1226,8 +1255,11 @@ int pp_launch_makespan_stages(int L, int D, int S, int64_t N, int nM, const int 
                               const int64_t *PF, const int64_t *PB, const int64_t *XF,
                               const int64_t *XB, const int32_t *orderings, const int32_t *bounds,
                               const int64_t *C, int64_t *T_st, int32_t *status, void *part,
-                              pp_result *out, const pp_ws_header *hdr, int lex, hipStream_t st) {
+                              pp_result *out, const pp_ws_header *hdr, int lex,
+                              const int32_t *rlist, hipStream_t st) {
+    if (rlist && (!pp_makespan_takes_list(S) || !hdr)) return PP_ERR_INVALID_ARG;
     mk_args a = {};
+    a.rlist = rlist;
     a.L = L; a.D = D; a.N = N; a.nM = nM;
     for (int q = 0; q < PP_MAX_M_LIST; ++q) a.Ms[q] = q < nM ? Ms[q] : 1;
     a.PF = (const long long *)PF; a.PB = (const long long *)PB;

@@ -40,7 +40,7 @@ struct share_args {
     long long *part;
     long long n_part;
     // scatter
-    int nC, nB, nT, vec;
+    int nC, nB, nT, tw, vec;
     long long *C_out, *T_out;
     int *bounds_out;
 };
@@ -258,7 +258,8 @@ __global__ __launch_bounds__(256) void k_share_scatter(share_args a) {
         const long long r = a.table[key];
         if (r == c) continue;
         for (int i = 0; i < a.nC; ++i) a.C_out[c * a.nC + i] = a.C_out[r * a.nC + i];
-        for (int q = 0; q < a.nT; ++q) a.T_out[q * a.N + c] = a.T_out[q * a.N + r];
+        for (int q = 0; q < a.nT; ++q)
+            for (int i = 0; i < a.tw; ++i) a.T_out[(q * a.N + c) * a.tw + i] = a.T_out[(q * a.N + r) * a.tw + i];
         if (a.vec) {
             const int4 *src = (const int4 *)(a.bounds_out + r * a.nB);
             int4 *dst = (int4 *)(a.bounds_out + c * a.nB);
@@ -308,11 +309,12 @@ int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, c
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
-int pp_launch_share_scatter(int64_t N, int nC, int nB, int nT, int64_t *C_out, int32_t *bounds_out,
-                            int64_t *T_out, void *ws, const pp_ws_layout &lay, hipStream_t st) {
+int pp_launch_share_scatter(int64_t N, int nC, int nB, int nT, int tw, int64_t *C_out,
+                            int32_t *bounds_out, int64_t *T_out, void *ws, const pp_ws_layout &lay,
+                            hipStream_t st) {
     if (!lay.sh_table) return PP_ERR_INVALID_ARG;
     share_args a = share_base(ws, lay);
-    a.N = N; a.nC = nC; a.nB = nB; a.nT = nT;
+    a.N = N; a.nC = nC; a.nB = nB; a.nT = nT; a.tw = tw;
     a.C_out = (long long *)C_out;
     a.T_out = (long long *)T_out;
     a.bounds_out = bounds_out;

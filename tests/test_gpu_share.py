@@ -167,22 +167,31 @@ def test_shared_dp_bad_orderings(ppo, G):
     assert stats["share_computed"] == len(set(keys)) + len(bad)
 
 
-def test_shared_dp_stage_counts_and_best_plan(ppo, G):
+@pytest.mark.parametrize("seed,L,D,S,N,size", [(4601, 145, 6, 6, 800, 2), (4602, 170, 12, 12, 1500, 4),
+                                               (4603, 133, 10, 8, 600, 5)])
+def test_shared_dp_stage_counts_and_best_plan(ppo, G, seed, L, D, S, N, size):
     # the plans for every stage count, and the whole search with its arg-min, on shared DPs
-    w = islands(workloads.random_small(4601, 145, 6, 6, 800, hi_time=60, hi_act=50000), 2, 210, 17)
+    # (the schedules too run over the representatives only)
+    w = islands(workloads.random_small(seed, L, D, S, N, hi_time=60, hi_act=50000), size, 210, 17)
     tables = oracle_tables(ppo, w)
     g = G(w)
     g.set_tables(*tables)
-    say("shared dp, stage counts")
+    say("shared dp, stage counts", seed, L, D, S, N)
     st, C, bounds = g.dp_stages()
     assert st == 0
-    rc, res0, T0, C0, b0 = ppo.best_plan_stages(w.L, w.D, w.S, w.N, 7, *tables, w.orderings)
-    assert rc == 0
-    np.testing.assert_array_equal(C, C0)
-    np.testing.assert_array_equal(bounds, b0)
-    st, res, T, C2 = g.best_stages((7,))
-    assert st == 0 and res[0] == res0
-    np.testing.assert_array_equal(T[0], T0)
+    Ms = (7, 2 * S + 1)
+    want = [ppo.best_plan_stages(w.L, w.D, w.S, w.N, M, *tables, w.orderings) for M in Ms]
+    assert all(x[0] == 0 for x in want)
+    np.testing.assert_array_equal(C, want[0][3])
+    np.testing.assert_array_equal(bounds, want[0][4])
+    for want_all in (True, False):
+        st, res, T, C2 = g.best_stages(Ms, want_all=want_all)
+        assert st == 0
+        for q in range(len(Ms)):
+            assert res[q] == want[q][1]
+            if want_all:
+                np.testing.assert_array_equal(T[q], want[q][2])
+                np.testing.assert_array_equal(C2, want[q][3])
     say("shared dp, best plan")
     for want_all in (True, False):
         st, res, T, C1 = g.best_multi((3, 24), want_all=want_all)
