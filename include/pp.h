@@ -112,7 +112,10 @@ int pp_prefix_costs(int L, int D, const int64_t *fwd_us, const int64_t *bwd_us,
  * whenever (number of distinct link rows)^(S-1) <= 2^20; the four uint32 at
  * byte PP_WS_SHARE then hold: 1 (0 if every candidate was computed on its
  * own), the number of distinct link rows, that power, and the number of
- * candidates computed.
+ * candidates computed.  Where that power is too large the candidates are
+ * instead taken in the order of their first k devices (D^k <= 2^20), so that
+ * consecutive ones share the first k - 1 rows: the uint32 at byte
+ * PP_WS_SHARE + 24 is then 1 and the one after it k.
  */
 #define PP_WS_WORK 1024
 #define PP_WS_WORK_STRIDE 128

@@ -321,10 +321,10 @@ def read_workspace_stats(workspace):
     import numpy as np
     rec = workspace[PP_WS_WORK:PP_WS_WORK + 64 * PP_WS_WORK_STRIDE].cpu().numpy().view(np.uint64)
     rec = rec.reshape(64, PP_WS_WORK_STRIDE // 8)
-    sh = workspace[PP_WS_SHARE:PP_WS_SHARE + 16].cpu().numpy().view(np.uint32)
+    sh = workspace[PP_WS_SHARE:PP_WS_SHARE + 32].cpu().numpy().view(np.uint32)
     return dict(pairs_executed=int(rec[:, 0].sum()), rows_executed=int(rec[:, 1].sum()),
                 share_active=int(sh[0]), share_classes=int(sh[1]), share_keys=int(sh[2]),
-                share_computed=int(sh[3]))
+                share_computed=int(sh[3]), share_sorted=int(sh[6]), share_sort_devices=int(sh[7]))
 
 
 def read_result(out, S=None, index=0):

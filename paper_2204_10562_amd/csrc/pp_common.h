@@ -38,7 +38,10 @@ struct pp_ws_header {
     // keys (first link most significant); the share_nbad candidates with a bad ordering follow,
     // stored from the end of the array backwards (pp_share_at)
     unsigned share_nsorted, share_nbad;
-    unsigned pad0[58];
+    // share_sorted != 0 (only when share_active == 0): the list holds all N candidates ordered
+    // by their first share_kdev devices, so that neighbours share the first share_kdev - 1 rows
+    unsigned share_sorted, share_kdev;
+    unsigned pad0[56];
     // byte 1024: work the partition DP actually did in this call, in 64 records of 128 bytes
     // (atomics that hit one cache line are served one after another, so every record has a
     // line of its own): (cell, split) pairs evaluated (rows shared between candidates are
@@ -63,7 +66,7 @@ struct pp_ws_layout {
     size_t hdr, p32, x32, xkt, xct, bfl, ord, arg, bounds, C, T, part, total;
     // candidates that share a DP (0 = not carved: see pp_share_possible)
     size_t sh_hash, sh_rep, sh_table, sh_keys, sh_reps, sh_cnt, sh_rows;
-    int sh_row_waves;  // waves that have a slice of sh_rows (saved DP rows, S rows of L + 132 keys)
+    long long sh_row_slots;  // DP rows (of pp_share_row_stride(L) keys) the area sh_rows holds
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
 };
@@ -114,7 +117,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.T = off;      off += pp_align256((size_t)N * 8);
     w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16 * PP_MAX_M_LIST);
     w.sh_hash = w.sh_rep = w.sh_table = w.sh_keys = w.sh_reps = w.sh_cnt = w.sh_rows = 0;
-    w.sh_row_waves = 0;
+    w.sh_row_slots = 0;
     if (pp_share_possible(L, D, N)) {
         w.sh_hash = off;  off += pp_align256((size_t)D * D * 8);
         w.sh_rep = off;   off += pp_align256((size_t)D * D * 4);
@@ -122,13 +125,14 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
         w.sh_keys = off;  off += pp_align256((size_t)N * 4);
         w.sh_reps = off;  off += pp_align256((size_t)N * 4);
         w.sh_cnt = off;   off += pp_align256((size_t)(PP_SHARE_TABLE / 256) * 4);
-        // DP rows a wave keeps for the next representative of its chunk: at most 64 MiB
-        const size_t per_wave = (size_t)S * pp_share_row_stride(L) * 4;
-        size_t nw = PP_SHARE_ROW_BYTES / per_wave;
-        if (nw > PP_SHARE_ROW_WAVES) nw = PP_SHARE_ROW_WAVES;
-        if (nw > (size_t)w.slots) nw = (size_t)w.slots;
-        w.sh_row_waves = (int)nw;
-        w.sh_rows = off;  off += pp_align256(nw * per_wave);
+        // DP rows the waves keep for the next candidate of their runs: S - 1 rows each for up
+        // to PP_SHARE_ROW_WAVES waves, at most 64 MiB (fewer rows per wave: more waves)
+        const size_t row = (size_t)pp_share_row_stride(L) * 4;
+        size_t nr = (size_t)PP_SHARE_ROW_WAVES * (S > 1 ? S - 1 : 1);
+        if (nr > PP_SHARE_ROW_BYTES / row) nr = PP_SHARE_ROW_BYTES / row;
+        if (nr > (size_t)w.slots * (S > 1 ? S - 1 : 1)) nr = (size_t)w.slots * (S > 1 ? S - 1 : 1);
+        w.sh_row_slots = (long long)nr;
+        w.sh_rows = off;  off += pp_align256(nr * row);
     }
     w.total = off;
     return w;

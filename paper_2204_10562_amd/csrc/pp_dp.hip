@@ -387,7 +387,7 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     list.reps = (const int *)(base + lay.sh_reps);
     list.keys = (const int *)(base + lay.sh_keys);
     list.rows = (int *)(base + lay.sh_rows);
-    list.row_waves = lay.sh_row_waves;
+    list.row_slots = lay.sh_row_slots;
     rc = pp_launch_dp_big(a, (int)waves, cus, &list, st);
     if (rc || keep_list) return rc;
     return pp_launch_share_scatter(N, stages ? S : 1, stages ? S * (S + 1) / 2 : S, 0, 1, C_out,

@@ -37,10 +37,10 @@ struct dp_big_args {
     // non-NULL: if the workspace header says so, walk this list of representatives (one per
     // group of candidates with the same DP, see pp_share.hip) instead of all candidates: every
     // wave a run of neighbours, which share their first links and so their first rows (keys:
-    // the key of every candidate; rows: row_waves slices of S saved rows of Lp + 4 keys)
+    // the key of every candidate; rows: room for row_slots saved rows of Lp + 4 keys)
     const int *reps, *keys;
     int *rows;
-    int row_waves;
+    long long row_slots;  // rows of Lp + 4 keys the area `rows` holds
     dp_args g;
 };
 
@@ -204,31 +204,44 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     unsigned long long pairs = 0, nrows = 0;
     const int tri = S * (S + 1) / 2;
 
-    // Which candidates this wave takes: every waves-th one, or, where candidates share their
-    // DP, a run of consecutive entries of the sorted list of representatives.
+    // Which candidates this wave takes: every waves-th one, or a run of consecutive entries of a
+    // list the preparation left (pp_share.hip): the sorted representatives where candidates
+    // share their DP, or all candidates sorted by their first devices.  Neighbours in a list
+    // share their first rows; the wave keeps the rows that can be shared (all of them, or the
+    // first kdev - 1) in its slice of the workspace.
     const bool listed = b.reps != NULL && a.hdr->share_active != 0;
+    const bool sorted = b.reps != NULL && !listed && a.hdr->share_sorted != 0;
     long long r_begin = wave, r_end = a.N, r_step = b.waves, nsorted = 0;
     unsigned pw = 1;  // lane n = 1..S-1: (classes)^(S-1-n), the weight of the key's digit n
-    if (listed) {
-        const long long total = a.hdr->share_nreps;
-        nsorted = a.hdr->share_nsorted;
-        const long long nw = b.waves < b.row_waves ? b.waves : b.row_waves;
+    int keep_rows = 0;  // rows 1..keep_rows are saved
+    if (listed || sorted) {
+        const long long total = listed ? (long long)a.hdr->share_nreps : a.N;
+        nsorted = listed ? (long long)a.hdr->share_nsorted : a.N;
+        keep_rows = listed ? S - 2 : (int)a.hdr->share_kdev - 1;
+        keep_rows = keep_rows < S - 2 ? keep_rows : S - 2;
+        keep_rows = keep_rows > 0 ? keep_rows : 0;
+        long long nw = b.row_slots / (keep_rows > 0 ? keep_rows : 1);  // waves whose rows fit the area
+        nw = nw < b.waves ? nw : b.waves;
+        nw = nw > 1 ? nw : 1;
         long long chunk = (total + nw - 1) / nw;
-        if (chunk < PP_SHARE_MIN_CHUNK) chunk = PP_SHARE_MIN_CHUNK;
+        if (listed && chunk < PP_SHARE_MIN_CHUNK) chunk = PP_SHARE_MIN_CHUNK;
         r_begin = wave * chunk;
         r_end = r_begin + chunk < total ? r_begin + chunk : total;
         r_step = 1;
-        const unsigned nc = a.hdr->share_nc;
-        for (int n = lane + 1; n < S; ++n) pw *= nc;
+        if (listed) {
+            const unsigned nc = a.hdr->share_nc;
+            for (int n = lane + 1; n < S; ++n) pw *= nc;
+        }
     }
-    int *save = b.rows + (size_t)(listed ? wave : 0) * S * RS;
-    int prev_key = -1;
+    // (row n >= 1 of this wave's slice at save + (n - 1) RS)
+    int *save = b.rows + (size_t)((listed || sorted) ? wave : 0) * keep_rows * RS;
+    int prev_key = -1, prev_o = -1;
     int v_tops = 0;  // lane n keeps W[n][L] (with its split index) for the stage-count search
     int *cur = bufA, *nxt = bufB;
     for (long long r = r_begin; r < r_end; r += r_step) {
-        const long long c = listed ? pp_share_at(a.hdr, b.reps, a.N, r) : r;
-        // rows 1..p of the previous representative are this one's too: its key has the same
-        // first p digits (equal links give equal rows)
+        const long long c = (listed || sorted) ? pp_share_at(a.hdr, b.reps, a.N, r) : r;
+        // rows 1..p of the previous candidate are this one's too: its key has the same first p
+        // digits (equal links give equal rows), or its first p + 1 devices are the same
         int p = 0, key = -1;
         if (listed && r < nsorted) {
             key = b.keys[c];
@@ -261,7 +274,16 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
                 if (lane < S) a.bounds_out[c * S + lane] = 0;
             }
             prev_key = -1;  // (the next candidate starts from row 0)
+            prev_o = -1;
             continue;
+        }
+        if (sorted) {
+            // (prev_o: the previous candidate's device in this lane, -1 if there is none)
+            const unsigned long long m = __ballot(lane < S && v_o != prev_o);
+            p = m ? __builtin_ctzll(m) - 1 : S - 2;
+            p = p < keep_rows ? p : keep_rows;
+            p = p > 0 ? p : 0;
+            prev_o = v_o;
         }
         const int v_link = __shfl_up(v_o, 1) * D + v_o;
 
@@ -276,7 +298,7 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
             // row p as this wave left it (stored by other lanes of the wave: wait for the
             // stores, then read past the L1 cache)
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-            const int *from = save + (size_t)p * RS;
+            const int *from = save + (size_t)(p - 1) * RS;
             for (int l = lane; l <= Lp; l += 64)
                 cur[l] = __hip_atomic_load(from + l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             big_lds_sync();
@@ -305,9 +327,9 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
                 int *t = cur; cur = nxt; nxt = t;
                 const int top_n = cur[L];
                 if (lane == n) v_tops = top_n;
-                if (listed) {
-                    // kept for the next representative of the run
-                    int *to = save + (size_t)n * RS;
+                if (n <= keep_rows) {
+                    // kept for the next candidate of the run
+                    int *to = save + (size_t)(n - 1) * RS;
                     for (int l = lane; l <= Lp; l += 64) to[l] = cur[l];
                 }
             } else {
@@ -380,7 +402,7 @@ int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_li
     b.reps = list ? list->reps : NULL;
     b.keys = list ? list->keys : NULL;
     b.rows = list ? list->rows : NULL;
-    b.row_waves = list ? list->row_waves : 0;
+    b.row_slots = list ? list->row_slots : 0;
     b.NI = (g.L + 127) / 128;
     const int Lp = 128 * b.NI, RS = Lp + 4;
     b.arg_stride = (size_t)g.S * Lp;

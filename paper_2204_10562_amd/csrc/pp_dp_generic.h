@@ -43,7 +43,7 @@ struct dp_args {
 struct pp_share_list {
     const int *reps, *keys;
     int *rows;
-    int row_waves;
+    long long row_slots;  // rows of (128 ceil(L / 128) + 4) keys that fit the area
 };
 int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_list *list,
                      hipStream_t st);

@@ -20,7 +20,14 @@
 // The DP kernel walks the list - neighbours in it share their first links and with them the
 // first rows of the table - and k_share_scatter hands every representative's results to the
 // candidates of its key.  Candidates with a bad ordering are representatives of themselves
-// (kept after the sorted ones), so the DP kernel reports them as it always does.  All decisions are taken on the device; when
+// (kept after the sorted ones), so the DP kernel reports them as it always does.
+//
+// When the keys do not fit the table (every link its own class) there is still something to
+// share: row n depends on the first n + 1 devices only, and a long sampled list holds each
+// choice of the first few devices many times.  The same kernels then sort the candidates by
+// their first k devices (D^k <= table entries; a counting sort: histogram in k_share_keys,
+// bucket offsets in k_share_count / k_share_reps, placement in k_share_place), the list holds
+// all N candidates, and the DP kernel reuses the first k - 1 rows between neighbours.  All decisions are taken on the device; when
 // the keys do not fit the table the kernels return at once and the DP runs over all candidates.
 #include "pp_common.h"
 
@@ -73,6 +80,8 @@ __global__ __launch_bounds__(256) void k_share_hash(share_args a) {
         a.hdr->share_nreps = 0;
         a.hdr->share_nsorted = 0;
         a.hdr->share_nbad = 0;
+        a.hdr->share_sorted = 0;
+        a.hdr->share_kdev = 0;
     }
     const int i = blockIdx.x * 4 + (tid >> 6);
     if (i >= nl) return;
@@ -155,13 +164,38 @@ __global__ __launch_bounds__(256) void k_share_keys(share_args a) {
         tsize = t <= PP_SHARE_TABLE ? (unsigned)t : 0;
     }
     if (nc == 0) tsize = S > 1 ? 0 : 1;
+    // otherwise: buckets of the first kdev devices (at least two, or there is no row to share)
+    int kdev = 0;
+    unsigned nbuck = 1;
+    if (!tsize) {
+        while (kdev < S && (unsigned long long)nbuck * (unsigned)D <= PP_SHARE_TABLE) { nbuck *= (unsigned)D; ++kdev; }
+        if (kdev < 2 || S < 3) kdev = 0;
+    }
     if (blockIdx.x == 0 && tid == 0) {
         a.hdr->share_nc = (unsigned)nc;
-        a.hdr->share_tsize = tsize;
+        a.hdr->share_tsize = tsize ? tsize : (kdev ? nbuck : 0);
         a.hdr->share_active = tsize != 0;
+        a.hdr->share_sorted = kdev != 0;
+        a.hdr->share_kdev = (unsigned)kdev;
     }
-    if (!tsize) return;
     const bool vec = (S & 3) == 0 && ((uintptr_t)a.ord & 15) == 0;
+    if (!tsize) {
+        if (!kdev) return;
+        // histogram of the buckets (the table starts at SHARE_NONE everywhere: counts are taken
+        // relative to that, in unsigned arithmetic)
+        for (long long c = (long long)blockIdx.x * 256 + tid; c < a.N; c += (long long)gridDim.x * 256) {
+            const int *row = a.ord + c * S;
+            unsigned key = 0;
+            for (int n = 0; n < kdev; ++n) {
+                int d = row[n];
+                d = (d < 0 || d >= D) ? 0 : d;  // (a bad row is found by the DP kernel; any bucket will do)
+                key = key * (unsigned)D + (unsigned)d;
+            }
+            a.keys[c] = (int)key;
+            atomicAdd((unsigned *)&a.table[key], 1u);
+        }
+        return;
+    }
     for (long long c = (long long)blockIdx.x * 256 + tid; c < a.N; c += (long long)gridDim.x * 256) {
         const int *row = a.ord + c * S;
         unsigned long long used = 0;
@@ -204,9 +238,16 @@ __global__ __launch_bounds__(256) void k_share_count(share_args a) {
     __shared__ int sh[4];
     const unsigned tsize = a.hdr->share_tsize;
     const unsigned key = blockIdx.x * 256u + threadIdx.x;
-    const bool has = key < tsize && a.table[key] != SHARE_NONE;
-    const unsigned long long mask = __ballot(has);
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = __builtin_popcountll(mask);
+    int n;
+    if (a.hdr->share_sorted) {
+        // candidates in the bucket
+        n = key < tsize ? (int)((unsigned)a.table[key] - (unsigned)SHARE_NONE) : 0;
+        for (int off = 32; off; off >>= 1) n += __shfl_xor(n, off);
+    } else {
+        const bool has = key < tsize && a.table[key] != SHARE_NONE;
+        n = __builtin_popcountll(__ballot(has));
+    }
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = n;
     __syncthreads();
     if (threadIdx.x == 0) a.cnt[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
 }
@@ -238,6 +279,22 @@ __global__ __launch_bounds__(256) void k_share_reps(share_args a) {
     }
     const int base = blockIdx.x ? before : 0;
     const unsigned key = blockIdx.x * 256u + tid;
+    if (a.hdr->share_sorted) {
+        // every bucket's first position in the list (k_share_place hands the positions out)
+        if (blockIdx.x == 0 && tid == 0) a.hdr->share_nsorted = a.hdr->share_nreps = (unsigned)a.N;
+        const int n = key < tsize ? (int)((unsigned)a.table[key] - (unsigned)SHARE_NONE) : 0;
+        int incl = n;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            incl += lane >= off ? o : 0;
+        }
+        if (lane == 63) shw[wib] = incl;
+        __syncthreads();
+        int at = base + incl - n;
+        for (int w = 0; w < wib; ++w) at += shw[w];
+        if (key < tsize) a.table[key] = at;
+        return;
+    }
     const int c = key < tsize ? a.table[key] : SHARE_NONE;
     const bool has = c != SHARE_NONE;
     const unsigned long long mask = __ballot(has);
@@ -246,6 +303,13 @@ __global__ __launch_bounds__(256) void k_share_reps(share_args a) {
     int at = base + __builtin_popcountll(mask & ((1ull << lane) - 1));
     for (int w = 0; w < wib; ++w) at += shw[w];
     if (has) a.reps[at] = c;
+}
+
+// Counting sort, last step: every candidate takes the next free position of its bucket.
+__global__ __launch_bounds__(256) void k_share_place(share_args a) {
+    if (!a.hdr->share_sorted) return;
+    for (long long c = (long long)blockIdx.x * 256 + threadIdx.x; c < a.N; c += (long long)gridDim.x * 256)
+        a.reps[atomicAdd(&a.table[a.keys[c]], 1)] = (int)c;
 }
 
 // Every candidate that is not the representative of its key takes the representative's
@@ -306,6 +370,7 @@ int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, c
     hipLaunchKernelGGL(k_share_keys, dim3((unsigned)share_grid(N)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_count, dim3(PP_SHARE_TABLE / 256), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_reps, dim3(PP_SHARE_TABLE / 256), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_share_place, dim3((unsigned)share_grid(N)), dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 

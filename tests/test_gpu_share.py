@@ -78,8 +78,14 @@ def check_shared(ppo, g, w, tables, expect_active=True):
         if len(set(keys)) <= 8:  # one run of one wave
             assert stats["rows_executed"] == prefixes
     else:
-        assert stats["share_active"] == 0
-        assert stats["rows_executed"] == w.N * (w.S - 1)
+        # every candidate is computed, in the order of its first k devices; those with the same
+        # first n + 1 devices can share rows 1..n (n < k)
+        assert stats["share_active"] == 0 and stats["share_sorted"] == 1
+        k = stats["share_sort_devices"]
+        assert k >= 2 and w.D ** k <= 2 ** 20 and (k == w.S or w.D ** (k + 1) > 2 ** 20)
+        o = [tuple(int(x) for x in row) for row in w.orderings]
+        least = sum(len({r[:n + 1] for r in o}) for n in range(1, min(k, w.S - 1))) + w.N * (w.S - 1 - (min(k, w.S - 1) - 1))
+        assert least <= stats["rows_executed"] <= w.N * (w.S - 1)
     return stats
 
 
@@ -128,14 +134,39 @@ def test_shared_dp_equal_rows_from_different_bandwidths(ppo, G):
     assert stats["share_classes"] == 1 and stats["share_computed"] == 1
 
 
-def test_shared_dp_keys_beyond_the_table(ppo, G):
-    # random bandwidths: 56 classes, 56^7 sequences: every candidate is computed on its own
-    w = workloads.random_small(4401, 133, 8, 8, 300, hi_time=60, hi_act=90000)
+@pytest.mark.parametrize("seed,L,D,S,N", [(4401, 133, 8, 8, 300), (4402, 150, 6, 6, 5000), (4403, 200, 40, 5, 900),
+                                          (4404, 140, 7, 7, 6000)])
+def test_shared_dp_keys_beyond_the_table(ppo, G, seed, L, D, S, N):
+    # random bandwidths: every link a class of its own and too many sequences for the table:
+    # every candidate is computed, sorted by its first devices so that neighbours share rows
+    w = workloads.random_small(seed, L, D, S, N, hi_time=60, hi_act=90000)
     tables = oracle_tables(ppo, w)
     g = G(w)
     g.set_tables(*tables)
-    say("shared dp, keys beyond the table")
-    check_shared(ppo, g, w, tables, expect_active=False)
+    say("shared dp, keys beyond the table", seed, L, D, S, N)
+    stats = check_shared(ppo, g, w, tables, expect_active=False)
+    if N > 4096:  # (more candidates than waves: runs of at least two)
+        assert stats["rows_executed"] < w.N * (w.S - 1)
+    # a list with bad rows and repeated rows, and the search over the stage counts
+    v = copy.copy(w)
+    v.orderings = w.orderings.copy()
+    v.orderings[N // 3] = v.orderings[N // 3 + 1]
+    v.orderings[7, 1] = v.orderings[7, 0]
+    v.orderings[N - 1, S - 1] = -1
+    g = G(v)
+    g.set_tables(*tables)
+    st, C, b = g.dp()
+    rc, C0, b0 = ppo.partition_dp(v.L, v.D, v.S, v.N, *tables, v.orderings)
+    assert st == rc == ppo.FAULT_ORDERING
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(b, b0)
+    g = G(w)
+    g.set_tables(*tables)
+    st, C, b = g.dp_stages()
+    rc, res0, T0, C0, b0 = ppo.best_plan_stages(w.L, w.D, w.S, w.N, 5, *tables, w.orderings)
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(b, b0)
 
 
 def test_shared_dp_bad_orderings(ppo, G):
