@@ -126,3 +126,19 @@ def test_argument_and_ordering_faults(ppo):
     assert ppo.partition_dp(w.L, 4, 4, 24, PF, PB, XF, XB, bad)[0] == ppo.FAULT_ORDERING
     bad = o.copy(); bad[5, 2] = 4
     assert ppo.partition_dp(w.L, 4, 4, 24, PF, PB, XF, XB, bad)[0] == ppo.FAULT_ORDERING
+
+
+def test_bottleneck_is_not_monotone_in_the_number_of_layers(ppo):
+    # With transfer times that depend on the cut position, more layers can mean a smaller
+    # bottleneck: three layers cut after the second (cheap link time there) beat two layers,
+    # whose only cut is the dear one after the first.  Any pruning of the recursion of Sec. IV-B
+    # that assumes W(l, xi) grows with l is therefore wrong in general (it does grow when no
+    # link's time depends on the position).
+    o = np.array([[0, 1]], np.int32)
+    L, PF, PB, XF, XB = _tables_from_p_x([1, 1], [100])
+    rc, C2, b2 = ppo.partition_dp(L, 2, 2, 1, PF, PB, XF, XB, o)
+    assert rc == 0 and C2[0] == 100 and b2[0].tolist() == [1, 2]
+    L, PF, PB, XF, XB = _tables_from_p_x([1, 1, 1], [100, 0])
+    rc, C3, b3 = ppo.partition_dp(L, 2, 2, 1, PF, PB, XF, XB, o)
+    assert rc == 0 and C3[0] == 2 and b3[0].tolist() == [2, 3]
+    assert C3[0] < C2[0]
