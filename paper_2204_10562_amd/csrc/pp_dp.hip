@@ -146,10 +146,31 @@ __device__ void unrank_rows(const pack_args &a, long long first, long long strid
 // One workgroup; sh holds P and two rows.  a.bfl: B [S][L+1] int64, then A [S][L+1] int32.
 __device__ void flat_table(const pack_args &a, long long *sh) {
     const int L = a.L, S = a.S, tid = threadIdx.x;
+    // The tables are read only when no link's channel time depends on the cut position.  If
+    // some link's times at the first two cut positions already differ, that is not so (the
+    // pack blocks will find the same), and the work below can be left out.  Only for long
+    // models: for L <= 128 the table is cheap and this launch is on the path of a step of a few
+    // tens of microseconds, where the test's own barriers cost more than it can save.
+    // (this thread's first entry of P is requested here, so that it travels with the loads of the test)
+    const long long p_first = tid <= L ? a.PF[tid] + a.PB[tid] : 0;
+    if (L > PP_TILE_MAX_L) {
+        __shared__ int s_differs;
+        if (tid == 0) s_differs = 0;
+        __syncthreads();
+        bool differs = false;
+        for (int link = tid; link < a.D * a.D; link += 256) {
+            if (link / a.D == link % a.D) continue;
+            const size_t at = (size_t)link * L;
+            differs |= a.XF[at] + a.XB[at] != a.XF[at + 1] + a.XB[at + 1];
+        }
+        if (differs) s_differs = 1;
+        __syncthreads();
+        if (s_differs) return;
+    }
     long long *P = sh, *cur = sh + (L + 1), *nxt = cur + (L + 1);
     int *A = (int *)(a.bfl + (size_t)S * (L + 1));
     for (int l = tid; l <= L; l += 256) {
-        const long long p = a.PF[l] + a.PB[l];
+        const long long p = l == tid ? p_first : a.PF[l] + a.PB[l];
         P[l] = p;
         cur[l] = p;
         a.bfl[l] = p;
