@@ -349,3 +349,21 @@ def test_shared_schedule_other_dp_paths(ppo, G, kind):
     assert stats["share_active"] == 1 and stats["share_computed"] < w.N
     if kind == "equal_activations":
         assert stats["rows_executed"] == 0
+
+
+def test_more_devices_than_the_class_table_holds(ppo, G):
+    # more than 64 devices: no grouping and no sorting, every candidate on its own as ever
+    w = workloads.random_small(5001, 140, 66, 3, 60, hi_time=60, hi_act=90000)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("dp, 66 devices")
+    st, C, b = g.dp()
+    rc, C0, b0 = ppo.partition_dp(w.L, w.D, w.S, w.N, *tables, w.orderings)
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(b, b0)
+    st, res, T, C = g.best(4)
+    rc, r0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, 4, *tables, w.orderings)
+    assert st == 0 and rc == 0 and res == r0
+    np.testing.assert_array_equal(T, T0)
