@@ -367,3 +367,42 @@ def test_more_devices_than_the_class_table_holds(ppo, G):
     rc, r0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, 4, *tables, w.orderings)
     assert st == 0 and rc == 0 and res == r0
     np.testing.assert_array_equal(T, T0)
+
+
+@pytest.mark.parametrize("two_bandwidths", [True, False])
+def test_library_list_of_all_orderings_with_many_layers(ppo, G, two_bandwidths):
+    # orderings = NULL (all D! in lexicographic order, generated on the device) with more than
+    # 128 layers: grouped by link classes (two bandwidths) or sorted by devices (random ones)
+    import math
+    w = workloads.random_small(5101, 150, 6, 6, 1, hi_time=60, hi_act=50000)
+    if two_bandwidths:
+        w = islands(w, 3, 180, 25)
+    w.orderings = None
+    w.N = math.factorial(6)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("all 6! orderings, 150 layers, two bandwidths:", two_bandwidths)
+    explicit = workloads.all_orderings(6)
+    st, C, b = g.dp()
+    rc, C0, b0 = ppo.partition_dp(w.L, w.D, w.S, w.N, *tables, explicit)
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(b, b0)
+    from paper_2204_10562_amd import binding as pp
+    stats = pp.read_workspace_stats(g.ws)
+    assert stats["share_active"] == int(two_bandwidths) and stats["share_sorted"] == int(not two_bandwidths)
+    for want_all in (True, False):
+        st, res, T, C1 = g.best_multi((2, 30), want_all=want_all)
+        assert st == 0
+        for q, M in enumerate((2, 30)):
+            rc, r0, T0, C0 = ppo.best_plan(w.L, w.D, w.S, w.N, M, *tables, explicit)
+            assert rc == 0 and res[q] == r0
+            if want_all:
+                np.testing.assert_array_equal(T[q], T0)
+        st, res, T, C2 = g.best_stages((9,), want_all=want_all)
+        rc, r0, T0, C0, _ = ppo.best_plan_stages(w.L, w.D, w.S, w.N, 9, *tables, explicit)
+        assert st == 0 and rc == 0 and res[0] == r0
+        if want_all:
+            np.testing.assert_array_equal(T[0], T0)
+            np.testing.assert_array_equal(C2, C0)
