@@ -61,6 +61,10 @@ struct mk_args {
     // i = c*search + xi-1; the record of the winner is decoded accordingly
     int search;
     int variant;  // k_makespan_variant only: PP_SCHED_*
+    // k_makespan_mid / k_makespan_lds launched together without a header (17..32 stages, no
+    // workspace): nonzero = every block of 64 candidates decides for itself which of the two
+    // kernels schedules it (see mid_takes_block)
+    int by_block;
     // workspace header with the largest time of the tables (NULL if there is none): lets every
     // wave of a launch take the same decision between 32-bit and 64-bit finish times
     const pp_ws_header *hdr;
@@ -923,6 +927,16 @@ __device__ __forceinline__ bool launch_is_narrow(const mk_args &a) {
     return vmax <= 0x7fffffffull / (unsigned long long)(mmax + 4 * a.S - 4);
 }
 
+// Without a header the same question per block of 64 candidates, from the largest per-resource
+// time of each of them (`worst` as gather_durations reports it; ok = this lane's candidates fit,
+// dead and faulty ones count as fitting): both kernels evaluate this on the same values, so
+// exactly one of them schedules the block.
+__device__ __forceinline__ bool fits_narrow(const mk_args &a, long long worst) {
+    int mmax = 1;
+    for (int q = 0; q < a.nM; ++q) mmax = a.Ms[q] > mmax ? a.Ms[q] : mmax;
+    return worst <= (long long)(0x7fffffffull / (unsigned long long)(mmax + 4 * a.S - 4));
+}
+
 // 16 < S <= 32 with 32-bit times: the 4S-3 finish times of a lane in registers (blocks
 // unrolled, each update selected by a per-lane test of the sweep's window), the durations in
 // the lane's LDS column.  Runs only if the whole launch is narrow; k_makespan_lds, launched
@@ -931,7 +945,7 @@ template <int S>
 __global__ __launch_bounds__(64) void k_makespan_mid(mk_args a) {
     constexpr int R = 2 * S - 1, J = 2 * R - 1;
     extern __shared__ int smi[];
-    if (!launch_is_narrow(a)) return;
+    if (!a.by_block && !launch_is_narrow(a)) return;
     const int lane = threadIdx.x;
     int *dur = smi + lane;  // [J][64]
     const long long c = (long long)blockIdx.x * 64 + lane;
@@ -939,6 +953,8 @@ __global__ __launch_bounds__(64) void k_makespan_mid(mk_args a) {
     long long worst;
     const int fault = gather_durations<S>(a, c, live, worst,
                                           [&](int j, long long d) { dur[(j - 1) * 64] = (int)d; });
+    // (by block: this kernel takes the block iff all of its 64 candidates fit 32 bits)
+    if (a.by_block && !__all(!live || fault || fits_narrow(a, worst))) return;
     for (int q = 0; q < a.nM; ++q) {
         const int M = a.Ms[q];
         const int fq = (live && !fault) ? overflow_fault(worst, M, S) : fault;
@@ -977,7 +993,21 @@ __global__ __launch_bounds__(64) void k_makespan_lds(mk_args a) {
     extern __shared__ long long sm[];
     const int lane = threadIdx.x, W = blockDim.x;
     const int S = a.S;
-    if (S > 16 && S <= 32 && launch_is_narrow(a)) return;  // k_makespan_mid does this launch
+    if (S > 16 && S <= 32 && !a.by_block && launch_is_narrow(a)) return;  // k_makespan_mid does this launch
+    if (a.by_block) {
+        // k_makespan_mid takes the block of 64 candidates this workgroup's W lie in iff all 64
+        // fit 32 bits: the same test here, every lane looking at 64 / W of them
+        const long long c0 = ((long long)blockIdx.x * W / 64) * 64;
+        bool ok = true;
+        for (int i = lane; i < 64; i += W) {
+            const long long cc = c0 + i;
+            const bool lv = cc < a.N;
+            long long w2;
+            const int f2 = gather_durations<0>(a, cc, lv, w2, [](int, long long) {});
+            ok = ok && (!lv || f2 || fits_narrow(a, w2));
+        }
+        if (__all(ok)) return;
+    }
     const int R = 2 * S - 1, J = 2 * R - 1;
     // rows 0..J-1: duration of block j = row+1; rows J..2J-1: its latest finish time
     long long *dur = sm + lane;
@@ -1123,6 +1153,21 @@ static int launch_makespan(const mk_args &a, hipStream_t st) {
 #undef CASE
     }
     const int W = lds_lanes(a.S);
+    mk_args b = a;
+    b.by_block = 0;
+    if (!a.hdr && !a.part && a.S <= 32) {
+        // no workspace header to tell whether the times fit 32 bits: both kernels are enqueued
+        // and every block of 64 candidates goes to one of them (W divides 64)
+        b.by_block = 1;
+        int rc = PP_ERR_INVALID_ARG;
+        switch (a.S) {
+#define CASE(n) case n: rc = launch_mid<n>(b, st); break;
+            CASE(17) CASE(18) CASE(19) CASE(20) CASE(21) CASE(22) CASE(23) CASE(24)
+            CASE(25) CASE(26) CASE(27) CASE(28) CASE(29) CASE(30) CASE(31) CASE(32)
+#undef CASE
+        }
+        if (rc) return rc;
+    }
     if (a.hdr && a.S <= 32 && (W == 64 || !a.part)) {
         // both kernels are enqueued; which one works depends on the data (see launch_is_narrow)
         int rc = PP_ERR_INVALID_ARG;
@@ -1136,7 +1181,7 @@ static int launch_makespan(const mk_args &a, hipStream_t st) {
     }
     const size_t lds = (size_t)2 * (4 * a.S - 3) * W * 8;
     unsigned grid = (unsigned)((a.N + W - 1) / W);
-    hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, a);
+    hipLaunchKernelGGL(k_makespan_lds, dim3(grid), dim3(W), lds, st, b);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 

@@ -794,3 +794,29 @@ def test_whole_path_random_shapes(ppo, G, seed):
     check_dp(ppo, g, w)
     Ms = (int(rng.integers(1, 5)), int(rng.integers(5, 80)))
     check_best_multi(ppo, g, w, Ms, tables)
+
+
+@pytest.mark.parametrize("seed,L,D,S,N,hi", [(1501, 60, 20, 20, 300, 2 * 10 ** 6), (1502, 90, 32, 32, 200, 10 ** 6),
+                                             (1503, 40, 17, 17, 130, 4 * 10 ** 6), (1504, 50, 24, 24, 64, 50)])
+def test_makespan_17_to_32_stages_without_workspace(ppo, G, seed, L, D, S, N, hi):
+    # pp_schedule_makespan has no workspace header that says whether the times fit 32 bits: every
+    # block of 64 candidates is scheduled by the register kernel if all of its plans fit and by
+    # the 64-bit kernel otherwise.  Layer times chosen so that a launch holds both kinds.
+    w = workloads.random_small(seed, L, D, S, N, hi_time=hi, hi_act=hi * 40)
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bounds = random_bounds(rng, N, S, L)
+    for Ms in ((50,), (3, 400)):
+        say("makespan 17..32 stages, no workspace", seed, L, D, S, N, Ms)
+        st, T = g.makespan_multi(Ms, bounds)
+        assert st == 0
+        fits = 0
+        for q, M in enumerate(Ms):
+            rc, T0 = ppo.schedule_makespan(L, D, S, N, M, *tables, w.orderings, bounds)
+            assert rc == 0
+            np.testing.assert_array_equal(T[q], T0)
+            fits += int((T0 < 2 ** 31).sum())
+        if hi > 50:
+            assert 0 < fits < N * len(Ms)  # some schedules fit 32 bits and some do not
