@@ -964,22 +964,35 @@ __global__ __launch_bounds__(64) void k_makespan_mid(mk_args a) {
         const int sweeps = M + 2 * R - 2;
         const unsigned width = (unsigned)(M - 1);
         for (int t = 1; t <= sweeps; ++t) {
-            int jlo = t - M + 1;
+            const int jlo_s = t - M + 1;  // the sweep's window is blocks jlo_s .. t
+            int jlo = jlo_s;
             asm volatile("" : "+v"(jlo));
             const int finR_prev = fin[R];
+            // groups of eight blocks; one that lies wholly outside the window is jumped over
+            // (while the pipeline fills and drains that is about half of them)
 #pragma unroll
-            for (int j = R; j >= 1; --j) {
-                int idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
-                int ready = j > 1 ? fin[j - 1] : 0;
-                int nv = (idle > ready ? idle : ready) + dur[(j - 1) * 64];
-                fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
+            for (int jb = R; jb >= 1; jb -= 8) {
+                const int ja = jb - 7 > 1 ? jb - 7 : 1;
+                if (jb < jlo_s || ja > t) continue;
+#pragma unroll
+                for (int j = jb; j >= ja; --j) {
+                    int idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+                    int ready = j > 1 ? fin[j - 1] : 0;
+                    int nv = (idle > ready ? idle : ready) + dur[(j - 1) * 64];
+                    fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
+                }
             }
 #pragma unroll
-            for (int j = J; j >= R + 1; --j) {
-                int idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
-                int ready = j == R + 1 ? finR_prev : fin[j - 1];
-                int nv = (idle > ready ? idle : ready) + dur[(j - 1) * 64];
-                fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
+            for (int jb = J; jb >= R + 1; jb -= 8) {
+                const int ja = jb - 7 > R + 1 ? jb - 7 : R + 1;
+                if (jb < jlo_s || ja > t) continue;
+#pragma unroll
+                for (int j = jb; j >= ja; --j) {
+                    int idle = fin[j] > fin[2 * R - j] ? fin[j] : fin[2 * R - j];
+                    int ready = j == R + 1 ? finR_prev : fin[j - 1];
+                    int nv = (idle > ready ? idle : ready) + dur[(j - 1) * 64];
+                    fin[j] = (unsigned)(j - jlo) <= width ? nv : fin[j];
+                }
             }
         }
         emit(a, q, c, live, fq, (long long)fin[J], blockIdx.x, gridDim.x, a.t_off);
