@@ -406,3 +406,48 @@ def test_library_list_of_all_orderings_with_many_layers(ppo, G, two_bandwidths):
         if want_all:
             np.testing.assert_array_equal(T[0], T0)
             np.testing.assert_array_equal(C2, C0)
+
+
+@pytest.mark.parametrize("seed", range(5200, 5240))
+def test_shared_random_shapes(ppo, G, seed):
+    # shapes drawn at random above 128 layers: islands of random size and two to four bandwidth
+    # levels (grouped), or random bandwidths (sorted); any S up to D; plans, schedules for two
+    # microbatch counts, winners, and every stage count
+    rng = np.random.Generator(np.random.PCG64(seed))
+    L = int(rng.integers(129, 400))
+    D = int(rng.integers(2, 13))
+    S = int(rng.integers(1, D + 1))
+    N = int(rng.integers(1, 6000)) if seed % 4 == 0 else int(rng.integers(1, 400))
+    w = workloads.random_small(seed, L, D, S, N, zero_frac=0.1 if seed % 2 else 0.0,
+                               hi_time=int(rng.integers(2, 200)), hi_act=int(rng.integers(1, 60000)))
+    if seed % 3:
+        levels = rng.integers(5, 300, size=int(rng.integers(2, 5)))
+        size = int(rng.integers(1, D + 1))
+        bw = np.empty((D, D), np.int64)
+        for u in range(D):
+            for v in range(D):
+                bw[u, v] = levels[0] if u // size == v // size else levels[1 + (u + v) % (len(levels) - 1)]
+        np.fill_diagonal(bw, 0)
+        w.bw = bw
+    tables = oracle_tables(ppo, w)
+    g = G(w)
+    g.set_tables(*tables)
+    say("shared random", seed, L, D, S, N)
+    Ms = (int(rng.integers(1, 9)), int(rng.integers(9, 200)))
+    st, res, T, C = g.best_multi(Ms)
+    assert st == 0
+    for q, M in enumerate(Ms):
+        rc, r0, T0, C0 = ppo.best_plan(L, D, S, N, M, *tables, w.orderings)
+        assert rc == 0 and res[q] == r0
+        np.testing.assert_array_equal(T[q], T0)
+        np.testing.assert_array_equal(C, C0)
+    st, C, b = g.dp()
+    rc, C0, b0 = ppo.partition_dp(L, D, S, N, *tables, w.orderings)
+    assert st == 0 and rc == 0
+    np.testing.assert_array_equal(C, C0)
+    np.testing.assert_array_equal(b, b0)
+    st, res, T, C = g.best_stages(Ms[:1])
+    rc, r0, T0, C0, b0 = ppo.best_plan_stages(L, D, S, N, Ms[0], *tables, w.orderings)
+    assert st == 0 and rc == 0 and res[0] == r0
+    np.testing.assert_array_equal(T[0], T0)
+    np.testing.assert_array_equal(C, C0)
