@@ -309,13 +309,27 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
             // Rewrite the previous row in place as g; on the way its split indices (the low
             // key bits) go to the backtrack table.
             unsigned short *arow = arg + (size_t)(n - 1) * Lp;
-            for (int k = lane; k < Lp; k += 64) {
-                const int w = cur[k];
-                if (n >= 2) arow[k] = (unsigned short)(w & kmask);
-                int xk = PP_INF32;
-                if (k >= 1 && k < L) xk = (xrow[k] << K) | k;
-                int wk = (w & ~kmask) | (xk & kmask);
-                cur[k] = bmax(wk, xk);
+            // (the link's times are requested eight steps at a time, ahead of the stores they
+            // could otherwise not be moved across: one trip per 512 splits instead of eight)
+            for (int k0 = lane; k0 < Lp; k0 += 512) {
+                int xv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = k0 + 64 * u;
+                    xv[u] = (k >= 1 && k < L) ? xrow[k] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = k0 + 64 * u;
+                    if (k < Lp) {
+                        const int w = cur[k];
+                        if (n >= 2) arow[k] = (unsigned short)(w & kmask);
+                        int xk = PP_INF32;
+                        if (k >= 1 && k < L) xk = (xv[u] << K) | k;
+                        int wk = (w & ~kmask) | (xk & kmask);
+                        cur[k] = bmax(wk, xk);
+                    }
+                }
             }
             big_lds_sync();
             if (n < S - 1) {
