@@ -238,13 +238,27 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     int prev_key = -1, prev_o = -1;
     int v_tops = 0;  // lane n keeps W[n][L] (with its split index) for the stage-count search
     int *cur = bufA, *nxt = bufB;
+    // A candidate's index, key and devices come from memory through a chain of loads (list
+    // entry, then key and ordering): they are fetched one candidate ahead.
+    auto fetch = [&](long long r, long long &c, int &key, int &v_o) {
+        c = 0; key = -1; v_o = 0;
+        if (r >= r_end) return;
+        c = (listed || sorted) ? pp_share_at(a.hdr, b.reps, a.N, r) : r;
+        if (listed && r < nsorted) key = b.keys[c];
+        v_o = lane < S ? a.ord[c * S + lane] : 0;
+    };
+    long long c_next;
+    int key_next, v_o_next;
+    fetch(r_begin, c_next, key_next, v_o_next);
     for (long long r = r_begin; r < r_end; r += r_step) {
-        const long long c = (listed || sorted) ? pp_share_at(a.hdr, b.reps, a.N, r) : r;
+        const long long c = c_next;
+        const int v_o = v_o_next;
         // rows 1..p of the previous candidate are this one's too: its key has the same first p
         // digits (equal links give equal rows), or its first p + 1 devices are the same
-        int p = 0, key = -1;
+        int p = 0;
+        const int key = key_next;
+        fetch(r + r_step, c_next, key_next, v_o_next);
         if (listed && r < nsorted) {
-            key = b.keys[c];
             if (prev_key >= 0) {
                 const bool differ = lane >= 1 && lane < S && (unsigned)key / pw != (unsigned)prev_key / pw;
                 const unsigned long long m = __ballot(differ);
@@ -255,7 +269,6 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
         }
         prev_key = key;
         // ordering: lane n holds device o[n]
-        const int v_o = lane < S ? a.ord[c * S + lane] : 0;
         bool bad = false;
         if (a.validate) {
             bad = lane < S && (v_o < 0 || v_o >= D);
