@@ -41,7 +41,10 @@ struct pp_ws_header {
     // share_sorted != 0 (only when share_active == 0): the list holds all N candidates ordered
     // by their first share_kdev devices, so that neighbours share the first share_kdev - 1 rows
     unsigned share_sorted, share_kdev;
-    unsigned pad0[56];
+    // share_active: the sorted representatives are cut into share_nchunks runs of about equal
+    // work (rows to compute); run w is entries start[w] .. start[w + 1] - 1 of the list
+    unsigned share_nchunks;
+    unsigned pad0[55];
     // byte 1024: work the partition DP actually did in this call, in 64 records of 128 bytes
     // (atomics that hit one cache line are served one after another, so every record has a
     // line of its own): (cell, split) pairs evaluated (rows shared between candidates are
@@ -65,7 +68,7 @@ __device__ __forceinline__ void pp_count_work(pp_ws_header *hdr, unsigned long l
 struct pp_ws_layout {
     size_t hdr, p32, x32, xkt, xct, bfl, ord, arg, bounds, C, T, part, total;
     // candidates that share a DP (0 = not carved: see pp_share_possible)
-    size_t sh_hash, sh_rep, sh_table, sh_keys, sh_reps, sh_cnt, sh_rows;
+    size_t sh_hash, sh_rep, sh_table, sh_keys, sh_reps, sh_cnt, sh_start, sh_rows;
     long long sh_row_slots;  // DP rows (of pp_share_row_stride(L) keys) the area sh_rows holds
     int slots;  // resident workgroups of the generic DP kernel (one backtrack table each)
     int nt;     // 8-cell tiles per row of the register-tiled DP kernel, 0 if L is too large for it
@@ -86,9 +89,6 @@ static inline bool pp_share_possible(int L, int D, int64_t N) {
 #endif
 #ifndef PP_SHARE_ROW_BYTES
 #define PP_SHARE_ROW_BYTES ((size_t)64 << 20)
-#endif
-#ifndef PP_SHARE_MIN_CHUNK
-#define PP_SHARE_MIN_CHUNK 8
 #endif
 __host__ __device__ static inline int pp_share_row_stride(int L) { return 128 * ((L + 127) / 128) + 4; }
 // Entry r of the list of representatives (hdr as the share kernels left it).
@@ -116,7 +116,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
     w.C = off;      off += pp_align256((size_t)N * 8);
     w.T = off;      off += pp_align256((size_t)N * 8);
     w.part = off;   off += pp_align256((size_t)((N + 63) / 64) * 16 * PP_MAX_M_LIST);
-    w.sh_hash = w.sh_rep = w.sh_table = w.sh_keys = w.sh_reps = w.sh_cnt = w.sh_rows = 0;
+    w.sh_hash = w.sh_rep = w.sh_table = w.sh_keys = w.sh_reps = w.sh_cnt = w.sh_start = w.sh_rows = 0;
     w.sh_row_slots = 0;
     if (pp_share_possible(L, D, N)) {
         w.sh_hash = off;  off += pp_align256((size_t)D * D * 8);
@@ -125,6 +125,7 @@ static inline pp_ws_layout pp_layout(int L, int D, int S, int64_t N) {
         w.sh_keys = off;  off += pp_align256((size_t)N * 4);
         w.sh_reps = off;  off += pp_align256((size_t)N * 4);
         w.sh_cnt = off;   off += pp_align256((size_t)(PP_SHARE_TABLE / 256) * 4);
+        w.sh_start = off; off += pp_align256((size_t)(PP_DP_SLOTS + 2) * 4);
         // DP rows the waves keep for the next candidate of their runs: S - 1 rows each for up
         // to PP_SHARE_ROW_WAVES waves, at most 64 MiB (fewer rows per wave: more waves)
         const size_t row = (size_t)pp_share_row_stride(L) * 4;
@@ -187,8 +188,10 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
 // and nB of bounds_out per candidate) to the candidates it stands for.  Both do nothing when
 // the class sequences do not fit the table.  Only where lay.sh_table != 0.
 // fill_part != 0: also set the arg-min partials of the workspace (lay.part) to "none".
+// run_waves (1 .. PP_DP_SLOTS): the waves of the DP kernel that will walk the list of
+// representatives; the list is cut into at most that many runs of about equal work.
 int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, const int64_t *XB,
-                            const int32_t *ord, int validate, int fill_part, void *ws,
+                            const int32_t *ord, int validate, int fill_part, int run_waves, void *ws,
                             const pp_ws_layout &lay, hipStream_t st);
 // With nT > 0 also T_out [nT][N][tw] (the makespan kernel ran over the representatives as well).
 int pp_launch_share_scatter(int64_t N, int nC, int nB, int nT, int tw, int64_t *C_out,

@@ -402,11 +402,13 @@ int pp_launch_dp(int L, int D, int S, int64_t N, const int64_t *PF, const int64_
     if (!lay.sh_table) return pp_launch_dp_big(a, (int)waves, cus, NULL, st);
     // candidates whose links have the same channel times share one DP: the kernel walks the
     // representatives the preparation finds, and their results are copied to the others
-    int rc = pp_launch_share_prepare(L, D, S, N, XF, XB, a.ord, a.validate, keep_list, ws, lay, st);
+    const int run_waves = pp_dp_big_run_waves(pp_dp_big_waves(L, D, S, (int)waves, cus), S, lay.sh_row_slots);
+    int rc = pp_launch_share_prepare(L, D, S, N, XF, XB, a.ord, a.validate, keep_list, run_waves, ws, lay, st);
     if (rc) return rc;
     pp_share_list list;
     list.reps = (const int *)(base + lay.sh_reps);
     list.keys = (const int *)(base + lay.sh_keys);
+    list.start = (const int *)(base + lay.sh_start);
     list.rows = (int *)(base + lay.sh_rows);
     list.row_slots = lay.sh_row_slots;
     rc = pp_launch_dp_big(a, (int)waves, cus, &list, st);

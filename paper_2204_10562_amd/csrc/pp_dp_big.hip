@@ -38,7 +38,7 @@ struct dp_big_args {
     // group of candidates with the same DP, see pp_share.hip) instead of all candidates: every
     // wave a run of neighbours, which share their first links and so their first rows (keys:
     // the key of every candidate; rows: room for row_slots saved rows of Lp + 4 keys)
-    const int *reps, *keys;
+    const int *reps, *keys, *start;
     int *rows;
     long long row_slots;  // rows of Lp + 4 keys the area `rows` holds
     dp_args g;
@@ -211,53 +211,67 @@ __global__ __launch_bounds__(256) void k_dp_big(dp_big_args b) {
     // first kdev - 1) in its slice of the workspace.
     const bool listed = b.reps != NULL && a.hdr->share_active != 0;
     const bool sorted = b.reps != NULL && !listed && a.hdr->share_sorted != 0;
-    long long r_begin = wave, r_end = a.N, r_step = b.waves, nsorted = 0;
+    // main part: entries r_begin, r_begin + r_step, ... (n_main of them); then, where candidates
+    // share their DP, this wave's share of the candidates with a bad ordering that follow the
+    // sorted representatives in the list (n_tail entries t_begin, t_begin + waves, ...)
+    long long r_begin = wave, r_step = b.waves, nsorted = 0, t_begin = 0, n_tail = 0;
+    long long n_main = wave < a.N ? (a.N - wave + b.waves - 1) / b.waves : 0;
     unsigned pw = 1;  // lane n = 1..S-1: (classes)^(S-1-n), the weight of the key's digit n
     int keep_rows = 0;  // rows 1..keep_rows are saved
-    if (listed || sorted) {
-        const long long total = listed ? (long long)a.hdr->share_nreps : a.N;
-        nsorted = listed ? (long long)a.hdr->share_nsorted : a.N;
-        keep_rows = listed ? S - 2 : (int)a.hdr->share_kdev - 1;
+    if (listed) {
+        // runs of about equal work, cut by the preparation
+        const long long total = a.hdr->share_nreps, nch = a.hdr->share_nchunks;
+        nsorted = a.hdr->share_nsorted;
+        keep_rows = S - 2 > 0 ? S - 2 : 0;
+        r_begin = wave < nch ? b.start[wave] : 0;
+        n_main = wave < nch ? b.start[wave + 1] - r_begin : 0;
+        r_step = 1;
+        t_begin = nsorted + wave;
+        n_tail = t_begin < total ? (total - t_begin + b.waves - 1) / b.waves : 0;
+        const unsigned nc = a.hdr->share_nc;
+        for (int n = lane + 1; n < S; ++n) pw *= nc;
+    } else if (sorted) {
+        nsorted = a.N;
+        keep_rows = (int)a.hdr->share_kdev - 1;
         keep_rows = keep_rows < S - 2 ? keep_rows : S - 2;
         keep_rows = keep_rows > 0 ? keep_rows : 0;
         long long nw = b.row_slots / (keep_rows > 0 ? keep_rows : 1);  // waves whose rows fit the area
         nw = nw < b.waves ? nw : b.waves;
         nw = nw > 1 ? nw : 1;
-        long long chunk = (total + nw - 1) / nw;
-        if (listed && chunk < PP_SHARE_MIN_CHUNK) chunk = PP_SHARE_MIN_CHUNK;
+        const long long chunk = (a.N + nw - 1) / nw;
         r_begin = wave * chunk;
-        r_end = r_begin + chunk < total ? r_begin + chunk : total;
+        n_main = r_begin < a.N ? (r_begin + chunk < a.N ? chunk : a.N - r_begin) : 0;
         r_step = 1;
-        if (listed) {
-            const unsigned nc = a.hdr->share_nc;
-            for (int n = lane + 1; n < S; ++n) pw *= nc;
-        }
     }
+    const long long n_items = n_main + n_tail;
+    auto entry = [&](long long i) { return i < n_main ? r_begin + i * r_step : t_begin + (i - n_main) * b.waves; };
     // (row n >= 1 of this wave's slice at save + (n - 1) RS)
-    int *save = b.rows + (size_t)((listed || sorted) ? wave : 0) * keep_rows * RS;
+    int *save = b.rows + (size_t)((listed || sorted) && n_main ? wave : 0) * keep_rows * RS;
     int prev_key = -1, prev_o = -1;
     int v_tops = 0;  // lane n keeps W[n][L] (with its split index) for the stage-count search
     int *cur = bufA, *nxt = bufB;
     // A candidate's index, key and devices come from memory through a chain of loads (list
     // entry, then key and ordering): they are fetched one candidate ahead.
-    auto fetch = [&](long long r, long long &c, int &key, int &v_o) {
+    auto fetch = [&](long long i, long long &c, int &key, int &v_o) {
         c = 0; key = -1; v_o = 0;
-        if (r >= r_end) return;
+        if (i >= n_items) return;
+        const long long r = entry(i);
         c = (listed || sorted) ? pp_share_at(a.hdr, b.reps, a.N, r) : r;
         if (listed && r < nsorted) key = b.keys[c];
         v_o = lane < S ? a.ord[c * S + lane] : 0;
     };
     long long c_next;
     int key_next, v_o_next;
-    fetch(r_begin, c_next, key_next, v_o_next);
-    for (long long r = r_begin; r < r_end; r += r_step) {
+    fetch(0, c_next, key_next, v_o_next);
+    for (long long i = 0; i < n_items; ++i) {
+        const long long r = entry(i);
         const long long c = c_next;
         const int v_o = v_o_next;
         // rows 1..p of the previous candidate are this one's too: its key has the same first p
         // digits (equal links give equal rows), or its first p + 1 devices are the same
         int p = 0;
         const int key = key_next;
-        fetch(r + r_step, c_next, key_next, v_o_next);
+        fetch(i + 1, c_next, key_next, v_o_next);
         if (listed && r < nsorted) {
             if (prev_key >= 0) {
                 const bool differ = lane >= 1 && lane < S && (unsigned)key / pw != (unsigned)prev_key / pw;
@@ -422,34 +436,50 @@ static int launch_big(const dp_big_args &b, int grid, int wpb, size_t lds, hipSt
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 
-int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_list *list,
-                     hipStream_t st) {
-    dp_big_args b;
-    b.g = g;
-    b.reps = list ? list->reps : NULL;
-    b.keys = list ? list->keys : NULL;
-    b.rows = list ? list->rows : NULL;
-    b.row_slots = list ? list->row_slots : 0;
-    b.NI = (g.L + 127) / 128;
-    const int Lp = 128 * b.NI, RS = Lp + 4;
-    b.arg_stride = (size_t)g.S * Lp;
-    const int ntl = (g.L - 128 * (b.NI - 1) + 7) / 8;
-    int wpb = 4;  // waves per workgroup: table + two rows per wave within 64 KiB of LDS
+// LDS of a workgroup and waves per workgroup for this shape (0 if it does not fit).
+static size_t big_lds(int L, int D, int S, int &wpb) {
+    const int Lp = 128 * ((L + 127) / 128), RS = Lp + 4;
+    wpb = 4;  // waves per workgroup: table + two rows per wave within 64 KiB of LDS
     while (wpb > 1 && (size_t)(1 + 2 * wpb) * RS * 4 > 64 * 1024) wpb >>= 1;
     size_t lds = (size_t)(1 + 2 * wpb) * RS * 4;
-    const size_t generic = (size_t)3 * (g.L + 1) * 8;  // the int64 fallback's rows
+    const size_t generic = (size_t)3 * (L + 1) * 8;  // the int64 fallback's rows
     if (lds < generic) lds = generic;
-    const size_t flat = pp_flat_lds_wanted(g.L, g.D, g.S, wpb);  // the closed-form body's tables
+    const size_t flat = pp_flat_lds_wanted(L, D, S, wpb);  // the closed-form body's tables
     if (lds < flat) lds = flat;
-    if (lds > 64 * 1024) return PP_ERR_INVALID_ARG;
-    b.g.lds_bytes = lds;
+    return lds > 64 * 1024 ? 0 : lds;
+}
+
+int pp_dp_big_waves(int L, int D, int S, int max_waves, int cus) {
+    int wpb;
+    const size_t lds = big_lds(L, D, S, wpb);
+    if (!lds) return 1;
     // resident waves: 4 per SIMD by registers, and what 160 KiB of LDS per CU allow
     long long per_cu = (long long)(160 * 1024 / lds) * wpb;
     if (per_cu > 16) per_cu = 16;
     if (per_cu < 1) per_cu = 1;
     long long waves = per_cu * cus;
     if (waves > max_waves) waves = max_waves;
-    if (waves < 1) waves = 1;
+    return (int)(waves < 1 ? 1 : waves);
+}
+
+int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_list *list,
+                     hipStream_t st) {
+    dp_big_args b;
+    b.g = g;
+    b.reps = list ? list->reps : NULL;
+    b.keys = list ? list->keys : NULL;
+    b.start = list ? list->start : NULL;
+    b.rows = list ? list->rows : NULL;
+    b.row_slots = list ? list->row_slots : 0;
+    b.NI = (g.L + 127) / 128;
+    const int Lp = 128 * b.NI, RS = Lp + 4;
+    b.arg_stride = (size_t)g.S * Lp;
+    const int ntl = (g.L - 128 * (b.NI - 1) + 7) / 8;
+    int wpb;
+    const size_t lds = big_lds(g.L, g.D, g.S, wpb);
+    if (!lds) return PP_ERR_INVALID_ARG;
+    b.g.lds_bytes = lds;
+    const long long waves = pp_dp_big_waves(g.L, g.D, g.S, max_waves, cus);
     b.waves = (int)waves;
     const int grid = (int)((waves + wpb - 1) / wpb);
     b.g.nblocks = g.nblocks < grid ? g.nblocks : grid;

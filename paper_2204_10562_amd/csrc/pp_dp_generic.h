@@ -41,12 +41,20 @@ struct dp_args {
 // list: what pp_launch_share_prepare leaves in the workspace (representatives, every
 // candidate's key, room for saved rows), or NULL.
 struct pp_share_list {
-    const int *reps, *keys;
+    const int *reps, *keys, *start;
     int *rows;
     long long row_slots;  // rows of (128 ceil(L / 128) + 4) keys that fit the area
 };
 int pp_launch_dp_big(const dp_args &g, int max_waves, int cus, const pp_share_list *list,
                      hipStream_t st);
+// The waves pp_launch_dp_big will use for this shape, and how many of them can walk the list of
+// representatives (each needs room for S - 2 saved rows).
+int pp_dp_big_waves(int L, int D, int S, int max_waves, int cus);
+static inline int pp_dp_big_run_waves(int waves, int S, long long row_slots) {
+    long long nw = row_slots / (S > 3 ? S - 2 : 1);
+    nw = nw < waves ? nw : waves;
+    return (int)(nw > 1 ? nw : 1);
+}
 
 // Loads candidate c's ordering into s_o[0..S-1]; returns false (uniformly) if it is not a
 // list of distinct devices below D.  Must be called by the whole workgroup.

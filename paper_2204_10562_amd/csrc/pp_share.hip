@@ -16,7 +16,9 @@
 //                       significant), and the lowest candidate of every key is kept with an
 //                       atomic min (only if nc^(S-1) fits the table);
 //   4. k_share_count, k_share_reps   the table compacted, in the order of the keys, into the
-//                       list of representatives.
+//                       list of representatives;
+//   5. k_share_cost, k_share_bounds  the list cut into runs of about equal work, one per wave
+//                       of the DP kernel.
 // The DP kernel walks the list - neighbours in it share their first links and with them the
 // first rows of the table - and k_share_scatter hands every representative's results to the
 // candidates of its key.  Candidates with a bad ordering are representatives of themselves
@@ -43,6 +45,8 @@ struct share_args {
     int *keys;                  // [N] key of every candidate (-1: bad ordering)
     int *reps;                  // [N] representatives (see pp_share_at)
     int *cnt;                   // [PP_SHARE_TABLE / 256] keys in use per 256 table entries
+    int *start;                 // [run_waves + 1] first list entry of every run
+    int run_waves;
     // arg-min partials to preset (pairs of int64), or NULL
     long long *part;
     long long n_part;
@@ -82,6 +86,7 @@ __global__ __launch_bounds__(256) void k_share_hash(share_args a) {
         a.hdr->share_nbad = 0;
         a.hdr->share_sorted = 0;
         a.hdr->share_kdev = 0;
+        a.hdr->share_nchunks = 0;
     }
     const int i = blockIdx.x * 4 + (tid >> 6);
     if (i >= nl) return;
@@ -305,6 +310,85 @@ __global__ __launch_bounds__(256) void k_share_reps(share_args a) {
     if (has) a.reps[at] = c;
 }
 
+// Work of representative r of the sorted list when it follows r - 1 in a run: the rows its key
+// does not share with its predecessor's (at least the last one), plus one row's worth for what
+// a candidate costs besides its rows.  A run's first entry computes all S - 1 rows.
+__device__ __forceinline__ int share_cost(const share_args &a, long long r) {
+    const int S = a.S;
+    if (r == 0 || S < 3) return S;
+    const unsigned key = (unsigned)a.keys[a.reps[r]], prev = (unsigned)a.keys[a.reps[r - 1]];
+    const unsigned nc = a.hdr->share_nc;
+    unsigned pw = a.hdr->share_tsize / nc;  // weight of the first digit
+    int p = 0;
+    for (int n = 1; n < S - 1 && key / pw == prev / pw; ++n) { ++p; pw /= nc; }
+    return S - p;
+}
+
+// Sum of share_cost over every 256 entries of the sorted list (cnt is free again by now).
+__global__ __launch_bounds__(256) void k_share_cost(share_args a) {
+    __shared__ int sh[4];
+    if (!a.hdr->share_active) return;
+    const long long r = (long long)blockIdx.x * 256 + threadIdx.x;
+    int c = r < (long long)a.hdr->share_nsorted ? share_cost(a, r) : 0;
+    for (int off = 32; off; off >>= 1) c += __shfl_xor(c, off);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) a.cnt[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// Cuts the sorted list into runs of about total / run_waves work each (never less than S + 1, so
+// that the running sum crosses at most one boundary per entry): start[w] = first entry of run w.
+__global__ __launch_bounds__(256) void k_share_bounds(share_args a) {
+    __shared__ long long sh[4], s_excl[256];
+    if (!a.hdr->share_active) return;
+    const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+    const long long ns = a.hdr->share_nsorted;
+    if (ns == 0) {
+        if (blockIdx.x == 0 && tid == 0) { a.hdr->share_nchunks = 0; a.start[0] = 0; }
+        return;
+    }
+    if ((long long)blockIdx.x * 256 >= ns) return;
+    // work before this block, and in all
+    const int nblk = (int)((ns + 255) / 256);
+    long long before = 0, total = 0;
+    for (int i = tid; i < nblk; i += 256) {
+        const int v = a.cnt[i];
+        total += v;
+        before += i < (int)blockIdx.x ? v : 0;
+    }
+    for (int off = 32; off; off >>= 1) { before += __shfl_xor(before, off); total += __shfl_xor(total, off); }
+    if (lane == 0) { sh[wib] = before; s_excl[wib] = total; }
+    __syncthreads();
+    before = sh[0] + sh[1] + sh[2] + sh[3];
+    total = s_excl[0] + s_excl[1] + s_excl[2] + s_excl[3];
+    __syncthreads();
+    long long quota = (total + a.run_waves - 1) / a.run_waves;
+    quota = quota > a.S + 1 ? quota : a.S + 1;
+    const long long r = (long long)blockIdx.x * 256 + tid;
+    const int c = r < ns ? share_cost(a, r) : 0;
+    long long incl = c;
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long o = __shfl_up(incl, off);
+        incl += lane >= off ? o : 0;
+    }
+    if (lane == 63) sh[wib] = incl;
+    __syncthreads();
+    long long excl = before + incl - c;
+    for (int w = 0; w < wib; ++w) excl += sh[w];
+    s_excl[tid] = excl;
+    __syncthreads();
+    if (r >= ns) return;
+    const long long id = excl / quota;
+    long long id_prev = -1;
+    if (tid) id_prev = s_excl[tid - 1] / quota;
+    else if (r) id_prev = (excl - share_cost(a, r - 1)) / quota;
+    if (id != id_prev) a.start[id] = (int)r;
+    if (r == ns - 1) {
+        a.start[id + 1] = (int)ns;
+        a.hdr->share_nchunks = (unsigned)(id + 1);
+    }
+}
+
 // Counting sort, last step: every candidate takes the next free position of its bucket.
 __global__ __launch_bounds__(256) void k_share_place(share_args a) {
     if (!a.hdr->share_sorted) return;
@@ -344,6 +428,7 @@ static share_args share_base(void *ws, const pp_ws_layout &lay) {
     a.keys = (int *)(base + lay.sh_keys);
     a.reps = (int *)(base + lay.sh_reps);
     a.cnt = (int *)(base + lay.sh_cnt);
+    a.start = (int *)(base + lay.sh_start);
     return a;
 }
 
@@ -353,9 +438,9 @@ static long long share_grid(int64_t N) {
 }
 
 int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, const int64_t *XB,
-                            const int32_t *ord, int validate, int fill_part, void *ws,
+                            const int32_t *ord, int validate, int fill_part, int run_waves, void *ws,
                             const pp_ws_layout &lay, hipStream_t st) {
-    if (!lay.sh_table) return PP_ERR_INVALID_ARG;
+    if (!lay.sh_table || run_waves < 1 || run_waves > PP_DP_SLOTS) return PP_ERR_INVALID_ARG;
     share_args a = share_base(ws, lay);
     if (fill_part) {
         a.part = (long long *)((char *)ws + lay.part);
@@ -364,6 +449,7 @@ int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, c
     a.L = L; a.D = D; a.S = S; a.N = N; a.validate = validate;
     a.XF = (const long long *)XF; a.XB = (const long long *)XB;
     a.ord = ord;
+    a.run_waves = run_waves;
     const int link_blocks = (D * D + 3) / 4;
     hipLaunchKernelGGL(k_share_hash, dim3(link_blocks + SHARE_FILL_BLOCKS), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_classes, dim3(link_blocks), dim3(256), 0, st, a);
@@ -371,6 +457,8 @@ int pp_launch_share_prepare(int L, int D, int S, int64_t N, const int64_t *XF, c
     hipLaunchKernelGGL(k_share_count, dim3(PP_SHARE_TABLE / 256), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_reps, dim3(PP_SHARE_TABLE / 256), dim3(256), 0, st, a);
     hipLaunchKernelGGL(k_share_place, dim3((unsigned)share_grid(N)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_share_cost, dim3((unsigned)share_grid(N)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_share_bounds, dim3((unsigned)share_grid(N)), dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? PP_OK : PP_ERR_HIP;
 }
 

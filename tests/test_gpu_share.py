@@ -75,7 +75,7 @@ def check_shared(ppo, g, w, tables, expect_active=True):
         # prefix of a key is computed once, at worst every row of every key
         prefixes = len({k[:n] for k in keys for n in range(1, w.S)})
         assert prefixes <= stats["rows_executed"] <= len(set(keys)) * (w.S - 1)
-        if len(set(keys)) <= 8:  # one run of one wave
+        if len(set(keys)) == 1:
             assert stats["rows_executed"] == prefixes
     else:
         # every candidate is computed, in the order of its first k devices; those with the same
