@@ -386,7 +386,10 @@ def main():
                    "GB_per_s": prefix_bytes / t_prefix["mean"] / 1e9, "hbm_peak_GB_per_s": 8000},
         "makespan": {"per_M": [{"M": M, "us": t_mk[M]["mean"] * 1e6, "block_ops_per_s": N * M * (4 * S - 3) / t_mk[M]["mean"]} for M in Ms],
                      "all_M_one_launch_block_ops_per_s": block_ops / t_mkm["mean"]},
-        "roofline": {"bound": "alu", "kernel": "pp_schedule_makespan_multi (the makespan launch of the step: all %d microbatch counts)" % len(Ms),
+        "roofline": {"bound": "alu", "kernel": ("pp_schedule_makespan_multi (the makespan launch of the step: all %d microbatch counts)" % len(Ms)
+                                               if not (L > 128 and stats["share_active"]) else
+                                               "pp_schedule_makespan_multi over all %d candidates, stand-alone (inside the step only the "
+                                               "%d representatives are scheduled)" % (N, stats["share_computed"])),
                      "achieved": achieved / 1e12, "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s (32-bit integer lane-ops)",
                      "frac": achieved / ALU_PEAK_OPS, "traffic": figures.get("makespan.traffic_bytes_per_launch"),
                      "launch": us(t_mkm), "launch_us": t_mkm["mean"] * 1e6, "block_ops_per_launch": block_ops,
